@@ -1,0 +1,87 @@
+"""SpaCO chunk selection, compensation factor and per-call chunk weights (oracle).
+
+TEST INFRASTRUCTURE ONLY (see the package docstring).
+
+Alg. 2 draws "t distinct indices" out of the k chunks but names no generator.
+This build fixes one so that the host library and this oracle can be compared
+bit for bit:
+
+  * integer stream: SplitMix64 (Steele, Lea, Flood 2014; Vigna's public-domain
+    reference): state += 0x9E3779B97F4A7C15, output = finaliser(state);
+  * stream key for (seed, step): state0 = finaliser(seed ^ finaliser(step + GOLDEN));
+  * bounded draw in [0, m): rejection sampling, accept u < floor(2^64 / m) * m,
+    return u mod m (so every residue is exactly equally likely);
+  * t of k without replacement: the first t steps of a Fisher-Yates shuffle of
+    0 .. k-1 (position i swaps with i + draw(k - i));
+  * output sorted in descending order, which is the order in which the chunks
+    must be back-propagated (reverse order, as in Alg. 1's second loop).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+_MASK = (1 << 64) - 1
+_GOLDEN = 0x9E3779B97F4A7C15
+
+
+def _finalise(z):
+    z &= _MASK
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK
+    return z ^ (z >> 31)
+
+
+class SplitMix64:
+    """The SplitMix64 stream started from a given 64-bit state."""
+
+    def __init__(self, state):
+        self.state = state & _MASK
+
+    def next(self):
+        self.state = (self.state + _GOLDEN) & _MASK
+        return _finalise(self.state)
+
+    def below(self, m):
+        """Uniform integer in [0, m) by rejection."""
+        limit = ((1 << 64) // m) * m
+        while True:
+            u = self.next()
+            if u < limit:
+                return u % m
+
+
+def stream_for(seed, step):
+    return SplitMix64(_finalise((seed & _MASK) ^ _finalise((step + _GOLDEN) & _MASK)))
+
+
+def select_chunks(seed, step, k, t):
+    """Alg. 2, selection step: t distinct chunk indices of 0..k-1, descending."""
+    if not (1 <= t <= k):
+        raise ValueError("need 1 <= t <= k")
+    rng = stream_for(seed, step)
+    perm = list(range(k))
+    for i in range(t):
+        r = i + rng.below(k - i)
+        perm[i], perm[r] = perm[r], perm[i]
+    return np.array(sorted(perm[:t], reverse=True), dtype=np.int32)
+
+
+def compensation_factor(k, t, cap=None):
+    """k/t (Sec. 5, "Compensation Factor"), optionally limited to `cap` (Sec. 6.4)."""
+    lam = k / t
+    return lam if cap is None else min(lam, cap)
+
+
+def chunk_weights(selected, j, factor):
+    """Weight vector w[0..j] of the backward call for chunk j.
+
+    w[i] = factor for an earlier selected chunk, w[j] = 1 for the chunk's own
+    rows, 0 for every chunk that is not selected (Alg. 2; appendix listing).
+    fp32, because that is the type the library's weight argument has.
+    """
+    w = np.zeros(j + 1, dtype=np.float32)
+    for i in selected:
+        if i < j:
+            w[int(i)] = factor
+    w[j] = 1.0
+    return w
