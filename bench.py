@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the chunk-wise attention hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic layer of the named workload:
+kvgrad_zero, then for every chunk in reverse order (Alg. 1, second loop) the forward of the
+chunk against the cache and its backward (delta, dQ, dK/dV accumulated into gK/gV), one call
+per chunk, in the method's order, on one stream.  Inputs are resident in HBM before timing.
+
+Prints ONE JSON line: whole-job TFLOP/s (algorithmic FLOPs: 4*D per visible (row, col) pair
+forward, 10*D backward), the roofline of the dominant kernel measured with HIP events around
+every launch of the timed region, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak (published)
+
+
+def pairs(j, C):
+    """visible (row, col) pairs per head in the call for chunk j"""
+    return C * j * C + C * (C + 1) // 2
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-layer32k", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU by design (one process, one MI355X); run with --gpus 1")
+
+    import torch
+    import paper_2505_16710_amd as seco
+    from workloads import CONFIGS
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    seco.load_library()
+    dev = "cuda:0"
+    cfg = CONFIGS[args.config]
+    B, Hq, Hkv, D, N, C = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.seq_len, cfg.chunk_len
+    k_chunks = cfg.n_chunks
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    scale = cfg.scale
+
+    def make_inputs(N):
+        gen = torch.Generator(device=dev).manual_seed(cfg.seed)
+        mk = lambda h: torch.randn(B, h, N, D, generator=gen, device=dev, dtype=torch.float32).to(tdt)
+        return mk(Hq), mk(Hkv), mk(Hkv), mk(Hq)
+
+    class Layer:
+        """Device buffers of one layer; O is kept whole so that O and dO chunk views share strides."""
+
+        def __init__(self, N, C):
+            self.N, self.C, self.k = N, C, N // C
+            self.q, self.kc, self.vc, self.do = make_inputs(N)
+            self.o = torch.empty_like(self.q)
+            self.lse = torch.empty(B, Hq, C, device=dev, dtype=torch.float32)
+            self.dq = torch.empty_like(self.q)
+            self.gk = torch.empty(B, Hkv, N, D, device=dev, dtype=torch.float32)
+            self.gv = torch.empty_like(self.gk)
+            self.ws = torch.empty(max(B * Hq * C * 4, 256), device=dev, dtype=torch.uint8)
+
+        def rows(self, t, j):
+            return t[:, :, j * self.C:(j + 1) * self.C]
+
+        def fwd(self, j):
+            seco.seco_chunk_attn_fwd(self.rows(self.q, j), self.kc, self.vc, j * self.C, scale,
+                                     o=self.rows(self.o, j), lse=self.lse)
+
+        def bwd(self, j, weights=None):
+            args = (self.rows(self.q, j), self.kc, self.vc, self.rows(self.o, j), self.lse, self.rows(self.do, j),
+                    self.gk, self.gv, j * self.C, scale)
+            if weights is None:
+                seco.seco_chunk_attn_bwd(*args, d_q=self.rows(self.dq, j), ws=self.ws)
+            else:
+                seco.spaco_chunk_attn_bwd(*args, weights, self.C, d_q=self.rows(self.dq, j), ws=self.ws)
+
+    L = Layer(N, C)
+
+    def step():
+        seco.kvgrad_zero(L.gk, L.gv)
+        for j in range(k_chunks - 1, -1, -1):
+            L.fwd(j)
+            L.bwd(j)
+
+    per_pair = D * Hq * B
+    flops_fwd = sum(4 * pairs(j, C) for j in range(k_chunks)) * per_pair
+    flops_dq = sum(6 * pairs(j, C) for j in range(k_chunks)) * per_pair
+    flops_dkdv = sum(4 * pairs(j, C) for j in range(k_chunks)) * per_pair
+    flops_step = flops_fwd + flops_dq + flops_dkdv
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if not args.no_profile:
+        seco.seco_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = None
+    if not args.no_profile:
+        prof = seco.seco_profile_read()
+        seco.seco_profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    out = {
+        "metric": "chunk_attn_fwd_bwd_tflops", "value": round(tflops, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: SeCO fwd+bwd, one call pair per chunk, full gK/gV accumulation",
+                   "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "seq_len": N, "chunk_len": C,
+                   "n_chunks": k_chunks, "flops_per_step": flops_step},
+        "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
+    }
+
+    if prof is not None:
+        alg = {"fwd": flops_fwd, "dq": flops_dq, "dkdv": flops_dkdv}
+        kern = {}
+        for kind, (ms, n) in prof.items():
+            if n:
+                kern[kind] = {"launches": int(n), "avg_ms": round(ms / n, 5), "total_ms_per_step": round(ms / args.steps, 4)}
+                if kind in alg:
+                    kern[kind]["tflops"] = round(alg[kind] * args.steps / (ms * 1e-3) / 1e12, 2)
+        dom = max(alg, key=lambda kd: prof[kd][0])
+        ms, n = prof[dom]
+        achieved = alg[dom] * args.steps / (ms * 1e-3) / 1e12
+        out["roofline"] = {"bound": "mfma", "kernel": dom + "_bf16_kernel" if cfg.dtype == "bf16" else dom + "_f32_kernel",
+                           "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                           "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                           "avg_launch_ms": round(ms / n, 5), "launches": int(n)}
+        out["kernels"] = kern
+
+    if not args.no_layer32k and cfg.dtype == "bf16":
+        # seconds per 32K-token layer under the two schedules (Alg. 1: 2 fwd + bwd per chunk;
+        # Alg. 2: k fwd, then fwd + bwd for the t selected chunks), 16 chunks of 2048, t = 4
+        del L
+        torch.cuda.empty_cache()
+        c3 = CONFIGS["cfg3"]
+        L3 = Layer(c3.seq_len, c3.chunk_len)
+        k3, t3 = c3.n_chunks, c3.spaco_t
+        sel = seco.spaco_select_chunks(c3.seed, 0, k3, t3)
+        lam = k3 / t3
+
+        def seco_layer():
+            for j in range(k3):
+                L3.fwd(j)
+            seco.kvgrad_zero(L3.gk, L3.gv)
+            for j in range(k3 - 1, -1, -1):
+                L3.fwd(j)
+                L3.bwd(j)
+
+        def spaco_layer():
+            for j in range(k3):
+                L3.fwd(j)
+            seco.kvgrad_zero(L3.gk, L3.gv)
+            for j in sel:
+                L3.fwd(j)
+                L3.bwd(j, seco.spaco_chunk_weights(sel, j, lam))
+
+        res = {}
+        for name, fn in (("seco", seco_layer), ("spaco_t4", spaco_layer)):
+            fn()
+            torch.cuda.synchronize()
+            best = 1e9
+            for _ in range(3):
+                a = time.perf_counter()
+                fn()
+                torch.cuda.synchronize()
+                best = min(best, time.perf_counter() - a)
+            res[name] = round(best, 5)
+        res["selected_chunks"] = sel
+        out["sec_per_32k_layer"] = res
+        del L3
+
+    if not args.no_cpu_baseline:
+        # the oracle, as it stands, on one independent (batch, KV head) unit of the same workload
+        from oracle import attention as A
+        from workloads import kv_group
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max((p.get("num_threads", 1) for p in threadpool_info()), default=1)
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        grp = kv_group(cfg, 0, 0)
+        q = grp["q"][None].astype(np.float64)
+        do = grp["do"][None].astype(np.float64)
+        kk = grp["k"][None, None].astype(np.float64)
+        vv = grp["v"][None, None].astype(np.float64)
+        n_time = min(k_chunks, 16)
+        chunks = list(range(k_chunks - 1, k_chunks - 1 - n_time, -1))
+        a = time.perf_counter()
+        done = 0
+        fl = 0
+        for j in chunks:
+            qs = q[:, :, j * C:(j + 1) * C]
+            o_j, lse_j = A.chunk_attn_fwd(qs, kk, vv, j * C, scale)
+            A.chunk_attn_bwd(qs, kk, vv, o_j, lse_j, do[:, :, j * C:(j + 1) * C], j * C, scale)
+            done += 1
+            fl += 14 * pairs(j, C) * D * (Hq // Hkv)
+            if time.perf_counter() - a > 25:
+                break
+        el = time.perf_counter() - a
+        out["cpu_baseline"] = {"value": round(fl / el / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"fp64 NumPy oracle, fwd+bwd of the last {done} chunk calls of one (batch, KV head) "
+                                         f"unit of {cfg.name} ({Hq // Hkv} query heads), {el:.1f} s",
+                               "host_cores_available": len(os.sched_getaffinity(0))}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

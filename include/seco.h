@@ -1,0 +1,189 @@
+/*
+ * seco.h - C ABI of the chunk-wise attention library for AMD MI355X (gfx950).
+ *
+ * The library implements the attention-layer hot path of Sequential / Sparse
+ * Chunk-wise Optimization (SeCO, Alg. 1; SpaCO, Alg. 2 of the paper):
+ *
+ *   - a sequence is processed in chunks; chunk j's queries see the K/V cache
+ *     rows of every earlier chunk plus a causal block over the chunk itself
+ *     (Eq. 1 at the attention layer);
+ *   - the backward of a chunk returns dQ for that chunk and ADDS its dK/dV
+ *     into a persistent fp32 gradient buffer that spans the whole cache (the
+ *     ".grad" of the paper's checkpoints m'_i, Alg. 1 second loop);
+ *   - SpaCO back-propagates only selected chunks and scales what a call
+ *     deposits on earlier selected chunks by the compensation factor k/t
+ *     (Sec. 5 "Compensation Factor", Alg. 2).
+ *
+ * Conventions
+ *   - All tensor pointers are DEVICE pointers unless a name ends in _host.
+ *   - Layout: [batch, head, row, head_dim]; head_dim is contiguous; the three
+ *     outer strides are given explicitly, in ELEMENTS.  Every row must start on
+ *     a 16-byte boundary (base pointer and strides).
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - The caller owns every buffer and the stream.  Entry points validate,
+ *     enqueue kernels on `hip_stream` (a hipStream_t, may be NULL for the
+ *     default stream) and return without synchronising.  They allocate no
+ *     device memory and keep no state between calls (the optional profiler
+ *     at the end of this header aside).
+ *   - Return value: SECO_OK (0) or a negative seco_status.  On a validation
+ *     error nothing is enqueued and no output is touched.
+ *   - Results are deterministic: no floating-point atomics are used anywhere;
+ *     every gK/gV tile has exactly one owner workgroup per call.
+ */
+#ifndef SECO_H_
+#define SECO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum seco_dtype {
+  SECO_F32 = 0,  /* Q,K,V,O,dO,dQ are float; arithmetic in fp32 */
+  SECO_BF16 = 1  /* Q,K,V,O,dO,dQ are bfloat16; bf16 matrix-core products, fp32 accumulation/softmax */
+} seco_dtype;
+
+typedef enum seco_status {
+  SECO_OK = 0,
+  SECO_ERR_NULL = -1,        /* a required pointer is NULL */
+  SECO_ERR_SHAPE = -2,       /* non-positive size, n_q_heads % n_kv_heads != 0, negative q_start, softmax_scale not finite and > 0 */
+  SECO_ERR_HEAD_DIM = -3,    /* head_dim not supported for this dtype (bf16: 128; f32: multiple of 4, <= 256) */
+  SECO_ERR_DTYPE = -4,       /* dtype is not a seco_dtype */
+  SECO_ERR_ALIGN = -5,       /* pointer or stride breaks the 16-byte row alignment */
+  SECO_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than seco_workspace_bytes() */
+  SECO_ERR_WEIGHTS = -7,     /* chunk weights: n_chunks/weight_chunk_len do not cover [0, q_start + chunk_len), or a weight is not finite */
+  SECO_ERR_RANGE = -8,       /* row range or selection arguments out of range */
+  SECO_ERR_LAUNCH = -9,      /* the HIP runtime refused a launch (hipGetLastError) */
+  SECO_ERR_TOO_LARGE = -10   /* a size exceeds what the 32-bit tile indexing supports */
+} seco_status;
+
+typedef enum seco_op {
+  SECO_OP_FWD = 0,
+  SECO_OP_BWD = 1            /* seco_chunk_attn_bwd and spaco_chunk_attn_bwd */
+} seco_op;
+
+/* One chunk call.  kv_len = q_start + chunk_len cache rows are visible. */
+typedef struct seco_desc {
+  int32_t batch;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  int32_t chunk_len;      /* C: query rows in this call (the last chunk may be short) */
+  int32_t q_start;        /* global position of the chunk's first row (j*C for chunk j) */
+  int32_t dtype;          /* seco_dtype */
+  float softmax_scale;    /* s > 0, normally 1/sqrt(head_dim) */
+  int64_t q_stride[3];    /* Q and dQ  : (batch, head, row) strides in elements */
+  int64_t o_stride[3];    /* O and dO  */
+  int64_t kv_stride[3];   /* K and V cache (row index = global position) */
+  int64_t g_stride[3];    /* gK and gV, fp32 (row index = global position) */
+} seco_desc;
+
+/*
+ * Forward of one chunk (Eq. 1; Alg. 1 both loops call it).
+ *   S = s * Q K^T over cache rows [0, q_start + chunk_len), row r sees columns c <= q_start + r;
+ *   O = softmax_row(S) V;   LSE[r] = ln sum_c exp(S[r,c])  (natural log of the scaled scores).
+ * q        in   [B, Hq, C, D]   (q_stride)
+ * k_cache  in   [B, Hkv, >= q_start + C, D]   (kv_stride); v_cache alike
+ * o        out  [B, Hq, C, D]   (o_stride), overwritten
+ * lse      out  fp32 [B, Hq, C] contiguous, overwritten
+ * ws       workspace of seco_workspace_bytes(desc, SECO_OP_FWD) bytes (may be NULL when that is 0)
+ */
+int seco_chunk_attn_fwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                        void* o, float* lse, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Backward of one chunk for SeCO (Alg. 1, "backprop(J_i)" at the attention layer).
+ * With P = exp(S - LSE), delta = rowsum(dO * O), dS = P * (dO V^T - delta):
+ *   d_q  out  [B, Hq, C, D] (q_stride), overwritten:  dQ = s * dS K          (all visible columns)
+ *   gk   i/o  fp32 [B, Hkv, >= q_start + C, D] (g_stride): gK[c] += s * sum_{heads of group} dS^T Q
+ *   gv   i/o  same:                                        gV[c] += sum_{heads of group} P^T dO
+ * for every visible cache row c.  gk/gv are accumulated into, never overwritten; rows at or
+ * beyond q_start + C are not touched.  o, lse are the outputs of seco_chunk_attn_fwd for the
+ * same desc; d_o has o's layout.
+ * ws: seco_workspace_bytes(desc, SECO_OP_BWD) bytes, 256-byte aligned.
+ */
+int seco_chunk_attn_bwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                        const void* o, const float* lse, const void* d_o,
+                        void* d_q, float* gk, float* gv, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Backward of one selected chunk for SpaCO (Alg. 2; appendix listing "grad + base * scaler").
+ * Same as seco_chunk_attn_bwd except that the contribution to cache rows of chunk i,
+ * i.e. rows [i * weight_chunk_len, (i+1) * weight_chunk_len), is multiplied by
+ * chunk_weight_host[i] before it is added:  gK[c] += w[chunk(c)] * dK_c, gV likewise.
+ * Column tiles whose weight is exactly 0 are neither computed nor touched.  dQ is exact
+ * (all visible columns) whatever the weights.
+ *   chunk_weight_host  HOST array of n_chunks floats, read before the call returns
+ *   n_chunks * weight_chunk_len must be >= q_start + chunk_len  (and (n_chunks-1)*weight_chunk_len < that)
+ * The paper's policy: w = k/t (optionally capped, Sec. 6.4) for earlier selected chunks,
+ * 1 for the chunk's own rows, 0 for unselected chunks; see spaco_chunk_weights().
+ * With all weights 1 the result is bit-identical to seco_chunk_attn_bwd.
+ */
+int spaco_chunk_attn_bwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                         const void* o, const float* lse, const void* d_o,
+                         void* d_q, float* gk, float* gv,
+                         const float* chunk_weight_host, int32_t n_chunks, int32_t weight_chunk_len,
+                         void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Zero rows [row_begin, row_end) of the KV gradient buffers (start of a training iteration;
+ * the buffers then collect the contributions of Alg. 1's / Alg. 2's second loop).
+ * Uses batch, n_kv_heads, head_dim and g_stride of desc.  Either pointer may be NULL (skipped).
+ */
+int kvgrad_zero(const seco_desc* desc, float* gk, float* gv, int64_t row_begin, int64_t row_end, void* hip_stream);
+
+/*
+ * dst[rows] += scale * src[rows] on fp32 KV gradient buffers: the gradient relay of the
+ * appendix listing (grad_hook: grad + base * scaler) and of Alg. 2's "(k/t) * m'_i.grad".
+ * dst and src both use g_stride.  A NULL dst/src pair is skipped; dst must not alias src.
+ */
+int kvgrad_accumulate(const seco_desc* desc, float* dst_k, float* dst_v, const float* src_k, const float* src_v,
+                      float scale, int64_t row_begin, int64_t row_end, void* hip_stream);
+
+/*
+ * SpaCO chunk selection (Alg. 2: "randomly select t distinct indices"), host only.
+ * Deterministic in (seed, step): SplitMix64 stream keyed by (seed, step), unbiased bounded
+ * draws by rejection, first t steps of a Fisher-Yates shuffle of 0..k-1, result sorted in
+ * DESCENDING order (the order in which the chunks have to be back-propagated).
+ * out_host: HOST array of t int32.
+ */
+int spaco_select_chunks(uint64_t seed, uint64_t step, int32_t k, int32_t t, int32_t* out_host);
+
+/*
+ * Weight vector for the backward call of chunk j under the paper's policy, host only:
+ * w[i] = factor for i in selected, i < j;  w[j] = 1;  0 otherwise.
+ * factor is k/t (Sec. 5), optionally capped by the caller (Sec. 6.4).
+ * selected_host: n_selected chunk indices (any order); w_host: j + 1 floats, overwritten.
+ */
+int spaco_chunk_weights(const int32_t* selected_host, int32_t n_selected, int32_t j, float factor, float* w_host);
+
+/*
+ * Optional per-kernel timing, for benchmarks (not part of the method).  While enabled, every
+ * kernel the library launches is bracketed by a pair of HIP events recorded on the launch
+ * stream.  seco_profile_read waits for the recorded events, adds up elapsed milliseconds and
+ * launch counts per kernel kind (arrays of SECO_PROFILE_KINDS entries, host memory), and
+ * forgets them.  This is the only process-wide state the library has; it is not thread-safe.
+ */
+typedef enum seco_profile_kind {
+  SECO_PROFILE_FWD = 0,     /* forward kernel */
+  SECO_PROFILE_DELTA = 1,   /* delta = rowsum(dO * O) */
+  SECO_PROFILE_DQ = 2,      /* dQ kernel */
+  SECO_PROFILE_DKDV = 3,    /* dK/dV kernel with the gK/gV accumulation */
+  SECO_PROFILE_KVGRAD = 4,  /* kvgrad_zero / kvgrad_accumulate */
+  SECO_PROFILE_KINDS = 5
+} seco_profile_kind;
+int seco_profile_enable(int on);
+int seco_profile_read(double* total_ms_host, int64_t* launches_host);
+
+/* Workspace bytes an entry point needs for this desc (0 if none; (size_t)-1 on an invalid desc). */
+size_t seco_workspace_bytes(const seco_desc* desc, int op);
+
+/* Static English description of a status code. */
+const char* seco_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SECO_H_ */

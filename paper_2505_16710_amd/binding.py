@@ -1,0 +1,243 @@
+"""ctypes binding of include/seco.h: argument marshalling only.
+
+Tensor arguments are torch tensors on the GPU, laid out [batch, head, row, head_dim] with a
+contiguous last dimension (any outer strides).  The functions build the `seco_desc`, pass
+raw device pointers and the current HIP stream, and raise SecoError on a non-zero status.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libseco_hip.so")
+_lib = None
+
+SECO_F32, SECO_BF16 = 0, 1
+SECO_OP_FWD, SECO_OP_BWD = 0, 1
+
+
+class SecoDesc(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("chunk_len", C.c_int32), ("q_start", C.c_int32), ("dtype", C.c_int32), ("softmax_scale", C.c_float),
+        ("q_stride", C.c_int64 * 3), ("o_stride", C.c_int64 * 3),
+        ("kv_stride", C.c_int64 * 3), ("g_stride", C.c_int64 * 3),
+    ]
+
+
+class SecoError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {seco_strerror(status)} (status {status})")
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libseco_hip.so (built by paper_2505_16710_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} not found: run `python -m paper_2505_16710_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(_LIB_PATH)
+    vp, fp, i32, i64, sz = C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    dp = C.POINTER(SecoDesc)
+    lib.seco_chunk_attn_fwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, sz, vp]
+    lib.seco_chunk_attn_bwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp, fp, fp, vp, sz, vp]
+    lib.spaco_chunk_attn_bwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp, fp, fp,
+                                         C.POINTER(C.c_float), i32, i32, vp, sz, vp]
+    lib.kvgrad_zero.argtypes = [dp, fp, fp, i64, i64, vp]
+    lib.kvgrad_accumulate.argtypes = [dp, fp, fp, fp, fp, C.c_float, i64, i64, vp]
+    lib.spaco_select_chunks.argtypes = [C.c_uint64, C.c_uint64, i32, i32, C.POINTER(i32)]
+    lib.spaco_chunk_weights.argtypes = [C.POINTER(i32), i32, i32, C.c_float, C.POINTER(C.c_float)]
+    lib.seco_workspace_bytes.argtypes = [dp, C.c_int]
+    lib.seco_workspace_bytes.restype = sz
+    lib.seco_strerror.argtypes = [C.c_int]
+    lib.seco_strerror.restype = C.c_char_p
+    lib.seco_profile_enable.argtypes = [C.c_int]
+    lib.seco_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.seco_profile_enable.restype = lib.seco_profile_read.restype = C.c_int
+    for name in ("seco_chunk_attn_fwd", "seco_chunk_attn_bwd", "spaco_chunk_attn_bwd", "kvgrad_zero",
+                 "kvgrad_accumulate", "spaco_select_chunks", "spaco_chunk_weights"):
+        getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def seco_strerror(status):
+    return load_library().seco_strerror(int(status)).decode()
+
+
+def _check(status, where):
+    if status != 0:
+        raise SecoError(status, where)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return SECO_BF16
+    if t.dtype == torch.float32:
+        return SECO_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _strides3(t):
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError("expected a [batch, head, row, head_dim] tensor with contiguous head_dim")
+    return (C.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def make_desc(q, k_cache, q_start, scale, o=None, g=None):
+    """seco_desc for a chunk call; o defaults to q's strides, g to a contiguous fp32 cache."""
+    B, Hq, Cn, D = q.shape
+    d = SecoDesc()
+    d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = B, Hq, k_cache.shape[1], D
+    d.chunk_len, d.q_start, d.dtype, d.softmax_scale = Cn, int(q_start), _dtype_code(q), float(scale)
+    d.q_stride = _strides3(q)
+    d.o_stride = _strides3(o if o is not None else q)
+    d.kv_stride = _strides3(k_cache)
+    d.g_stride = _strides3(g) if g is not None else _strides3(k_cache)
+    return d
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def seco_workspace_bytes(desc, op):
+    n = load_library().seco_workspace_bytes(C.byref(desc), int(op))
+    if n == C.c_size_t(-1).value:
+        raise SecoError(-2, "seco_workspace_bytes")
+    return n
+
+
+def _workspace(desc, op, like):
+    import torch
+    n = seco_workspace_bytes(desc, op)
+    return (torch.empty(max(n, 256), dtype=torch.uint8, device=like.device), n)
+
+
+def seco_chunk_attn_fwd(q, k_cache, v_cache, q_start, scale, o=None, lse=None, stream=None):
+    """O, LSE of one chunk against cache rows [0, q_start + C).  Returns (o, lse)."""
+    import torch
+    lib = load_library()
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
+    d = make_desc(q, k_cache, q_start, scale, o=o)
+    _check(lib.seco_chunk_attn_fwd(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(o), _ptr(lse),
+                                   None, 0, _stream(stream)), "seco_chunk_attn_fwd")
+    return o, lse
+
+
+def seco_chunk_attn_bwd(q, k_cache, v_cache, o, lse, d_o, gk, gv, q_start, scale, d_q=None, ws=None, stream=None):
+    """dQ of the chunk; adds the chunk's dK/dV into gk, gv (fp32, whole cache).  Returns d_q."""
+    import torch
+    lib = load_library()
+    if d_q is None:
+        d_q = torch.empty_strided(q.size(), q.stride(), dtype=q.dtype, device=q.device)
+    if o.stride() != d_o.stride() or q.stride() != d_q.stride():
+        raise ValueError("o/d_o and q/d_q must share strides")
+    d = make_desc(q, k_cache, q_start, scale, o=o, g=gk)
+    if ws is None:
+        ws, _ = _workspace(d, SECO_OP_BWD, q)
+    _check(lib.seco_chunk_attn_bwd(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(o), _ptr(lse), _ptr(d_o),
+                                   _ptr(d_q), _ptr(gk), _ptr(gv), _ptr(ws), ws.numel() * ws.element_size(),
+                                   _stream(stream)), "seco_chunk_attn_bwd")
+    return d_q
+
+
+def spaco_chunk_attn_bwd(q, k_cache, v_cache, o, lse, d_o, gk, gv, q_start, scale, chunk_weight, weight_chunk_len,
+                         d_q=None, ws=None, stream=None):
+    """As seco_chunk_attn_bwd with per-chunk weights (host sequence of floats) on the dK/dV contributions."""
+    import torch
+    lib = load_library()
+    if d_q is None:
+        d_q = torch.empty_strided(q.size(), q.stride(), dtype=q.dtype, device=q.device)
+    if o.stride() != d_o.stride() or q.stride() != d_q.stride():
+        raise ValueError("o/d_o and q/d_q must share strides")
+    d = make_desc(q, k_cache, q_start, scale, o=o, g=gk)
+    if ws is None:
+        ws, _ = _workspace(d, SECO_OP_BWD, q)
+    n = len(chunk_weight)
+    w = (C.c_float * n)(*[float(x) for x in chunk_weight])
+    _check(lib.spaco_chunk_attn_bwd(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(o), _ptr(lse), _ptr(d_o),
+                                    _ptr(d_q), _ptr(gk), _ptr(gv), w, n, int(weight_chunk_len), _ptr(ws),
+                                    ws.numel() * ws.element_size(), _stream(stream)), "spaco_chunk_attn_bwd")
+    return d_q
+
+
+def _g_desc(g):
+    d = SecoDesc()
+    d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = g.shape[0], g.shape[1], g.shape[1], g.shape[3]
+    d.chunk_len, d.q_start, d.dtype, d.softmax_scale = 1, 0, SECO_F32, 1.0
+    d.q_stride = d.o_stride = d.kv_stride = d.g_stride = _strides3(g)
+    return d
+
+
+def kvgrad_zero(gk, gv, row_begin=0, row_end=None, stream=None):
+    """Zero rows [row_begin, row_end) of the fp32 KV-gradient buffers (either may be None)."""
+    ref = gk if gk is not None else gv
+    d = _g_desc(ref)
+    if row_end is None:
+        row_end = ref.shape[2]
+    _check(load_library().kvgrad_zero(C.byref(d), _ptr(gk), _ptr(gv), int(row_begin), int(row_end), _stream(stream)),
+           "kvgrad_zero")
+
+
+def kvgrad_accumulate(dst_k, dst_v, src_k, src_v, scale, row_begin=0, row_end=None, stream=None):
+    """dst[rows] += scale * src[rows] on fp32 KV-gradient buffers with identical strides."""
+    ref = dst_k if dst_k is not None else dst_v
+    d = _g_desc(ref)
+    if row_end is None:
+        row_end = ref.shape[2]
+    for a, b in ((dst_k, src_k), (dst_v, src_v)):
+        if a is not None and b is not None and a.stride() != b.stride():
+            raise ValueError("dst and src must share strides")
+    _check(load_library().kvgrad_accumulate(C.byref(d), _ptr(dst_k), _ptr(dst_v), _ptr(src_k), _ptr(src_v),
+                                            float(scale), int(row_begin), int(row_end), _stream(stream)),
+           "kvgrad_accumulate")
+
+
+def spaco_select_chunks(seed, step, k, t):
+    """t distinct chunk indices of 0..k-1, descending (list of int)."""
+    out = (C.c_int32 * max(int(t), 1))()
+    _check(load_library().spaco_select_chunks(int(seed), int(step), int(k), int(t), out), "spaco_select_chunks")
+    return list(out[:t])
+
+
+def spaco_chunk_weights(selected, j, factor):
+    """Weight vector w[0..j] of the backward call for chunk j (list of float)."""
+    sel = (C.c_int32 * max(len(selected), 1))(*[int(i) for i in selected])
+    w = (C.c_float * (int(j) + 1))()
+    _check(load_library().spaco_chunk_weights(sel, len(selected), int(j), float(factor), w), "spaco_chunk_weights")
+    return list(w)
+
+
+PROFILE_KINDS = ("fwd", "delta", "dq", "dkdv", "kvgrad")
+
+
+def seco_profile_enable(on=True):
+    _check(load_library().seco_profile_enable(1 if on else 0), "seco_profile_enable")
+
+
+def seco_profile_read():
+    """{kind: (total_ms, launches)} of the kernels launched since profiling was enabled / last read."""
+    ms = (C.c_double * len(PROFILE_KINDS))()
+    n = (C.c_int64 * len(PROFILE_KINDS))()
+    _check(load_library().seco_profile_read(ms, n), "seco_profile_read")
+    return {k: (ms[i], n[i]) for i, k in enumerate(PROFILE_KINDS)}

@@ -1,0 +1,152 @@
+// dQ of one chunk, bf16 matrix cores: dQ = s * dS K over ALL visible cache rows, with
+// P = exp(S - LSE), dS = P * (dO V^T - delta).  (SpaCO keeps dQ exact: a selected chunk's
+// graph is rebuilt against every earlier cache, Alg. 2.)
+//
+// Same row-parallel decomposition as the forward: a workgroup owns 128 query rows of one
+// head, a wavefront 32 of them, K and V tiles of 64 cache rows stream through swizzled,
+// double-buffered LDS.  Scores are again computed transposed (S^T = K Q^T, dP^T = V dO^T) so
+// that LSE and delta are per-lane scalars and dS^T feeds dQ^T += K^T dS^T from registers;
+// K^T comes from the same K tile through the LDS transpose read.
+#include "mfma_tiles.h"
+#include "seco_internal.h"
+
+namespace seco {
+namespace {
+
+constexpr int BM = 128;
+constexpr int BN = 64;
+constexpr int kTileBytes = BN * kRowBytes;
+
+__global__ __launch_bounds__(256, 2) void dq_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
+  __shared__ __attribute__((aligned(16))) char smem_raw[4 * kTileBytes];
+  lds_char* smem = (lds_char*)smem_raw;
+
+  const int item = xcd_item(blockIdx.x, total_items);
+  if (item < 0) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int hg = item % p.G;
+  int rest = item / p.G;
+  const int mt = n_mtiles - 1 - rest % n_mtiles;
+  rest /= n_mtiles;
+  const int kvh = rest % p.Hkv, b = rest / p.Hkv;
+  const int h = kvh * p.G + hg;
+
+  const int kv_len = p.q_start + p.C;
+  const int m0 = mt * BM + wave * 32;
+  const int row = m0 + l32;
+  const int crow = min(row, p.C - 1);
+  const int qpos = p.q_start + row;
+  const __bf16* qptr = static_cast<const __bf16*>(p.q) + b * p.qs[0] + h * p.qs[1] + (int64_t)crow * p.qs[2];
+  const __bf16* doptr = static_cast<const __bf16*>(p.d_o) + b * p.os[0] + h * p.os[1] + (int64_t)crow * p.os[2];
+  bf16x8 qf[8], dof[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    qf[t] = *reinterpret_cast<const bf16x8*>(qptr + 16 * t + 8 * g);
+    dof[t] = *reinterpret_cast<const bf16x8*>(doptr + 16 * t + 8 * g);
+  }
+  const int64_t stat = ((int64_t)b * p.Hq + h) * p.C + crow;
+  const float lse_c = p.lse[stat] * kLog2e;
+  const float delta = p.delta[stat];
+  const float c = p.scale * kLog2e;
+
+  const __bf16* kbase = static_cast<const __bf16*>(p.k) + b * p.kvs[0] + kvh * p.kvs[1];
+  const __bf16* vbase = static_cast<const __bf16*>(p.v) + b * p.kvs[0] + kvh * p.kvs[1];
+  const int wg_kv_end = p.q_start + min((mt + 1) * BM, p.C);
+  const int n_tiles = (wg_kv_end + BN - 1) / BN;
+  const int wave_kv_end = m0 < p.C ? p.q_start + min(m0 + 32, p.C) : 0;
+
+  bf16x8 kreg[4], vreg[4];
+  auto fetch = [&](int n) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int cid = tid + 256 * i, r = cid >> 4, ch = cid & 15;
+      const int64_t off = (int64_t)min(n * BN + r, kv_len - 1) * p.kvs[2] + ch * 8;
+      kreg[i] = *reinterpret_cast<const bf16x8*>(kbase + off);
+      vreg[i] = *reinterpret_cast<const bf16x8*>(vbase + off);
+    }
+  };
+  auto stash = [&](int buf) {
+    lds_char* kt = smem + buf * 2 * kTileBytes;
+    lds_char* vt = kt + kTileBytes;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int cid = tid + 256 * i, r = cid >> 4, ch = cid & 15;
+      lds_store16(kt, r, ch, kreg[i]);
+      lds_store16(vt, r, ch, vreg[i]);
+    }
+  };
+
+  f32x16 dq[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
+
+  fetch(0);
+  stash(0);
+  __syncthreads();
+
+  for (int n = 0; n < n_tiles; ++n) {
+    const int buf = n & 1;
+    if (n + 1 < n_tiles) fetch(n + 1);
+    lds_char* kt = smem + buf * 2 * kTileBytes;
+    lds_char* vt = kt + kTileBytes;
+#pragma unroll
+    for (int kvb = 0; kvb < 2; ++kvb) {
+      const int col0 = n * BN + kvb * 32;
+      if (col0 < wave_kv_end) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) s = mfma(lds_row8(kt, kvb * 32 + l32, 2 * t + g), qf[t], s);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) dp = mfma(lds_row8(vt, kvb * 32 + l32, 2 * t + g), dof[t], dp);
+        const bool diag = col0 + 31 > p.q_start + m0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kv = col0 + 8 * (r >> 2) + 4 * g + (r & 3);
+          float pr = fast_exp2(__builtin_fmaf(s[r], c, -lse_c));
+          if (diag && kv > qpos) pr = 0.f;
+          s[r] = pr * (dp[r] - delta);
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8 dsb = pack8(s, t);
+#pragma unroll
+          for (int db = 0; db < 4; ++db) dq[db] = mfma(lds_tr8(kt, kvb * 32 + 16 * t, db, lane), dsb, dq[db]);
+        }
+      }
+    }
+    if (n + 1 < n_tiles) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  if (row < p.C) {
+    __bf16* out = static_cast<__bf16*>(p.d_q) + b * p.qs[0] + h * p.qs[1] + (int64_t)row * p.qs[2];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = (__bf16)(dq[db][4 * r4 + i] * p.scale);
+        *reinterpret_cast<bf16x4*>(out + 32 * db + 8 * r4 + 4 * g) = v;
+      }
+  }
+}
+
+}  // namespace
+
+int launch_dq_bf16(const AttnParams& p, hipStream_t s) {
+  const int n_mtiles = (p.C + BM - 1) / BM;
+  const int total = p.B * p.Hq * n_mtiles;
+  {
+    ProfScope prof(kKernelDq, s);
+    hipLaunchKernelGGL(dq_bf16_kernel, dim3(xcd_grid(total)), dim3(256), 0, s, p, n_mtiles, total);
+  }
+  return launch_status();
+}
+
+}  // namespace seco

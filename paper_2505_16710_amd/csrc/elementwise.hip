@@ -1,0 +1,121 @@
+// Bandwidth-bound helpers: KV-gradient buffer zero / axpy (the gradient relay of the
+// paper's appendix listing, "grad + base * scaler") and the softmax-gradient row term
+// delta = rowsum(dO * O).
+#include "seco_internal.h"
+
+namespace seco {
+namespace {
+
+// Rows [r0, r1) of a [B, H, N, D] fp32 buffer, one float4 per thread-iteration.
+// Work item index -> (b, h, row, d4); consecutive threads touch consecutive 16-byte words of a row.
+template <bool kAxpy>
+__global__ __launch_bounds__(256) void kvgrad_kernel(float* __restrict__ dst, const float* __restrict__ src, float scale,
+                                                     int H, int d4, int64_t gs0, int64_t gs1, int64_t gs2, int64_t r0,
+                                                     int64_t nrows, int64_t total) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t dd = i % d4;
+    int64_t t = i / d4;
+    const int64_t row = t % nrows;
+    t /= nrows;
+    const int64_t h = t % H, b = t / H;
+    const int64_t off = b * gs0 + h * gs1 + (r0 + row) * gs2 + dd * 4;
+    float4* d = reinterpret_cast<float4*>(dst + off);
+    if (kAxpy) {
+      const float4 x = *reinterpret_cast<const float4*>(src + off);
+      float4 y = *d;
+      y.x += scale * x.x;
+      y.y += scale * x.y;
+      y.z += scale * x.z;
+      y.w += scale * x.w;
+      *d = y;
+    } else {
+      *d = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+}
+
+__device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// One wavefront per row; 16-byte loads; fp32 accumulation; cross-lane tree reduction.
+template <bool kBf16>
+__global__ __launch_bounds__(256) void delta_kernel(AttnParams p) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t nrows = (int64_t)p.B * p.Hq * p.C;
+  if (row >= nrows) return;
+  const int r = row % p.C;
+  const int h = (row / p.C) % p.Hq;
+  const int b = row / ((int64_t)p.C * p.Hq);
+  const int64_t off = b * p.os[0] + h * p.os[1] + (int64_t)r * p.os[2];
+  float acc = 0.f;
+  if (kBf16) {
+    const uint4* o = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p.o) + off);
+    const uint4* g = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p.d_o) + off);
+    for (int i = lane; i < p.D / 8; i += 64) {
+      const uint4 a = o[i], c = g[i];
+      acc += bf16_lo(a.x) * bf16_lo(c.x) + bf16_hi(a.x) * bf16_hi(c.x);
+      acc += bf16_lo(a.y) * bf16_lo(c.y) + bf16_hi(a.y) * bf16_hi(c.y);
+      acc += bf16_lo(a.z) * bf16_lo(c.z) + bf16_hi(a.z) * bf16_hi(c.z);
+      acc += bf16_lo(a.w) * bf16_lo(c.w) + bf16_hi(a.w) * bf16_hi(c.w);
+    }
+  } else {
+    const float4* o = reinterpret_cast<const float4*>(static_cast<const float*>(p.o) + off);
+    const float4* g = reinterpret_cast<const float4*>(static_cast<const float*>(p.d_o) + off);
+    for (int i = lane; i < p.D / 4; i += 64) {
+      const float4 a = o[i], c = g[i];
+      acc += a.x * c.x + a.y * c.y + a.z * c.z + a.w * c.w;
+    }
+  }
+#pragma unroll
+  for (int s = 32; s > 0; s >>= 1) acc += __shfl_xor(acc, s);
+  if (lane == 0) p.delta[row] = acc;
+}
+
+int grid_for(int64_t total) {
+  const int64_t blocks = (total + 255) / 256;
+  return (int)(blocks < 65536 ? blocks : 65536);  // grid-stride loop covers the rest
+}
+
+}  // namespace
+
+int launch_kvgrad_zero(float* g, int B, int H, int D, const int64_t gs[3], int64_t r0, int64_t r1, hipStream_t s) {
+  const int64_t total = (int64_t)B * H * (r1 - r0) * (D / 4);
+  if (total == 0) return SECO_OK;
+  {
+    ProfScope prof(kKernelKvgrad, s);
+    hipLaunchKernelGGL(kvgrad_kernel<false>, dim3(grid_for(total)), dim3(256), 0, s, g, nullptr, 0.f, H, D / 4, gs[0],
+                     gs[1], gs[2], r0, r1 - r0, total);
+  }
+  return launch_status();
+}
+
+int launch_kvgrad_axpy(float* dst, const float* src, float scale, int B, int H, int D, const int64_t gs[3], int64_t r0,
+                       int64_t r1, hipStream_t s) {
+  const int64_t total = (int64_t)B * H * (r1 - r0) * (D / 4);
+  if (total == 0) return SECO_OK;
+  {
+    ProfScope prof(kKernelKvgrad, s);
+    hipLaunchKernelGGL(kvgrad_kernel<true>, dim3(grid_for(total)), dim3(256), 0, s, dst, src, scale, H, D / 4, gs[0],
+                     gs[1], gs[2], r0, r1 - r0, total);
+  }
+  return launch_status();
+}
+
+int launch_delta(const AttnParams& p, int dtype, hipStream_t s) {
+  const int64_t nrows = (int64_t)p.B * p.Hq * p.C;
+  const unsigned blocks = (unsigned)((nrows + 3) / 4);
+  if (dtype == SECO_BF16)
+    {
+    ProfScope prof(kKernelDelta, s);
+    hipLaunchKernelGGL(delta_kernel<true>, dim3(blocks), dim3(256), 0, s, p);
+  }
+  else
+    {
+    ProfScope prof(kKernelDelta, s);
+    hipLaunchKernelGGL(delta_kernel<false>, dim3(blocks), dim3(256), 0, s, p);
+  }
+  return launch_status();
+}
+
+}  // namespace seco

@@ -1,0 +1,180 @@
+// Forward of one chunk, bf16 matrix cores (Eq. 1 at the attention layer):
+// O = softmax(s Q K^T) V over cache rows [0, q_start + C) with the causal rule
+// col <= q_start + row, plus the per-row log-sum-exp.
+//
+// Decomposition.  One workgroup (4 wavefronts) owns 128 query rows of one head; each
+// wavefront owns 32 of them and keeps Q^T fragments, the running max / sum and the O^T
+// accumulator (128 x 32, fp32) in registers.  K and V tiles of 64 cache rows stream through a
+// double-buffered, swizzled LDS tile shared by the four wavefronts; the next tile is fetched
+// into registers while the current one is consumed.
+//
+// The score tile is computed transposed, S^T = K Q^T, so that a lane owns one query row
+// (C layout: lane = column): row max / row sum are in-lane reductions plus one exchange with
+// lane^32, the rescale of O^T is a per-lane scalar, and P^T feeds the second product
+// O^T += V^T P^T straight from registers.  V^T comes from the row-major V tile through the
+// LDS transpose read.
+#include "mfma_tiles.h"
+#include "seco_internal.h"
+
+namespace seco {
+namespace {
+
+constexpr int BM = 128;  // query rows per workgroup
+constexpr int BN = 64;   // cache rows per tile
+constexpr int kTileBytes = BN * kRowBytes;
+
+__global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
+  __shared__ __attribute__((aligned(16))) char smem_raw[4 * kTileBytes];
+  lds_char* smem = (lds_char*)smem_raw;  // [buf][K|V]
+
+  const int item = xcd_item(blockIdx.x, total_items);
+  if (item < 0) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  // item -> (batch, kv head, row tile (heavy first), head within the group)
+  const int hg = item % p.G;
+  int rest = item / p.G;
+  const int mt = n_mtiles - 1 - rest % n_mtiles;
+  rest /= n_mtiles;
+  const int kvh = rest % p.Hkv, b = rest / p.Hkv;
+  const int h = kvh * p.G + hg;
+
+  const int kv_len = p.q_start + p.C;
+  const int m0 = mt * BM + wave * 32;          // first chunk-local row of this wavefront
+  const int row = m0 + l32;                    // this lane's row
+  const int qpos = p.q_start + row;            // its global position
+  const __bf16* qptr = static_cast<const __bf16*>(p.q) + b * p.qs[0] + h * p.qs[1] + (int64_t)min(row, p.C - 1) * p.qs[2];
+  bf16x8 qf[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(qptr + 16 * t + 8 * g);
+
+  const __bf16* kbase = static_cast<const __bf16*>(p.k) + b * p.kvs[0] + kvh * p.kvs[1];
+  const __bf16* vbase = static_cast<const __bf16*>(p.v) + b * p.kvs[0] + kvh * p.kvs[1];
+
+  const int wg_kv_end = p.q_start + min((mt + 1) * BM, p.C);   // columns any row of the workgroup sees
+  const int n_tiles = (wg_kv_end + BN - 1) / BN;
+  const int wave_kv_end = m0 < p.C ? p.q_start + min(m0 + 32, p.C) : 0;  // columns this wavefront sees
+
+  // global -> register staging of one K and one V tile: thread owns chunks tid + 256*i
+  bf16x8 kreg[4], vreg[4];
+  auto fetch = [&](int n) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int cid = tid + 256 * i, r = cid >> 4, ch = cid & 15;
+      const int64_t off = (int64_t)min(n * BN + r, kv_len - 1) * p.kvs[2] + ch * 8;
+      kreg[i] = *reinterpret_cast<const bf16x8*>(kbase + off);
+      vreg[i] = *reinterpret_cast<const bf16x8*>(vbase + off);
+    }
+  };
+  auto stash = [&](int buf) {
+    lds_char* kt = smem + buf * 2 * kTileBytes;
+    lds_char* vt = kt + kTileBytes;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int cid = tid + 256 * i, r = cid >> 4, ch = cid & 15;
+      lds_store16(kt, r, ch, kreg[i]);
+      lds_store16(vt, r, ch, vreg[i]);
+    }
+  };
+
+  f32x16 o[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c = p.scale * kLog2e;
+
+  fetch(0);
+  stash(0);
+  __syncthreads();
+
+  for (int n = 0; n < n_tiles; ++n) {
+    const int buf = n & 1;
+    if (n + 1 < n_tiles) fetch(n + 1);
+    if (n * BN < wave_kv_end) {
+      lds_char* kt = smem + buf * 2 * kTileBytes;
+      lds_char* vt = kt + kTileBytes;
+      f32x16 s[2];
+#pragma unroll
+      for (int kvb = 0; kvb < 2; ++kvb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[kvb][r] = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) s[kvb] = mfma(lds_row8(kt, kvb * 32 + l32, 2 * t + g), qf[t], s[kvb]);
+      }
+      if (n * BN + BN - 1 > p.q_start + m0) {  // tile reaches past this wavefront's first row: causal mask
+#pragma unroll
+        for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kv = n * BN + kvb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+            if (kv > qpos) s[kvb][r] = -INFINITY;
+          }
+      }
+      float mx = s[0][0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx * c);
+      const float alpha = fast_exp2(m_run - m_new);
+      float sum = 0.f;
+#pragma unroll
+      for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float e = fast_exp2(__builtin_fmaf(s[kvb][r], c, -m_new));
+          s[kvb][r] = e;
+          sum += e;
+        }
+      l_run = l_run * alpha + sum;
+      m_run = m_new;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+#pragma unroll
+      for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8 pb = pack8(s[kvb], t);
+#pragma unroll
+          for (int db = 0; db < 4; ++db) o[db] = mfma(lds_tr8(vt, kvb * 32 + 16 * t, db, lane), pb, o[db]);
+        }
+    }
+    if (n + 1 < n_tiles) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  if (row < p.C) {
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv = 1.f / l_tot;
+    __bf16* optr = static_cast<__bf16*>(p.o_out) + b * p.os[0] + h * p.os[1] + (int64_t)row * p.os[2];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = (__bf16)(o[db][4 * r4 + i] * inv);
+        *reinterpret_cast<bf16x4*>(optr + 32 * db + 8 * r4 + 4 * g) = v;
+      }
+    if (g == 0) p.lse[((int64_t)b * p.Hq + h) * p.C + row] = (m_run + __log2f(l_tot)) * kLn2;
+  }
+}
+
+}  // namespace
+
+int launch_fwd_bf16(const AttnParams& p, hipStream_t s) {
+  const int n_mtiles = (p.C + BM - 1) / BM;
+  const int total = p.B * p.Hq * n_mtiles;
+  {
+    ProfScope prof(kKernelFwd, s);
+    hipLaunchKernelGGL(fwd_bf16_kernel, dim3(xcd_grid(total)), dim3(256), 0, s, p, n_mtiles, total);
+  }
+  return launch_status();
+}
+
+}  // namespace seco

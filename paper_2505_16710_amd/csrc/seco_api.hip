@@ -1,0 +1,271 @@
+// Host side of the C ABI: argument validation, segment tables and kernel dispatch.
+// Nothing here allocates device memory or synchronises the stream.
+#include <cmath>
+#include <cstring>
+#include <algorithm>
+#include <vector>
+
+#include "seco_internal.h"
+
+namespace seco {
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_desc(const seco_desc* d) {
+  if (!d) return SECO_ERR_NULL;
+  if (d->dtype != SECO_F32 && d->dtype != SECO_BF16) return SECO_ERR_DTYPE;
+  if (d->batch < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->head_dim < 1 || d->chunk_len < 1 || d->q_start < 0)
+    return SECO_ERR_SHAPE;
+  if (d->n_q_heads % d->n_kv_heads != 0) return SECO_ERR_SHAPE;
+  if ((int64_t)d->q_start + d->chunk_len > (int64_t)1 << 30) return SECO_ERR_TOO_LARGE;
+  if (d->batch > 65535 || d->n_q_heads > 65535) return SECO_ERR_TOO_LARGE;
+  if ((int64_t)d->batch * d->n_q_heads * ((d->chunk_len + 3) / 4) > (int64_t)1 << 31) return SECO_ERR_TOO_LARGE;
+  if (d->dtype == SECO_BF16) {
+    if (d->head_dim != 128) return SECO_ERR_HEAD_DIM;
+  } else if (d->head_dim % 4 != 0 || d->head_dim > 256) {
+    return SECO_ERR_HEAD_DIM;
+  }
+  if (!std::isfinite(d->softmax_scale) || !(d->softmax_scale > 0.f)) return SECO_ERR_SHAPE;
+  return SECO_OK;
+}
+
+// strides in elements; rows must start on 16-byte boundaries
+int check_strides(const int64_t s[3], int elem_bytes, int D) {
+  const int64_t per16 = 16 / elem_bytes;
+  for (int i = 0; i < 3; ++i)
+    if (s[i] < 0 || s[i] % per16 != 0) return SECO_ERR_ALIGN;
+  if (s[2] < D) return SECO_ERR_ALIGN;
+  return SECO_OK;
+}
+
+AttnParams make_params(const seco_desc* d) {
+  AttnParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.B = d->batch;
+  p.Hq = d->n_q_heads;
+  p.Hkv = d->n_kv_heads;
+  p.D = d->head_dim;
+  p.C = d->chunk_len;
+  p.q_start = d->q_start;
+  p.G = d->n_q_heads / d->n_kv_heads;
+  p.scale = d->softmax_scale;
+  for (int i = 0; i < 3; ++i) {
+    p.qs[i] = d->q_stride[i];
+    p.os[i] = d->o_stride[i];
+    p.kvs[i] = d->kv_stride[i];
+    p.gs[i] = d->g_stride[i];
+  }
+  return p;
+}
+
+size_t delta_bytes(const seco_desc* d) {
+  const size_t n = (size_t)d->batch * d->n_q_heads * d->chunk_len * sizeof(float);
+  return (n + 255) & ~(size_t)255;
+}
+
+int check_fwd_like(const seco_desc* d) {
+  int rc = check_desc(d);
+  if (rc) return rc;
+  const int eb = d->dtype == SECO_BF16 ? 2 : 4;
+  if ((rc = check_strides(d->q_stride, eb, d->head_dim))) return rc;
+  if ((rc = check_strides(d->o_stride, eb, d->head_dim))) return rc;
+  if ((rc = check_strides(d->kv_stride, eb, d->head_dim))) return rc;
+  return SECO_OK;
+}
+
+int backward(const seco_desc* d, const void* q, const void* k, const void* v, const void* o, const float* lse,
+             const void* d_o, void* d_q, float* gk, float* gv, const float* w, int32_t n_chunks, int32_t wlen, void* ws,
+             size_t ws_bytes, void* stream) {
+  int rc = check_fwd_like(d);
+  if (rc) return rc;
+  if ((rc = check_strides(d->g_stride, 4, d->head_dim))) return rc;
+  if (!q || !k || !v || !o || !lse || !d_o || !d_q || !gk || !gv) return SECO_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(d_q) ||
+      !aligned16(gk) || !aligned16(gv) || !aligned16(lse))
+    return SECO_ERR_ALIGN;
+  if (!ws || ws_bytes < delta_bytes(d) || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SECO_ERR_WORKSPACE;
+  const int kv_len = d->q_start + d->chunk_len;
+  const int tile = d->dtype == SECO_BF16 ? kColTileBf16 : kColTileF32;
+
+  // Column segments: maximal runs of cache rows with one non-zero weight.
+  struct Run { int b, e; float w; };
+  std::vector<Run> runs;
+  if (!w) {
+    runs.push_back({0, kv_len, 1.f});
+  } else {
+    if (n_chunks < 1 || wlen < 1) return SECO_ERR_WEIGHTS;
+    if ((int64_t)n_chunks * wlen < kv_len || (int64_t)(n_chunks - 1) * wlen >= kv_len) return SECO_ERR_WEIGHTS;
+    for (int i = 0; i < n_chunks; ++i)
+      if (!std::isfinite(w[i])) return SECO_ERR_WEIGHTS;
+    for (int i = 0; i < n_chunks; ++i) {
+      if (w[i] == 0.f) continue;
+      const int b = (int)((int64_t)i * wlen), e = (int)std::min<int64_t>((int64_t)(i + 1) * wlen, kv_len);
+      if (!runs.empty() && runs.back().e == b && runs.back().w == w[i])
+        runs.back().e = e;
+      else
+        runs.push_back({b, e, w[i]});
+    }
+  }
+
+  AttnParams p = make_params(d);
+  p.q = q; p.k = k; p.v = v; p.o = o; p.d_o = d_o; p.d_q = d_q;
+  p.lse = const_cast<float*>(lse);
+  p.delta = static_cast<float*>(ws);
+  p.gk = gk; p.gv = gv;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool bf16 = d->dtype == SECO_BF16;
+  if ((rc = launch_delta(p, d->dtype, s))) return rc;
+  if ((rc = bf16 ? launch_dq_bf16(p, s) : launch_dq_f32(p, s))) return rc;
+  for (size_t first = 0; first < runs.size(); first += kMaxSegments) {
+    SegTable seg;
+    std::memset(&seg, 0, sizeof(seg));
+    seg.n = (int)std::min<size_t>(kMaxSegments, runs.size() - first);
+    for (int i = 0; i < seg.n; ++i) {
+      const Run& r = runs[first + i];
+      seg.col_begin[i] = r.b;
+      seg.col_end[i] = r.e;
+      seg.weight[i] = r.w;
+      seg.tile_begin[i + 1] = seg.tile_begin[i] + (r.e - r.b + tile - 1) / tile;
+    }
+    if ((rc = bf16 ? launch_dkdv_bf16(p, seg, s) : launch_dkdv_f32(p, seg, s))) return rc;
+  }
+  return SECO_OK;
+}
+
+}  // namespace
+}  // namespace seco
+
+// ---- optional per-kernel timing ---------------------------------------------------------
+namespace seco {
+namespace {
+struct ProfRecord { int kind; hipEvent_t start, stop; };
+bool g_prof_on = false;
+std::vector<ProfRecord> g_prof;
+}  // namespace
+
+ProfScope::ProfScope(KernelKind kind, hipStream_t s) : stream(s), slot(-1) {
+  if (!g_prof_on) return;
+  ProfRecord r;
+  r.kind = kind;
+  if (hipEventCreate(&r.start) != hipSuccess) return;
+  if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return; }
+  (void)hipEventRecord(r.start, s);
+  slot = (int)g_prof.size();
+  g_prof.push_back(r);
+}
+ProfScope::~ProfScope() {
+  if (slot >= 0) (void)hipEventRecord(g_prof[slot].stop, stream);
+}
+}  // namespace seco
+
+using namespace seco;
+
+extern "C" int seco_profile_enable(int on) {
+  for (ProfRecord& r : g_prof) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  g_prof.clear();
+  g_prof_on = on != 0;
+  return SECO_OK;
+}
+
+extern "C" int seco_profile_read(double* total_ms, int64_t* launches) {
+  if (!total_ms || !launches) return SECO_ERR_NULL;
+  for (int i = 0; i < SECO_PROFILE_KINDS; ++i) {
+    total_ms[i] = 0.0;
+    launches[i] = 0;
+  }
+  int rc = SECO_OK;
+  for (ProfRecord& r : g_prof) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
+      rc = SECO_ERR_LAUNCH;
+    total_ms[r.kind] += ms;
+    launches[r.kind] += 1;
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  g_prof.clear();
+  return rc;
+}
+
+extern "C" size_t seco_workspace_bytes(const seco_desc* desc, int op) {
+  if (check_desc(desc) != SECO_OK) return (size_t)-1;
+  if (op == SECO_OP_FWD) return 0;
+  if (op == SECO_OP_BWD) return delta_bytes(desc);
+  return (size_t)-1;
+}
+
+extern "C" int seco_chunk_attn_fwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                   void* o, float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
+  (void)ws;
+  (void)ws_bytes;
+  int rc = check_fwd_like(desc);
+  if (rc) return rc;
+  if (!q || !k_cache || !v_cache || !o || !lse) return SECO_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(o) || !aligned16(lse))
+    return SECO_ERR_ALIGN;
+  AttnParams p = make_params(desc);
+  p.q = q; p.k = k_cache; p.v = v_cache; p.o_out = o; p.lse = lse;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  return desc->dtype == SECO_BF16 ? launch_fwd_bf16(p, s) : launch_fwd_f32(p, s);
+}
+
+extern "C" int seco_chunk_attn_bwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                   const void* o, const float* lse, const void* d_o, void* d_q, float* gk, float* gv,
+                                   void* ws, size_t ws_bytes, void* hip_stream) {
+  return backward(desc, q, k_cache, v_cache, o, lse, d_o, d_q, gk, gv, nullptr, 0, 0, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int spaco_chunk_attn_bwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                    const void* o, const float* lse, const void* d_o, void* d_q, float* gk, float* gv,
+                                    const float* chunk_weight_host, int32_t n_chunks, int32_t weight_chunk_len, void* ws,
+                                    size_t ws_bytes, void* hip_stream) {
+  if (!chunk_weight_host) return SECO_ERR_NULL;
+  return backward(desc, q, k_cache, v_cache, o, lse, d_o, d_q, gk, gv, chunk_weight_host, n_chunks, weight_chunk_len, ws,
+                  ws_bytes, hip_stream);
+}
+
+namespace {
+int check_rows(const seco_desc* d, int64_t r0, int64_t r1) {
+  int rc = check_desc(d);
+  if (rc) return rc;
+  if ((rc = check_strides(d->g_stride, 4, d->head_dim))) return rc;
+  if (r0 < 0 || r1 < r0 || r1 > ((int64_t)1 << 40)) return SECO_ERR_RANGE;
+  return SECO_OK;
+}
+}  // namespace
+
+extern "C" int kvgrad_zero(const seco_desc* desc, float* gk, float* gv, int64_t row_begin, int64_t row_end,
+                           void* hip_stream) {
+  int rc = check_rows(desc, row_begin, row_end);
+  if (rc) return rc;
+  if ((gk && !aligned16(gk)) || (gv && !aligned16(gv))) return SECO_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  for (float* g : {gk, gv}) {
+    if (!g) continue;
+    if ((rc = launch_kvgrad_zero(g, desc->batch, desc->n_kv_heads, desc->head_dim, desc->g_stride, row_begin, row_end, s)))
+      return rc;
+  }
+  return SECO_OK;
+}
+
+extern "C" int kvgrad_accumulate(const seco_desc* desc, float* dst_k, float* dst_v, const float* src_k,
+                                 const float* src_v, float scale, int64_t row_begin, int64_t row_end, void* hip_stream) {
+  int rc = check_rows(desc, row_begin, row_end);
+  if (rc) return rc;
+  if ((dst_k == nullptr) != (src_k == nullptr) || (dst_v == nullptr) != (src_v == nullptr)) return SECO_ERR_NULL;
+  if ((dst_k && dst_k == src_k) || (dst_v && dst_v == src_v)) return SECO_ERR_RANGE;
+  for (const void* ptr : {(const void*)dst_k, (const void*)dst_v, (const void*)src_k, (const void*)src_v})
+    if (ptr && !aligned16(ptr)) return SECO_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (dst_k && (rc = launch_kvgrad_axpy(dst_k, src_k, scale, desc->batch, desc->n_kv_heads, desc->head_dim,
+                                        desc->g_stride, row_begin, row_end, s)))
+    return rc;
+  if (dst_v && (rc = launch_kvgrad_axpy(dst_v, src_v, scale, desc->batch, desc->n_kv_heads, desc->head_dim,
+                                        desc->g_stride, row_begin, row_end, s)))
+    return rc;
+  return SECO_OK;
+}

@@ -1,0 +1,247 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle on the
+same seeded inputs.  Tolerances (max |x - ref| / max |ref| per tensor): fp32 1e-4;
+bf16 1e-2 on O (and LSE), 2e-2 on dQ, gK, gV."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_16710_amd as seco
+from oracle import attention as A
+from oracle import selection as S
+from workloads import CONFIGS, full_layer, small_layer, kv_group, Config
+
+from hip_driver import DEV, max_rel, run_layer, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": {"o": 1e-4, "lse": 1e-4, "dq": 1e-4, "gk": 1e-4, "gv": 1e-4},
+       "bf16": {"o": 1e-2, "lse": 1e-2, "dq": 2e-2, "gk": 2e-2, "gv": 2e-2}}
+
+
+def check(got, ref, dtype, what=""):
+    names = ("o", "lse", "dq", "gk", "gv")
+    errs = {n: max_rel(got[n], r) for n, r in zip(names, ref)}
+    print(what, {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+    for n in names:
+        assert np.isfinite(got[n]).all(), n
+        assert errs[n] <= TOL[dtype][n], (what, n, errs[n])
+
+
+def test_cfg1_fp32_seco_full_parity():
+    cfg = CONFIGS["cfg1"]
+    x = full_layer(cfg)
+    got = run_layer(x, cfg.chunk_len, cfg.scale, "f32")
+    ref = A.seco_layer(x["q"], x["k"], x["v"], x["do"], cfg.chunk_len, cfg.scale)
+    check(got, ref, "f32", "cfg1")
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,D,C", [
+    (2, 4, 2, 300, 64, 128),     # ragged last chunk, GQA
+    (1, 3, 3, 130, 20, 50),      # head_dim not a multiple of 64, odd sizes
+    (1, 2, 1, 70, 256, 70),      # largest head_dim, single chunk
+    (1, 2, 2, 5, 4, 1),          # one row per chunk
+])
+def test_fp32_shapes(B, Hq, Hkv, N, D, C):
+    x = small_layer(10, B, Hq, Hkv, N, D, "f32")
+    s = 1 / np.sqrt(D)
+    got = run_layer(x, C, s, "f32")
+    ref = A.seco_layer(x["q"], x["k"], x["v"], x["do"], C, s)
+    check(got, ref, "f32", f"f32 {B,Hq,Hkv,N,D,C}")
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,C", [
+    (1, 4, 1, 512, 256),     # aligned, G = 4
+    (2, 4, 2, 640, 256),     # short last chunk (128 rows)
+    (1, 2, 2, 700, 200),     # nothing aligned to the 32/64/128 tiles
+    (1, 8, 2, 1536, 512),    # several row tiles per chunk, several column tiles
+    (1, 2, 1, 33, 33),       # single tiny chunk
+    (1, 2, 1, 96, 1),        # one row per call
+])
+def test_bf16_seco_parity(B, Hq, Hkv, N, C):
+    x = small_layer(20, B, Hq, Hkv, N, 128, "bf16")
+    s = 1 / np.sqrt(128)
+    got = run_layer(x, C, s, "bf16")
+    ref = A.seco_layer(x["q"], x["k"], x["v"], x["do"], C, s)
+    check(got, ref, "bf16", f"bf16 {B,Hq,Hkv,N,C}")
+
+
+@pytest.mark.parametrize("dtype,D,N,C,sel,lam", [
+    ("f32", 64, 256, 64, [3, 1, 0], 4 / 3),
+    ("bf16", 128, 1024, 256, [3, 1, 0], 4 / 3),
+    ("bf16", 128, 1280, 160, [7, 6, 2], 8 / 3),   # chunk length not a multiple of the column tile
+    ("bf16", 128, 1024, 128, [5], 8.0),           # a single selected chunk: own block only
+])
+def test_spaco_parity(dtype, D, N, C, sel, lam):
+    x = small_layer(30, 1, 4, 2, N, D, dtype)
+    s = 1 / np.sqrt(D)
+    lam32 = float(np.float32(lam))
+    got = run_layer(x, C, s, dtype, selected=sel, factor=lam32)
+    ref = A.spaco_layer(x["q"], x["k"], x["v"], x["do"], C, s, sel, lam32)
+    check(got, ref, dtype, f"spaco {dtype} {N,C,sel}")
+    k = -(-N // C)
+    for i in range(k):
+        if i not in sel:   # unselected chunks: untouched rows are exactly zero
+            assert not got["gk"][:, :, i * C:(i + 1) * C].any() and not got["dq"][:, :, i * C:(i + 1) * C].any()
+
+
+def _one_call(dtype, D, N, C, j, weights=None, seed=40):
+    x = small_layer(seed, 1, 4, 2, N, D, dtype)
+    q, k, v, do = (to_dev(x[n], dtype) for n in ("q", "k", "v", "do"))
+    s = 1 / np.sqrt(D)
+    qc = q[:, :, j * C:(j + 1) * C]
+    o, lse = seco.seco_chunk_attn_fwd(qc, k, v, j * C, s)
+    doc = do[:, :, j * C:(j + 1) * C].contiguous()
+    gk = torch.zeros(k.shape, dtype=torch.float32, device=DEV)
+    gv = torch.zeros(k.shape, dtype=torch.float32, device=DEV)
+    if weights is None:
+        dq = seco.seco_chunk_attn_bwd(qc, k, v, o, lse, doc, gk, gv, j * C, s)
+    else:
+        dq = seco.spaco_chunk_attn_bwd(qc, k, v, o, lse, doc, gk, gv, j * C, s, weights, C)
+    torch.cuda.synchronize()
+    return dq, gk, gv
+
+
+@pytest.mark.parametrize("dtype,D", [("f32", 64), ("bf16", 128)])
+def test_unit_weights_equal_seco_bitwise_and_reruns_are_identical(dtype, D):
+    """No atomics anywhere: the same call gives the same bits, and SpaCO with all weights 1
+    is the SeCO backward."""
+    a = _one_call(dtype, D, 1024, 256, 3)
+    b = _one_call(dtype, D, 1024, 256, 3)
+    c = _one_call(dtype, D, 1024, 256, 3, weights=[1.0, 1.0, 1.0, 1.0])
+    for x, y, z in zip(a, b, c):
+        assert torch.equal(x, y) and torch.equal(x, z)
+
+
+@pytest.mark.parametrize("dtype,D", [("f32", 64), ("bf16", 128)])
+def test_weights_in_kernel_equal_scaled_accumulate(dtype, D):
+    """The factor applied inside the backward equals an unweighted backward followed by
+    kvgrad_accumulate(scale) on the earlier rows (the appendix listing's grad + base*scaler)."""
+    lam = 2.5
+    dq_w, gk_w, gv_w = _one_call(dtype, D, 1024, 256, 3, weights=[lam, 0.0, lam, 1.0])
+    dq_u, gk_u, gv_u = _one_call(dtype, D, 1024, 256, 3)
+    gk2, gv2 = torch.zeros_like(gk_u), torch.zeros_like(gv_u)
+    seco.kvgrad_accumulate(gk2, gv2, gk_u, gv_u, lam, 0, 256)
+    seco.kvgrad_accumulate(gk2, gv2, gk_u, gv_u, lam, 512, 768)
+    seco.kvgrad_accumulate(gk2, gv2, gk_u, gv_u, 1.0, 768, 1024)
+    torch.cuda.synchronize()
+    assert torch.equal(dq_w, dq_u)
+    for a, b in ((gk_w, gk2), (gv_w, gv2)):
+        assert not b[:, :, 256:512].any() and not a[:, :, 256:512].any()
+        assert max_rel(to_host(a), to_host(b)) < 1e-6
+
+
+def test_backward_accumulates_into_existing_gradients():
+    x = small_layer(41, 1, 2, 1, 512, 128, "bf16")
+    q, k, v, do = (to_dev(x[n], "bf16") for n in ("q", "k", "v", "do"))
+    s = 1 / np.sqrt(128)
+    o, lse = seco.seco_chunk_attn_fwd(q[:, :, 256:], k, v, 256, s)
+    base = torch.randn(k.shape, dtype=torch.float32, device=DEV)
+    gk, gv = base.clone(), (2 * base).clone()
+    zk, zv = torch.zeros_like(base), torch.zeros_like(base)
+    doc = do[:, :, 256:].contiguous()
+    seco.seco_chunk_attn_bwd(q[:, :, 256:], k, v, o, lse, doc, gk, gv, 256, s)
+    seco.seco_chunk_attn_bwd(q[:, :, 256:], k, v, o, lse, doc, zk, zv, 256, s)
+    torch.cuda.synchronize()
+    assert torch.allclose(gk, base + zk, rtol=1e-6, atol=1e-6) and torch.allclose(gv, 2 * base + zv, rtol=1e-6, atol=1e-6)
+
+
+def test_kvgrad_zero_and_accumulate_with_strides_and_row_ranges():
+    big = torch.randn(2, 3, 40, 2 * 64, device=DEV)
+    gk = big[:, :, :, :64]          # row stride 128, head_dim 64: a strided view
+    gv = big[:, :, :, 64:]          # gK and gV share one stride triple in the descriptor
+    keep_k, keep_v = gk.clone(), gv.clone()
+    seco.kvgrad_zero(gk, gv, 8, 24)
+    torch.cuda.synchronize()
+    assert not gk[:, :, 8:24].any() and not gv[:, :, 8:24].any()
+    assert torch.equal(gk[:, :, :8], keep_k[:, :, :8]) and torch.equal(gk[:, :, 24:], keep_k[:, :, 24:])
+    assert torch.equal(gv[:, :, :8], keep_v[:, :, :8]) and torch.equal(gv[:, :, 24:], keep_v[:, :, 24:])
+    src = torch.randn(2, 3, 40, 64, device=DEV)
+    dst = torch.randn(2, 3, 40, 64, device=DEV)
+    want = dst.clone()
+    want[:, :, 4:30] += 1.5 * src[:, :, 4:30]
+    seco.kvgrad_accumulate(dst, None, src, None, 1.5, 4, 30)
+    torch.cuda.synchronize()
+    assert torch.allclose(dst, want, rtol=1e-6, atol=1e-6)
+    seco.kvgrad_zero(dst, None, 7, 7)      # empty range: no-op
+    torch.cuda.synchronize()
+    assert torch.allclose(dst, want, rtol=1e-6, atol=1e-6)
+
+
+def test_strided_inputs_bf16():
+    """Q/O/dO/dQ taken as views of a packed [B, N, H, D] projection output (row stride H*D)."""
+    x = small_layer(42, 1, 4, 2, 384, 128, "bf16")
+    s = 1 / np.sqrt(128)
+    def packed(a):   # [B,H,N,D] -> storage [B,N,H,D], viewed back as [B,H,N,D]
+        return to_dev(a, "bf16").permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    q, k, v, do = packed(x["q"]), packed(x["k"]), packed(x["v"]), packed(x["do"])
+    assert q.stride(2) == 4 * 128
+    o, lse = seco.seco_chunk_attn_fwd(q[:, :, 128:], k, v, 128, s, o=torch.empty_like(q)[:, :, 128:])
+    gk = torch.zeros(1, 384, 2, 128, device=DEV).permute(0, 2, 1, 3)
+    gv = torch.zeros(1, 384, 2, 128, device=DEV).permute(0, 2, 1, 3)
+    dq = seco.seco_chunk_attn_bwd(q[:, :, 128:], k, v, o, lse, do[:, :, 128:], gk, gv, 128, s,
+                                  d_q=torch.empty_like(q)[:, :, 128:])
+    torch.cuda.synchronize()
+    o_ref, lse_ref = A.chunk_attn_fwd(x["q"][:, :, 128:], x["k"], x["v"], 128, s)
+    dq_ref, dk_ref, dv_ref = A.chunk_attn_bwd(x["q"][:, :, 128:], x["k"], x["v"], o_ref, lse_ref, x["do"][:, :, 128:], 128, s)
+    assert max_rel(to_host(o), o_ref) < 1e-2 and max_rel(to_host(dq), dq_ref) < 2e-2
+    assert max_rel(to_host(gk), dk_ref) < 2e-2 and max_rel(to_host(gv), dv_ref) < 2e-2
+
+
+def _device_group(cfg, b, kvh):
+    """One (batch, KV head) unit of a configuration as a G-head layer: host dict + fp64 views."""
+    grp = kv_group(cfg, b, kvh)
+    return {"q": grp["q"][None], "do": grp["do"][None], "k": grp["k"][None, None], "v": grp["v"][None, None]}
+
+
+def test_cfg2_full_size_slice_parity():
+    """Benchmark configuration (16K tokens, 16 chunks of 1024, head_dim 128, G = 4): one
+    complete (batch, KV head) unit - they are independent - through all 16 + 16 + 16 calls."""
+    cfg = CONFIGS["cfg2"]
+    x = _device_group(cfg, 0, 5)
+    got = run_layer(x, cfg.chunk_len, cfg.scale, "bf16")
+    ref = A.seco_layer(x["q"], x["k"], x["v"], x["do"], cfg.chunk_len, cfg.scale)
+    check(got, ref, "bf16", "cfg2 slice")
+
+
+def test_cfg3_spaco_sampled_parity():
+    """32K tokens, 16 chunks of 2048, 4 selected chunks, factor k/t = 4: one (batch, KV head)
+    unit on the GPU; the oracle evaluates sampled query rows (O, LSE, dQ need one row each)
+    and the top selected chunk's own rows of gK/gV (which only that call touches)."""
+    cfg = CONFIGS["cfg3"]
+    k, t, C = cfg.n_chunks, cfg.spaco_t, cfg.chunk_len
+    sel = S.select_chunks(cfg.seed, 0, k, t).tolist()
+    assert sel == seco.spaco_select_chunks(cfg.seed, 0, k, t)
+    lam = float(np.float32(S.compensation_factor(k, t)))
+    x = _device_group(cfg, 0, 2)
+    got = run_layer(x, C, cfg.scale, "bf16", selected=sel, factor=lam)
+    rng = np.random.default_rng(7)
+    q64, k64, v64, do64 = (x[n].astype(np.float64) for n in ("q", "k", "v", "do"))
+    for j in sel:
+        for r in rng.integers(0, C, size=3):
+            p = j * C + int(r)
+            o_r, lse_r = A.chunk_attn_fwd(q64[:, :, p:p + 1], k64, v64, p, cfg.scale)
+            dq_r, dk_r, dv_r = A.chunk_attn_bwd(q64[:, :, p:p + 1], k64, v64, o_r, lse_r, do64[:, :, p:p + 1], p, cfg.scale)
+            assert np.abs(got["o"][:, :, p] - o_r[:, :, 0]).max() <= 1e-2 * np.abs(o_r).max()
+            assert np.abs(got["lse"][:, :, p] - lse_r[:, :, 0]).max() <= 1e-2 * np.abs(lse_r).max()
+            assert np.abs(got["dq"][:, :, p] - dq_r[:, :, 0]).max() <= 2e-2 * np.abs(dq_r).max()
+    top = sel[0]
+    rows = slice(top * C, (top + 1) * C)
+    # own block of the top selected chunk: restrict the cache to that chunk and pass the true LSE / O
+    o_ref, lse_ref = A.chunk_attn_fwd(q64[:, :, rows], k64, v64, top * C, cfg.scale)
+    qs, dos = q64[:, :, rows], do64[:, :, rows]
+    G = qs.shape[1]
+    dk_own = np.zeros((C, cfg.head_dim))
+    dv_own = np.zeros((C, cfg.head_dim))
+    for h in range(G):
+        sc = cfg.scale * qs[0, h] @ k64[0, 0, rows].T
+        vis = np.arange(C)[None, :] <= np.arange(C)[:, None]
+        P = np.where(vis, np.exp(sc - lse_ref[0, h][:, None]), 0.0)
+        dP = dos[0, h] @ v64[0, 0, rows].T
+        dS = P * (dP - (dos[0, h] * o_ref[0, h]).sum(1, keepdims=True))
+        dk_own += cfg.scale * dS.T @ qs[0, h]
+        dv_own += P.T @ dos[0, h]
+    assert max_rel(got["gk"][0, 0, rows], dk_own) <= 2e-2
+    assert max_rel(got["gv"][0, 0, rows], dv_own) <= 2e-2
+    for i in range(k):
+        if i not in sel:
+            assert not got["gk"][:, :, i * C:(i + 1) * C].any() and not got["gv"][:, :, i * C:(i + 1) * C].any()
