@@ -10,7 +10,8 @@ import ctypes as C
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libseco_hip.so")
+# SECO_LIBRARY overrides the path (e.g. to try a library built with other tile parameters)
+_LIB_PATH = os.environ.get("SECO_LIBRARY") or os.path.join(_HERE, "libseco_hip.so")
 _lib = None
 
 SECO_F32, SECO_BF16 = 0, 1

@@ -46,7 +46,10 @@ def _compile(src, extra=()):
     return obj
 
 
-def build_library(verbose=True, extra=()):
+def build_library(verbose=True, extra=(), out=None):
+    global LIB
+    if out:
+        LIB = out
     os.makedirs(os.path.join(CSRC, "_build"), exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
@@ -60,4 +63,9 @@ def build_library(verbose=True, extra=()):
 
 
 if __name__ == "__main__":
-    build_library(extra=tuple(sys.argv[1:]))
+    # usage: python -m paper_2505_16710_amd.build [-o out.so] [extra hipcc flags, e.g. -DSECO_DKDV_RB=2]
+    argv = sys.argv[1:]
+    out = None
+    if argv[:1] == ["-o"]:
+        out, argv = argv[1], argv[2:]
+    build_library(extra=tuple(argv), out=out)

@@ -27,20 +27,33 @@
 #include "mfma_tiles.h"
 #include "seco_internal.h"
 
+#ifndef SECO_DKDV_RB
+#define SECO_DKDV_RB 2
+#endif
+
 namespace seco {
 namespace {
 
-constexpr int BQ = 32;                                     // query rows per stage
-constexpr int kTileBytes = BQ * kRowBytes;                 // 8 KiB
-constexpr int kStageBytes = 2 * kTileBytes + 2 * BQ * 4;   // Q, dO, lse, delta
+constexpr int kPBytes = 2048;   // one 32x32 bf16 P tile
 constexpr int kStages = 3;
-constexpr int kPBytes = 2048;                              // one 32x32 bf16 P tile
-constexpr int kSmemBytes = kStages * kStageBytes + 2 * 4 * kPBytes;
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// NCB: 32-row column blocks per workgroup (2 wavefronts each); RB: 32-row query blocks per stage
+template <int NCB, int RB>
+struct DkdvCfg {
+  static constexpr int kThreads = NCB * 128;
+  static constexpr int kBQ = 32 * RB;                                   // query rows per stage
+  static constexpr int kTileBytes = kBQ * kRowBytes;
+  static constexpr int kStageBytes = 2 * kTileBytes + 2 * kBQ * 4;      // Q, dO, lse, delta
+  static constexpr int kSmemBytes = kStages * kStageBytes + 2 * NCB * RB * kPBytes;
+  static constexpr int kCols = NCB * 32;                                // cache rows per workgroup
+  static constexpr int kChunksPerThread = (kBQ * 16) / kThreads;        // 16-byte chunks of Q (and of dO) per thread
+};
 
-__global__ __launch_bounds__(512, 1) void dkdv_bf16_kernel(AttnParams p, SegTable seg, int total_items) {
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];   // kSmemBytes, above the 64 KiB static limit
+template <int NCB, int RB>
+__global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, SegTable seg, int total_items) {
+  using Cfg = DkdvCfg<NCB, RB>;
+  constexpr int BQ = Cfg::kBQ, kTileBytes = Cfg::kTileBytes, kStageBytes = Cfg::kStageBytes, NCH = Cfg::kChunksPerThread;
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];   // Cfg::kSmemBytes (can exceed the 64 KiB static limit)
   lds_char* smem = (lds_char*)smem_raw;
   lds_char* pbuf = smem + kStages * kStageBytes;
 
@@ -48,15 +61,15 @@ __global__ __launch_bounds__(512, 1) void dkdv_bf16_kernel(AttnParams p, SegTabl
   if (item < 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
-  const int role = wave >> 2, cb = wave & 3;
+  const int role = wave / NCB, cb = wave % NCB;
   // item -> (batch, kv head, column tile)
   const int n_ctiles = seg.tile_begin[seg.n];
   const int tile = item % n_ctiles;
   const int kvh = (item / n_ctiles) % p.Hkv, b = item / (n_ctiles * p.Hkv);
   int si = 0;
   while (si + 1 < seg.n && tile >= seg.tile_begin[si + 1]) ++si;
-  const int c0 = seg.col_begin[si] + (tile - seg.tile_begin[si]) * kColTileBf16;
-  const int c_end = min(c0 + kColTileBf16, seg.col_end[si]);
+  const int c0 = seg.col_begin[si] + (tile - seg.tile_begin[si]) * Cfg::kCols;
+  const int c_end = min(c0 + Cfg::kCols, seg.col_end[si]);
   const float weight = seg.weight[si];
 
   const int kv_len = p.q_start + p.C;
@@ -69,39 +82,51 @@ __global__ __launch_bounds__(512, 1) void dkdv_bf16_kernel(AttnParams p, SegTabl
 #pragma unroll
   for (int t = 0; t < 8; ++t) frag[t] = *reinterpret_cast<const bf16x8*>(fptr + 16 * t + 8 * g);
 
-  // query-row tiles that see at least one cache row of this workgroup
+  // query-row stages that see at least one cache row of this workgroup; iteration = (head of the group, stage)
   const int rt0 = max(0, c0 - p.q_start) / BQ;
   const int n_rt = (p.C + BQ - 1) / BQ - rt0;
   const int n_iter = n_rt * p.G;
   const float c = p.scale * kLog2e;
-  auto row0_of = [&](int it) { return (rt0 + it % n_rt) * BQ; };
-  // does any row of tile `it` see any cache row of this wavefront?
-  auto live = [&](int it) { return p.q_start + row0_of(it) + BQ - 1 >= n0; };
+  // first chunk-local row of a stage that has a row able to see this wavefront's cache rows
+  const int live_from = n0 - p.q_start - (BQ - 1);
+  struct Pos { int hg, r0; };   // head within the group, first chunk-local row of the stage
+  auto advance = [&](Pos x) {
+    x.r0 += BQ;
+    if (x.r0 >= p.C) { x.r0 = rt0 * BQ; x.hg += 1; }
+    return x;
+  };
 
-  // staging: one 16-byte chunk of Q and one of dO per thread, LSE / delta by the first wavefront
-  bf16x8 qreg, doreg;
+  // staging: NCH 16-byte chunks of Q and of dO per thread, LSE / delta by the first threads
+  bf16x8 qreg[NCH], doreg[NCH];
   float stat = 0.f;
-  auto fetch = [&](int it) {
-    const int h = kvh * p.G + it / n_rt;
-    const int r0 = row0_of(it);
-    const int r = min(r0 + (tid >> 4), p.C - 1), ch = tid & 15;
-    qreg = *reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(p.q) + b * p.qs[0] + h * p.qs[1] +
-                                            (int64_t)r * p.qs[2] + ch * 8);
-    doreg = *reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(p.d_o) + b * p.os[0] + h * p.os[1] +
-                                             (int64_t)r * p.os[2] + ch * 8);
-    if (tid < 64) {
-      const int rr = r0 + (tid & 31);
-      const int64_t idx = ((int64_t)b * p.Hq + h) * p.C + min(rr, p.C - 1);
+  const __bf16* qbase = static_cast<const __bf16*>(p.q) + b * p.qs[0] + (int64_t)kvh * p.G * p.qs[1];
+  const __bf16* dobase = static_cast<const __bf16*>(p.d_o) + b * p.os[0] + (int64_t)kvh * p.G * p.os[1];
+  const int64_t stat_base = ((int64_t)b * p.Hq + (int64_t)kvh * p.G) * p.C;
+  auto fetch = [&](Pos x) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int cid = tid + Cfg::kThreads * i;
+      const int r = min(x.r0 + (cid >> 4), p.C - 1), ch = cid & 15;
+      qreg[i] = *reinterpret_cast<const bf16x8*>(qbase + x.hg * p.qs[1] + (int64_t)r * p.qs[2] + ch * 8);
+      doreg[i] = *reinterpret_cast<const bf16x8*>(dobase + x.hg * p.os[1] + (int64_t)r * p.os[2] + ch * 8);
+    }
+    if (tid < 2 * BQ) {
+      const int rr = x.r0 + (tid % BQ);
+      const int64_t idx = stat_base + (int64_t)x.hg * p.C + min(rr, p.C - 1);
       // rows past the chunk get LSE = +inf so that their probabilities vanish
-      if (tid < 32) stat = rr < p.C ? p.lse[idx] * kLog2e : INFINITY;
+      if (tid < BQ) stat = rr < p.C ? p.lse[idx] * kLog2e : INFINITY;
       else stat = p.delta[idx];
     }
   };
-  auto stash = [&](int it) {
-    lds_char* qt = smem + (it % kStages) * kStageBytes;
-    lds_store16(qt, tid >> 4, tid & 15, qreg);
-    lds_store16(qt + kTileBytes, tid >> 4, tid & 15, doreg);
-    if (tid < 64) *reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes + tid * 4) = stat;
+  auto stash = [&](int slot) {
+    lds_char* qt = smem + slot * kStageBytes;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int cid = tid + Cfg::kThreads * i;
+      lds_store16(qt, cid >> 4, cid & 15, qreg[i]);
+      lds_store16(qt + kTileBytes, cid >> 4, cid & 15, doreg[i]);
+    }
+    if (tid < 2 * BQ) *reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes + tid * 4) = stat;
   };
 
   f32x16 acc[4];   // role A: dV, role B: dK  (32 cache rows x 128)
@@ -109,81 +134,104 @@ __global__ __launch_bounds__(512, 1) void dkdv_bf16_kernel(AttnParams p, SegTabl
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
-  bf16x8 p_cur[2] = {}, p_next[2] = {};   // role A: P of the tile being accumulated / of the next tile
+  bf16x8 p_cur[RB][2] = {}, p_next[RB][2] = {};   // role A: P of the stage being accumulated / of the next stage
 
-  // role A: S = Q K^T for tile `it`, P = exp2(S*c - LSE) with the causal mask, as two operand halves;
-  // the same values go to the partner through pbuf
-  auto scores = [&](int it, bf16x8 (&out)[2]) {
-    lds_char* qt = smem + (it % kStages) * kStageBytes;
-    SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes);
+  // role A: S = Q K^T for row block rb of the stage in `slot`, P = exp2(S*c - LSE) with the causal mask,
+  // as two operand halves; the same values go to the partner through pbuf
+  auto scores = [&](int slot, int parity, int r0, int rb, bf16x8 (&out)[2]) {
+    lds_char* qt = smem + slot * kStageBytes;
+    SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + 32 * rb;
     f32x16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) s = mfma(lds_row8(qt, l32, 2 * t + g), frag[t], s);
-    const int r0 = row0_of(it);
-    const bool diag = n0 + 31 > p.q_start + r0;
+    for (int t = 0; t < 8; ++t) s = mfma(lds_row8(qt, 32 * rb + l32, 2 * t + g), frag[t], s);
+    const int qpos0 = p.q_start + r0 + 32 * rb;
+    const bool diag = n0 + 31 > qpos0;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
       float pr = fast_exp2(__builtin_fmaf(s[r], c, -lse_s[qr]));
-      if (diag && col > p.q_start + r0 + qr) pr = 0.f;
+      if (diag && col > qpos0 + qr) pr = 0.f;
       s[r] = pr;
     }
     out[0] = pack8(s, 0);
     out[1] = pack8(s, 1);
-    lds_char* pb = pbuf + ((it & 1) * 4 + cb) * kPBytes;
+    lds_char* pb = pbuf + ((parity * NCB + cb) * RB + rb) * kPBytes;
     *reinterpret_cast<SECO_LDS bf16x8*>(pb + lane * 16) = out[0];
     *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 + lane * 16) = out[1];
   };
 
-  const int n_pro = min(n_iter, 2);
-  for (int it = 0; it < n_pro; ++it) {
-    fetch(it);
-    stash(it);
+  Pos cur{0, rt0 * BQ};
+  Pos nxt = advance(cur);
+  fetch(cur);
+  stash(0);
+  if (n_iter > 1) {
+    fetch(nxt);
+    stash(1);
   }
   __syncthreads();
-  if (role == 0 && live(0)) scores(0, p_cur);
+  if (role == 0 && cur.r0 >= live_from) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) scores(0, 0, cur.r0, rb, p_cur[rb]);
+  }
   __syncthreads();
+  Pos nxt2 = advance(nxt);
 
+  int slot = 0;   // it % kStages
   for (int it = 0; it < n_iter; ++it) {
-    if (it + 2 < n_iter) fetch(it + 2);
-    lds_char* qt = smem + (it % kStages) * kStageBytes;
+    const int slot1 = slot + 1 == kStages ? 0 : slot + 1;
+    const int slot2 = slot1 + 1 == kStages ? 0 : slot1 + 1;
+    if (it + 2 < n_iter) fetch(nxt2);
+    lds_char* qt = smem + slot * kStageBytes;
     lds_char* dot = qt + kTileBytes;
+    const bool live = cur.r0 >= live_from;
     if (role == 0) {
-      if (it + 1 < n_iter && live(it + 1)) scores(it + 1, p_next);
-      if (live(it)) {
+      const bool live1 = it + 1 < n_iter && nxt.r0 >= live_from;
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+      for (int rb = 0; rb < RB; ++rb) {
+        if (live1) scores(slot1, (it + 1) & 1, nxt.r0, rb, p_next[rb]);
+        if (live) {
 #pragma unroll
-          for (int db = 0; db < 4; ++db) acc[db] = mfma(p_cur[t], lds_tr8(dot, 16 * t, db, lane), acc[db]);
+          for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+              acc[db] = mfma(p_cur[rb][t], lds_tr8(dot, 32 * rb + 16 * t, db, lane), acc[db]);
+        }
+        p_cur[rb][0] = p_next[rb][0];
+        p_cur[rb][1] = p_next[rb][1];
       }
-      p_cur[0] = p_next[0];
-      p_cur[1] = p_next[1];
-    } else if (live(it)) {
+    } else if (live) {
       SECO_LDS float* delta_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + BQ;
-      f32x16 dp;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dp[r] = 0.f;
+      for (int rb = 0; rb < RB; ++rb) {
+        f32x16 dp;
 #pragma unroll
-      for (int t = 0; t < 8; ++t) dp = mfma(lds_row8(dot, l32, 2 * t + g), frag[t], dp);
-      lds_char* pb = pbuf + ((it & 1) * 4 + cb) * kPBytes;
-      const bf16x8 ph[2] = {*reinterpret_cast<SECO_LDS bf16x8*>(pb + lane * 16),
-                            *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 + lane * 16)};
+        for (int r = 0; r < 16; ++r) dp[r] = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
-        dp[r] = (float)ph[r >> 3][r & 7] * (dp[r] - delta_s[qr]);
-      }
+        for (int t = 0; t < 8; ++t) dp = mfma(lds_row8(dot, 32 * rb + l32, 2 * t + g), frag[t], dp);
+        lds_char* pb = pbuf + (((it & 1) * NCB + cb) * RB + rb) * kPBytes;
+        const bf16x8 ph[2] = {*reinterpret_cast<SECO_LDS bf16x8*>(pb + lane * 16),
+                              *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 + lane * 16)};
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const bf16x8 dsa = pack8(dp, t);
+        for (int r = 0; r < 16; ++r) {
+          const int qr = 32 * rb + 8 * (r >> 2) + 4 * g + (r & 3);
+          dp[r] = (float)ph[r >> 3][r & 7] * (dp[r] - delta_s[qr]);
+        }
 #pragma unroll
-        for (int db = 0; db < 4; ++db) acc[db] = mfma(dsa, lds_tr8(qt, 16 * t, db, lane), acc[db]);
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8 dsa = pack8(dp, t);
+#pragma unroll
+          for (int db = 0; db < 4; ++db) acc[db] = mfma(dsa, lds_tr8(qt, 32 * rb + 16 * t, db, lane), acc[db]);
+        }
       }
     }
-    if (it + 2 < n_iter) stash(it + 2);
+    if (it + 2 < n_iter) stash(slot2);
     __syncthreads();
+    cur = nxt;
+    nxt = nxt2;
+    nxt2 = advance(nxt2);
+    slot = slot1;
   }
 
   // exclusive read-modify-write of this workgroup's gK/gV rows: role A adds dV, role B adds s * dK
@@ -202,18 +250,24 @@ __global__ __launch_bounds__(512, 1) void dkdv_bf16_kernel(AttnParams p, SegTabl
 
 }  // namespace
 
-int launch_dkdv_bf16(const AttnParams& p, const SegTable& seg, hipStream_t s) {
-  const int tiles = seg.tile_begin[seg.n];
-  if (tiles == 0) return SECO_OK;
-  const int total = tiles * p.Hkv * p.B;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(dkdv_bf16_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          kSmemBytes) != hipSuccess)
+template <int NCB, int RB>
+int launch_cfg(const AttnParams& p, const SegTable& seg, hipStream_t s) {
+  using Cfg = DkdvCfg<NCB, RB>;
+  const int total = seg.tile_begin[seg.n] * p.Hkv * p.B;
+  auto kern = dkdv_bf16_kernel<NCB, RB>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          Cfg::kSmemBytes) != hipSuccess)
     return SECO_ERR_LAUNCH;
   {
     ProfScope prof(kKernelDkdv, s);
-    hipLaunchKernelGGL(dkdv_bf16_kernel, dim3(xcd_grid(total)), dim3(512), kSmemBytes, s, p, seg, total);
+    hipLaunchKernelGGL(kern, dim3(xcd_grid(total)), dim3(Cfg::kThreads), Cfg::kSmemBytes, s, p, seg, total);
   }
   return launch_status();
+}
+
+int launch_dkdv_bf16(const AttnParams& p, const SegTable& seg, hipStream_t s) {
+  if (seg.tile_begin[seg.n] == 0) return SECO_OK;
+  return launch_cfg<kColTileBf16 / 32, SECO_DKDV_RB>(p, seg, s);
 }
 
 }  // namespace seco

@@ -2,10 +2,12 @@
 // P = exp(S - LSE), dS = P * (dO V^T - delta).  (SpaCO keeps dQ exact: a selected chunk's
 // graph is rebuilt against every earlier cache, Alg. 2.)
 //
-// Same row-parallel decomposition as the forward: a workgroup owns 128 query rows of one
-// head, a wavefront 32 of them, K and V tiles of 64 cache rows stream through swizzled,
-// double-buffered LDS.  Scores are again computed transposed (S^T = K Q^T, dP^T = V dO^T) so
-// that LSE and delta are per-lane scalars and dS^T feeds dQ^T += K^T dS^T from registers;
+// Same row-parallel decomposition as the forward, in the same two workgroup shapes: a workgroup
+// owns 128 query rows of one head, a wavefront 32 of them; K and V tiles stream through
+// swizzled, double-buffered LDS; with KH = 2 (8 wavefronts, 128-row tiles) the two wavefronts
+// of a row block take one 64-row half of every tile each and their partial dQ are added
+// through LDS at the end.  Scores are again computed transposed (S^T = K Q^T, dP^T = V dO^T)
+// so that LSE and delta are per-lane scalars and dS^T feeds dQ^T += K^T dS^T from registers;
 // K^T comes from the same K tile through the LDS transpose read.
 #include "mfma_tiles.h"
 #include "seco_internal.h"
@@ -14,17 +16,21 @@ namespace seco {
 namespace {
 
 constexpr int BM = 128;
-constexpr int BN = 64;
-constexpr int kTileBytes = BN * kRowBytes;
+constexpr int BNW = 64;   // cache rows per wavefront and tile
 
-__global__ __launch_bounds__(256, 2) void dq_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
-  __shared__ __attribute__((aligned(16))) char smem_raw[4 * kTileBytes];
+template <int KH>
+__global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
+  constexpr int BN = BNW * KH;
+  constexpr int kTileBytes = BN * kRowBytes;
+  constexpr int kThreads = 256 * KH;
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];   // 4 * kTileBytes: [buf][K|V]
   lds_char* smem = (lds_char*)smem_raw;
 
   const int item = xcd_item(blockIdx.x, total_items);
   if (item < 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
+  const int rb = wave & 3, kh = wave >> 2;
   const int hg = item % p.G;
   int rest = item / p.G;
   const int mt = n_mtiles - 1 - rest % n_mtiles;
@@ -33,7 +39,7 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(AttnParams p, int n_mti
   const int h = kvh * p.G + hg;
 
   const int kv_len = p.q_start + p.C;
-  const int m0 = mt * BM + wave * 32;
+  const int m0 = mt * BM + rb * 32;
   const int row = m0 + l32;
   const int crow = min(row, p.C - 1);
   const int qpos = p.q_start + row;
@@ -60,7 +66,7 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(AttnParams p, int n_mti
   auto fetch = [&](int n) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int cid = tid + 256 * i, r = cid >> 4, ch = cid & 15;
+      const int cid = tid + kThreads * i, r = cid >> 4, ch = cid & 15;
       const int64_t off = (int64_t)min(n * BN + r, kv_len - 1) * p.kvs[2] + ch * 8;
       kreg[i] = *reinterpret_cast<const bf16x8*>(kbase + off);
       vreg[i] = *reinterpret_cast<const bf16x8*>(vbase + off);
@@ -71,7 +77,7 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(AttnParams p, int n_mti
     lds_char* vt = kt + kTileBytes;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int cid = tid + 256 * i, r = cid >> 4, ch = cid & 15;
+      const int cid = tid + kThreads * i, r = cid >> 4, ch = cid & 15;
       lds_store16(kt, r, ch, kreg[i]);
       lds_store16(vt, r, ch, vreg[i]);
     }
@@ -90,11 +96,11 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(AttnParams p, int n_mti
   for (int n = 0; n < n_tiles; ++n) {
     const int buf = n & 1;
     if (n + 1 < n_tiles) fetch(n + 1);
-    lds_char* kt = smem + buf * 2 * kTileBytes;
+    lds_char* kt = smem + buf * 2 * kTileBytes + kh * BNW * kRowBytes;
     lds_char* vt = kt + kTileBytes;
 #pragma unroll
     for (int kvb = 0; kvb < 2; ++kvb) {
-      const int col0 = n * BN + kvb * 32;
+      const int col0 = n * BN + kh * BNW + kvb * 32;
       if (col0 < wave_kv_end) {
         f32x16 s, dp;
 #pragma unroll
@@ -123,6 +129,31 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(AttnParams p, int n_mti
     __syncthreads();
   }
 
+  if (KH == 2) {
+    // add the partial dQ of the two column halves of each row block through LDS
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    lds_char* slot = smem + rb * (16 * 1024);
+    if (kh == 1) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          f32x4 v = {dq[db][4 * r4], dq[db][4 * r4 + 1], dq[db][4 * r4 + 2], dq[db][4 * r4 + 3]};
+          *reinterpret_cast<SECO_LDS f32x4*>(slot + ((db * 4 + r4) * 64 + lane) * 16) = v;
+        }
+    }
+    __syncthreads();
+    if (kh == 1) return;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const f32x4 v = *reinterpret_cast<SECO_LDS f32x4*>(slot + ((db * 4 + r4) * 64 + lane) * 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dq[db][4 * r4 + i] += v[i];
+      }
+  }
+
   if (row < p.C) {
     __bf16* out = static_cast<__bf16*>(p.d_q) + b * p.qs[0] + h * p.qs[1] + (int64_t)row * p.qs[2];
 #pragma unroll
@@ -137,16 +168,26 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(AttnParams p, int n_mti
   }
 }
 
+template <int KH>
+int launch_kh(const AttnParams& p, int n_mtiles, int total, hipStream_t s) {
+  constexpr int smem = 4 * BNW * KH * kRowBytes;
+  auto kern = dq_bf16_kernel<KH>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
+      hipSuccess)
+    return SECO_ERR_LAUNCH;
+  {
+    ProfScope prof(kKernelDq, s);
+    hipLaunchKernelGGL(kern, dim3(xcd_grid(total)), dim3(256 * KH), smem, s, p, n_mtiles, total);
+  }
+  return launch_status();
+}
+
 }  // namespace
 
 int launch_dq_bf16(const AttnParams& p, hipStream_t s) {
   const int n_mtiles = (p.C + BM - 1) / BM;
   const int total = p.B * p.Hq * n_mtiles;
-  {
-    ProfScope prof(kKernelDq, s);
-    hipLaunchKernelGGL(dq_bf16_kernel, dim3(xcd_grid(total)), dim3(256), 0, s, p, n_mtiles, total);
-  }
-  return launch_status();
+  return total < 2 * kNumCUs ? launch_kh<2>(p, n_mtiles, total, s) : launch_kh<1>(p, n_mtiles, total, s);
 }
 
 }  // namespace seco

@@ -2,11 +2,17 @@
 // O = softmax(s Q K^T) V over cache rows [0, q_start + C) with the causal rule
 // col <= q_start + row, plus the per-row log-sum-exp.
 //
-// Decomposition.  One workgroup (4 wavefronts) owns 128 query rows of one head; each
-// wavefront owns 32 of them and keeps Q^T fragments, the running max / sum and the O^T
-// accumulator (128 x 32, fp32) in registers.  K and V tiles of 64 cache rows stream through a
-// double-buffered, swizzled LDS tile shared by the four wavefronts; the next tile is fetched
-// into registers while the current one is consumed.
+// Decomposition.  A workgroup owns 128 query rows of one head; a wavefront owns 32 of them and
+// keeps Q^T fragments, the running max / sum and the O^T accumulator (128 x 32, fp32) in
+// registers.  K and V tiles stream through a double-buffered, swizzled LDS tile shared by the
+// workgroup; the next tile is fetched into registers while the current one is consumed.
+// Two shapes of workgroup (template parameter KH):
+//   KH = 1: 4 wavefronts, tiles of 64 cache rows, 64 KiB of LDS -> two workgroups per CU;
+//   KH = 2: 8 wavefronts, tiles of 128 cache rows; wavefront (rb, kh) handles row block rb and
+//           the kh-th 64-row half of every tile, and the two partial (max, sum, O) of a row
+//           block are merged through LDS at the end.  One such workgroup fills a CU with two
+//           wavefronts per SIMD, which is what short chunks need (a 1024-row chunk of a
+//           32-head layer has only 256 row tiles for 256 CUs).
 //
 // The score tile is computed transposed, S^T = K Q^T, so that a lane owns one query row
 // (C layout: lane = column): row max / row sum are in-lane reductions plus one exchange with
@@ -20,17 +26,21 @@ namespace seco {
 namespace {
 
 constexpr int BM = 128;  // query rows per workgroup
-constexpr int BN = 64;   // cache rows per tile
-constexpr int kTileBytes = BN * kRowBytes;
+constexpr int BNW = 64;  // cache rows per wavefront and tile
 
-__global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
-  __shared__ __attribute__((aligned(16))) char smem_raw[4 * kTileBytes];
-  lds_char* smem = (lds_char*)smem_raw;  // [buf][K|V]
+template <int KH>
+__global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
+  constexpr int BN = BNW * KH;                 // cache rows per tile
+  constexpr int kTileBytes = BN * kRowBytes;
+  constexpr int kThreads = 256 * KH;
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];   // 4 * kTileBytes: [buf][K|V]
+  lds_char* smem = (lds_char*)smem_raw;
 
   const int item = xcd_item(blockIdx.x, total_items);
   if (item < 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
+  const int rb = wave & 3, kh = wave >> 2;
   // item -> (batch, kv head, row tile (heavy first), head within the group)
   const int hg = item % p.G;
   int rest = item / p.G;
@@ -40,7 +50,7 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(AttnParams p, int n_mt
   const int h = kvh * p.G + hg;
 
   const int kv_len = p.q_start + p.C;
-  const int m0 = mt * BM + wave * 32;          // first chunk-local row of this wavefront
+  const int m0 = mt * BM + rb * 32;            // first chunk-local row of this wavefront
   const int row = m0 + l32;                    // this lane's row
   const int qpos = p.q_start + row;            // its global position
   const __bf16* qptr = static_cast<const __bf16*>(p.q) + b * p.qs[0] + h * p.qs[1] + (int64_t)min(row, p.C - 1) * p.qs[2];
@@ -55,12 +65,12 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(AttnParams p, int n_mt
   const int n_tiles = (wg_kv_end + BN - 1) / BN;
   const int wave_kv_end = m0 < p.C ? p.q_start + min(m0 + 32, p.C) : 0;  // columns this wavefront sees
 
-  // global -> register staging of one K and one V tile: thread owns chunks tid + 256*i
+  // global -> register staging of one K and one V tile: thread owns chunks tid + kThreads*i
   bf16x8 kreg[4], vreg[4];
   auto fetch = [&](int n) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int cid = tid + 256 * i, r = cid >> 4, ch = cid & 15;
+      const int cid = tid + kThreads * i, r = cid >> 4, ch = cid & 15;
       const int64_t off = (int64_t)min(n * BN + r, kv_len - 1) * p.kvs[2] + ch * 8;
       kreg[i] = *reinterpret_cast<const bf16x8*>(kbase + off);
       vreg[i] = *reinterpret_cast<const bf16x8*>(vbase + off);
@@ -71,7 +81,7 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(AttnParams p, int n_mt
     lds_char* vt = kt + kTileBytes;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int cid = tid + 256 * i, r = cid >> 4, ch = cid & 15;
+      const int cid = tid + kThreads * i, r = cid >> 4, ch = cid & 15;
       lds_store16(kt, r, ch, kreg[i]);
       lds_store16(vt, r, ch, vreg[i]);
     }
@@ -92,8 +102,9 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(AttnParams p, int n_mt
   for (int n = 0; n < n_tiles; ++n) {
     const int buf = n & 1;
     if (n + 1 < n_tiles) fetch(n + 1);
-    if (n * BN < wave_kv_end) {
-      lds_char* kt = smem + buf * 2 * kTileBytes;
+    const int col0 = n * BN + kh * BNW;        // first cache row of this wavefront's part of the tile
+    if (col0 < wave_kv_end) {
+      lds_char* kt = smem + buf * 2 * kTileBytes + kh * BNW * kRowBytes;
       lds_char* vt = kt + kTileBytes;
       f32x16 s[2];
 #pragma unroll
@@ -103,12 +114,12 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(AttnParams p, int n_mt
 #pragma unroll
         for (int t = 0; t < 8; ++t) s[kvb] = mfma(lds_row8(kt, kvb * 32 + l32, 2 * t + g), qf[t], s[kvb]);
       }
-      if (n * BN + BN - 1 > p.q_start + m0) {  // tile reaches past this wavefront's first row: causal mask
+      if (col0 + BNW - 1 > p.q_start + m0) {  // reaches past this wavefront's first row: causal mask
 #pragma unroll
         for (int kvb = 0; kvb < 2; ++kvb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const int kv = n * BN + kvb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+            const int kv = col0 + kvb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
             if (kv > qpos) s[kvb][r] = -INFINITY;
           }
       }
@@ -118,14 +129,17 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(AttnParams p, int n_mt
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32));
+      // a part of a tile can be fully masked for a row (only when kh > 0 or q_start is unaligned);
+      // keep the running max finite-or-unchanged so that exp2(-inf - (-inf)) never appears
       const float m_new = fmaxf(m_run, mx * c);
-      const float alpha = fast_exp2(m_run - m_new);
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = fast_exp2(m_run - m_use);
       float sum = 0.f;
 #pragma unroll
       for (int kvb = 0; kvb < 2; ++kvb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float e = fast_exp2(__builtin_fmaf(s[kvb][r], c, -m_new));
+          const float e = fast_exp2(__builtin_fmaf(s[kvb][r], c, -m_use));
           s[kvb][r] = e;
           sum += e;
         }
@@ -148,8 +162,41 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(AttnParams p, int n_mt
     __syncthreads();
   }
 
+  float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (KH == 2) {
+    // merge the two column halves of each row block: kh = 1 publishes (m, l, O), kh = 0 combines
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    lds_char* slot = smem + rb * (17 * 1024);            // 16 KiB of O + 512 B of (m, l) per row block
+    if (kh == 1) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          f32x4 v = {o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]};
+          *reinterpret_cast<SECO_LDS f32x4*>(slot + ((db * 4 + r4) * 64 + lane) * 16) = v;
+        }
+      *reinterpret_cast<SECO_LDS float*>(slot + 16384 + lane * 4) = m_run;
+      *reinterpret_cast<SECO_LDS float*>(slot + 16384 + 256 + lane * 4) = l_tot;
+    }
+    __syncthreads();
+    if (kh == 1) return;
+    const float m1 = *reinterpret_cast<SECO_LDS float*>(slot + 16384 + lane * 4);
+    const float l1 = *reinterpret_cast<SECO_LDS float*>(slot + 16384 + 256 + lane * 4);
+    const float m = fmaxf(m_run, m1);               // finite: half 0 always sees column 0
+    const float a0 = fast_exp2(m_run - m), a1 = fast_exp2(m1 - m);
+    l_tot = l_tot * a0 + l1 * a1;
+    m_run = m;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const f32x4 v = *reinterpret_cast<SECO_LDS f32x4*>(slot + ((db * 4 + r4) * 64 + lane) * 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[db][4 * r4 + i] = o[db][4 * r4 + i] * a0 + v[i] * a1;
+      }
+  }
+
   if (row < p.C) {
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = 1.f / l_tot;
     __bf16* optr = static_cast<__bf16*>(p.o_out) + b * p.os[0] + h * p.os[1] + (int64_t)row * p.os[2];
 #pragma unroll
@@ -165,16 +212,27 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(AttnParams p, int n_mt
   }
 }
 
+template <int KH>
+int launch_kh(const AttnParams& p, int n_mtiles, int total, hipStream_t s) {
+  constexpr int smem = 4 * BNW * KH * kRowBytes;
+  auto kern = fwd_bf16_kernel<KH>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
+      hipSuccess)
+    return SECO_ERR_LAUNCH;
+  {
+    ProfScope prof(kKernelFwd, s);
+    hipLaunchKernelGGL(kern, dim3(xcd_grid(total)), dim3(256 * KH), smem, s, p, n_mtiles, total);
+  }
+  return launch_status();
+}
+
 }  // namespace
 
 int launch_fwd_bf16(const AttnParams& p, hipStream_t s) {
   const int n_mtiles = (p.C + BM - 1) / BM;
   const int total = p.B * p.Hq * n_mtiles;
-  {
-    ProfScope prof(kKernelFwd, s);
-    hipLaunchKernelGGL(fwd_bf16_kernel, dim3(xcd_grid(total)), dim3(256), 0, s, p, n_mtiles, total);
-  }
-  return launch_status();
+  // fewer row tiles than two per CU: use the 8-wavefront shape so that every SIMD still has two wavefronts
+  return total < 2 * kNumCUs ? launch_kh<2>(p, n_mtiles, total, s) : launch_kh<1>(p, n_mtiles, total, s);
 }
 
 }  // namespace seco

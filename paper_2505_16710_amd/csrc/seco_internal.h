@@ -46,7 +46,10 @@ constexpr int kColTileF32 = 4;     // columns per workgroup in launch_dkdv_f32
 int launch_fwd_bf16(const AttnParams& p, hipStream_t s);
 int launch_dq_bf16(const AttnParams& p, hipStream_t s);
 int launch_dkdv_bf16(const AttnParams& p, const SegTable& seg, hipStream_t s);
-constexpr int kColTileBf16 = 128;  // columns per workgroup in launch_dkdv_bf16
+#ifndef SECO_DKDV_COLS
+#define SECO_DKDV_COLS 128
+#endif
+constexpr int kColTileBf16 = SECO_DKDV_COLS;  // columns per workgroup in launch_dkdv_bf16
 
 // delta[r] = sum_d dO[r,d] * O[r,d]
 int launch_delta(const AttnParams& p, int dtype, hipStream_t s);
