@@ -16,11 +16,12 @@
 // wavefronts share a SIMD.  Role A runs one row tile ahead of role B, so the P hand-over
 // costs no extra barrier: one barrier per 32-row tile.
 //
-// Q, dO, LSE and delta of 32 query rows stream through a three-deep ring of swizzled LDS
-// stages (A reads Q of tile i+1 while B reads Q and dO of tile i and tile i+2 is landing).
+// Q, dO, LSE and delta of one stage of query rows stream through a three-deep ring of swizzled LDS
+// stages (A reads Q of stage i+1 while B reads Q and dO of stage i and stage i+2 is landing).
 // S and dP are computed in the "row = query" orientation, so P and dS sit in the C layout
-// with lane = cache row and feed the second products as A operands straight from registers;
-// dO and Q for those products come through the LDS transpose read.
+// with lane = cache row and feed the second products as A operands; dO and Q for those
+// products come through the LDS transpose read.  P is written to LDS once (bf16, in operand
+// order) and read back by both roles, so it costs no registers across stages.
 //
 // Column tiles are enumerated from a by-value segment table (runs of cache rows that share
 // one non-zero weight); SpaCO's unselected chunks simply have no tiles.
@@ -46,13 +47,15 @@ struct DkdvCfg {
   static constexpr int kStageBytes = 2 * kTileBytes + 2 * kBQ * 4;      // Q, dO, lse, delta
   static constexpr int kSmemBytes = kStages * kStageBytes + 2 * NCB * RB * kPBytes;
   static constexpr int kCols = NCB * 32;                                // cache rows per workgroup
-  static constexpr int kChunksPerThread = (kBQ * 16) / kThreads;        // 16-byte chunks of Q (and of dO) per thread
 };
 
 template <int NCB, int RB>
 __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, SegTable seg, int total_items) {
   using Cfg = DkdvCfg<NCB, RB>;
-  constexpr int BQ = Cfg::kBQ, kTileBytes = Cfg::kTileBytes, kStageBytes = Cfg::kStageBytes, NCH = Cfg::kChunksPerThread;
+  constexpr int BQ = Cfg::kBQ, kTileBytes = Cfg::kTileBytes, kStageBytes = Cfg::kStageBytes;
+  constexpr int NW = 2 * NCB;                 // wavefronts
+  constexpr int kCopies = (BQ / 4) / NW;      // 4-row direct copies of Q (and of dO) per wavefront and stage
+  static_assert((BQ / 4) % NW == 0, "stage rows must split evenly over the wavefronts");
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];   // Cfg::kSmemBytes (can exceed the 64 KiB static limit)
   lds_char* smem = (lds_char*)smem_raw;
   lds_char* pbuf = smem + kStages * kStageBytes;
@@ -87,8 +90,6 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   const int n_rt = (p.C + BQ - 1) / BQ - rt0;
   const int n_iter = n_rt * p.G;
   const float c = p.scale * kLog2e;
-  // first chunk-local row of a stage that has a row able to see this wavefront's cache rows
-  const int live_from = n0 - p.q_start - (BQ - 1);
   struct Pos { int hg, r0; };   // head within the group, first chunk-local row of the stage
   auto advance = [&](Pos x) {
     x.r0 += BQ;
@@ -96,19 +97,19 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     return x;
   };
 
-  // staging: NCH 16-byte chunks of Q and of dO per thread, LSE / delta by the first threads
-  bf16x8 qreg[NCH], doreg[NCH];
-  float stat = 0.f;
   const __bf16* qbase = static_cast<const __bf16*>(p.q) + b * p.qs[0] + (int64_t)kvh * p.G * p.qs[1];
   const __bf16* dobase = static_cast<const __bf16*>(p.d_o) + b * p.os[0] + (int64_t)kvh * p.G * p.os[1];
   const int64_t stat_base = ((int64_t)b * p.Hq + (int64_t)kvh * p.G) * p.C;
-  auto fetch = [&](Pos x) {
+  // staging through registers: kCopies 16-byte chunks of Q and of dO per thread (4 rows per wavefront and
+  // copy), plus LSE (scaled to log2 units) and delta of the stage on threads 0 .. 2*BQ-1
+  bf16x8 qreg[kCopies], doreg[kCopies];
+  float stat = 0.f;
+  auto fetch_stat = [&](Pos x) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int cid = tid + Cfg::kThreads * i;
-      const int r = min(x.r0 + (cid >> 4), p.C - 1), ch = cid & 15;
-      qreg[i] = *reinterpret_cast<const bf16x8*>(qbase + x.hg * p.qs[1] + (int64_t)r * p.qs[2] + ch * 8);
-      doreg[i] = *reinterpret_cast<const bf16x8*>(dobase + x.hg * p.os[1] + (int64_t)r * p.os[2] + ch * 8);
+    for (int i = 0; i < kCopies; ++i) {
+      const int src_row = min(x.r0 + 4 * (wave + NW * i) + (lane >> 4), p.C - 1), ch = lane & 15;
+      qreg[i] = *reinterpret_cast<const bf16x8*>(qbase + x.hg * p.qs[1] + (int64_t)src_row * p.qs[2] + ch * 8);
+      doreg[i] = *reinterpret_cast<const bf16x8*>(dobase + x.hg * p.os[1] + (int64_t)src_row * p.os[2] + ch * 8);
     }
     if (tid < 2 * BQ) {
       const int rr = x.r0 + (tid % BQ);
@@ -118,15 +119,15 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       else stat = p.delta[idx];
     }
   };
-  auto stash = [&](int slot) {
+  auto stash_stat = [&](int slot) {
     lds_char* qt = smem + slot * kStageBytes;
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int cid = tid + Cfg::kThreads * i;
-      lds_store16(qt, cid >> 4, cid & 15, qreg[i]);
-      lds_store16(qt + kTileBytes, cid >> 4, cid & 15, doreg[i]);
+    for (int i = 0; i < kCopies; ++i) {
+      const int r = 4 * (wave + NW * i) + (lane >> 4);
+      lds_store16(qt, r, lane & 15, qreg[i]);
+      lds_store16(qt + kTileBytes, r, lane & 15, doreg[i]);
     }
-    if (tid < 2 * BQ) *reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes + tid * 4) = stat;
+    if (tid < 2 * BQ) *reinterpret_cast<SECO_LDS float*>(smem + slot * kStageBytes + 2 * kTileBytes + tid * 4) = stat;
   };
 
   f32x16 acc[4];   // role A: dV, role B: dK  (32 cache rows x 128)
@@ -134,46 +135,54 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
-  bf16x8 p_cur[RB][2] = {}, p_next[RB][2] = {};   // role A: P of the stage being accumulated / of the next stage
 
-  // role A: S = Q K^T for row block rb of the stage in `slot`, P = exp2(S*c - LSE) with the causal mask,
-  // as two operand halves; the same values go to the partner through pbuf
-  auto scores = [&](int slot, int parity, int r0, int rb, bf16x8 (&out)[2]) {
+  auto pslot = [&](int parity, int rb) { return pbuf + ((parity * NCB + cb) * RB + rb) * kPBytes; };
+
+  // role A: S = Q K^T for row block rb of the stage in `slot`, P = exp2(S*c - LSE) with the causal mask;
+  // P goes to pbuf as two operand halves (lane-contiguous 16-byte words)
+  auto scores = [&](int slot, int parity, int r0, int rb) {
     lds_char* qt = smem + slot * kStageBytes;
     SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + 32 * rb;
+    bf16x8 a[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) a[t] = lds_row8(qt, 32 * rb + l32, 2 * t + g);
     f32x16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) s = mfma(lds_row8(qt, 32 * rb + l32, 2 * t + g), frag[t], s);
-    const int qpos0 = p.q_start + r0 + 32 * rb;
-    const bool diag = n0 + 31 > qpos0;
+    for (int t = 0; t < 8; ++t) s = mfma(a[t], frag[t], s);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
-      float pr = fast_exp2(__builtin_fmaf(s[r], c, -lse_s[qr]));
-      if (diag && col > qpos0 + qr) pr = 0.f;
-      s[r] = pr;
+      s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_s[qr]));
     }
-    out[0] = pack8(s, 0);
-    out[1] = pack8(s, 1);
-    lds_char* pb = pbuf + ((parity * NCB + cb) * RB + rb) * kPBytes;
-    *reinterpret_cast<SECO_LDS bf16x8*>(pb + lane * 16) = out[0];
-    *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 + lane * 16) = out[1];
+    const int qpos0 = p.q_start + r0 + 32 * rb;
+    if (n0 + 31 > qpos0) {   // the block touches the diagonal: zero what lies above it
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
+        if (col > qpos0 + qr) s[r] = 0.f;
+      }
+    }
+    lds_char* pb = pslot(parity, rb);
+    *reinterpret_cast<SECO_LDS bf16x8*>(pb + lane * 16) = pack8(s, 0);
+    *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 + lane * 16) = pack8(s, 1);
   };
 
   Pos cur{0, rt0 * BQ};
   Pos nxt = advance(cur);
-  fetch(cur);
-  stash(0);
+  fetch_stat(cur);
+  stash_stat(0);
   if (n_iter > 1) {
-    fetch(nxt);
-    stash(1);
+    fetch_stat(nxt);
+    stash_stat(1);
   }
   __syncthreads();
+  // first chunk-local row from which a stage has a row able to see this wavefront's cache rows
+  const int live_from = n0 - p.q_start - (BQ - 1);
   if (role == 0 && cur.r0 >= live_from) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) scores(0, 0, cur.r0, rb, p_cur[rb]);
+    for (int rb = 0; rb < RB; ++rb) scores(0, 0, cur.r0, rb);
   }
   __syncthreads();
   Pos nxt2 = advance(nxt);
@@ -182,7 +191,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   for (int it = 0; it < n_iter; ++it) {
     const int slot1 = slot + 1 == kStages ? 0 : slot + 1;
     const int slot2 = slot1 + 1 == kStages ? 0 : slot1 + 1;
-    if (it + 2 < n_iter) fetch(nxt2);
+    if (it + 2 < n_iter) fetch_stat(nxt2);
     lds_char* qt = smem + slot * kStageBytes;
     lds_char* dot = qt + kTileBytes;
     const bool live = cur.r0 >= live_from;
@@ -190,27 +199,33 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       const bool live1 = it + 1 < n_iter && nxt.r0 >= live_from;
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
-        if (live1) scores(slot1, (it + 1) & 1, nxt.r0, rb, p_next[rb]);
+        if (live1) scores(slot1, (it + 1) & 1, nxt.r0, rb);
         if (live) {
+          lds_char* pb = pslot(it & 1, rb);
 #pragma unroll
-          for (int t = 0; t < 2; ++t)
+          for (int t = 0; t < 2; ++t) {
+            const bf16x8 pa = *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 * t + lane * 16);
+            bf16x8 bo[4];
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
-              acc[db] = mfma(p_cur[rb][t], lds_tr8(dot, 32 * rb + 16 * t, db, lane), acc[db]);
+            for (int db = 0; db < 4; ++db) bo[db] = lds_tr8(dot, 32 * rb + 16 * t, db, lane);
+#pragma unroll
+            for (int db = 0; db < 4; ++db) acc[db] = mfma(pa, bo[db], acc[db]);
+          }
         }
-        p_cur[rb][0] = p_next[rb][0];
-        p_cur[rb][1] = p_next[rb][1];
       }
     } else if (live) {
       SECO_LDS float* delta_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + BQ;
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
+        bf16x8 a[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) a[t] = lds_row8(dot, 32 * rb + l32, 2 * t + g);
         f32x16 dp;
 #pragma unroll
         for (int r = 0; r < 16; ++r) dp[r] = 0.f;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) dp = mfma(lds_row8(dot, 32 * rb + l32, 2 * t + g), frag[t], dp);
-        lds_char* pb = pbuf + (((it & 1) * NCB + cb) * RB + rb) * kPBytes;
+        for (int t = 0; t < 8; ++t) dp = mfma(a[t], frag[t], dp);
+        lds_char* pb = pslot(it & 1, rb);
         const bf16x8 ph[2] = {*reinterpret_cast<SECO_LDS bf16x8*>(pb + lane * 16),
                               *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 + lane * 16)};
 #pragma unroll
@@ -221,12 +236,15 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const bf16x8 dsa = pack8(dp, t);
+          bf16x8 bq[4];
 #pragma unroll
-          for (int db = 0; db < 4; ++db) acc[db] = mfma(dsa, lds_tr8(qt, 32 * rb + 16 * t, db, lane), acc[db]);
+          for (int db = 0; db < 4; ++db) bq[db] = lds_tr8(qt, 32 * rb + 16 * t, db, lane);
+#pragma unroll
+          for (int db = 0; db < 4; ++db) acc[db] = mfma(dsa, bq[db], acc[db]);
         }
       }
     }
-    if (it + 2 < n_iter) stash(slot2);
+    if (it + 2 < n_iter) stash_stat(slot2);
     __syncthreads();
     cur = nxt;
     nxt = nxt2;

@@ -68,12 +68,30 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// registers 8t .. 8t+7 of a C tile, rounded to bf16, as an operand over 16 contraction steps
+// registers 8t .. 8t+7 of a C tile, rounded to bf16 (pairwise, one v_cvt_pk_bf16_f32 per pair),
+// as an operand over 16 contraction steps
 __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int t) {
-  bf16x8 r;
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 r;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) r[i] = (__bf16)x[8 * t + i];
-  return r;
+  for (int i = 0; i < 4; ++i) {
+    const f32x2 v = {x[8 * t + 2 * i], x[8 * t + 2 * i + 1]};
+    r[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+  }
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// Asynchronous copy of four 256-byte rows (rows r .. r+3 of a swizzled tile) from global memory
+// straight into LDS (global_load_lds_dwordx4: lane i's 16 bytes land at dst + 16*i).  `row_ptr`
+// is this lane's source row (lane / 16 selects the row), already clamped by the caller; the
+// swizzle is applied by choosing which 16-byte chunk of the row the lane fetches.
+__device__ __forceinline__ void copy4rows_g2lds(lds_char* dst_tile, int r, const __bf16* row_ptr, int lane) {
+  const int row = r + (lane >> 4);
+  const int chunk = (lane & 15) ^ swz(row);
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(row_ptr + chunk * 8),
+                                   reinterpret_cast<SECO_LDS void*>(dst_tile + r * kRowBytes), 16, 0, 0);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
