@@ -38,6 +38,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-layer32k", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events in the timed region")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch kvgrad_accumulate on a 1 GiB pair of buffers (a plain streaming kernel of known "
+                         "size: reads 2 GiB, writes 1 GiB) so that rocprofv3 FETCH_SIZE / WRITE_SIZE can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (one process, one MI355X); run with --gpus 1")
@@ -221,6 +224,16 @@ def main():
                                "sample": f"fp64 NumPy oracle, fwd+bwd of the last {done} chunk calls of one (batch, KV head) "
                                          f"unit of {cfg.name} ({Hq // Hkv} query heads), {el:.1f} s",
                                "host_cores_available": len(os.sched_getaffinity(0))}
+
+    if args.calibrate_copy:
+        n_rows = (1 << 30) // (Hkv * D * 4)
+        dst = torch.zeros(1, Hkv, n_rows, D, device=dev, dtype=torch.float32)
+        src = torch.ones_like(dst)
+        for _ in range(3):
+            seco.kvgrad_accumulate(dst, None, src, None, 0.5)
+        torch.cuda.synchronize()
+        out["calibration"] = {"kernel": "kvgrad_kernel<true>", "launches": 3, "read_bytes_per_launch": 2 * dst.numel() * 4,
+                              "write_bytes_per_launch": dst.numel() * 4}
 
     print(json.dumps(out))
 
