@@ -17,7 +17,8 @@
 // costs no extra barrier: one barrier per 32-row tile.
 //
 // Q, dO, LSE and delta of one stage of query rows stream through a three-deep ring of swizzled LDS
-// stages (A reads Q of stage i+1 while B reads Q and dO of stage i and stage i+2 is landing).
+// stages (A reads Q of stage i+1 while B reads Q and dO of stage i and stage i+2 is landing);
+// Q and dO are copied global -> LDS directly (no staging registers), issued two stages ahead.
 // S and dP are computed in the "row = query" orientation, so P and dS sit in the C layout
 // with lane = cache row and feed the second products as A operands; dO and Q for those
 // products come through the LDS transpose read.  P is written to LDS once (bf16, in operand
@@ -100,17 +101,20 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   const __bf16* qbase = static_cast<const __bf16*>(p.q) + b * p.qs[0] + (int64_t)kvh * p.G * p.qs[1];
   const __bf16* dobase = static_cast<const __bf16*>(p.d_o) + b * p.os[0] + (int64_t)kvh * p.G * p.os[1];
   const int64_t stat_base = ((int64_t)b * p.Hq + (int64_t)kvh * p.G) * p.C;
-  // staging through registers: kCopies 16-byte chunks of Q and of dO per thread (4 rows per wavefront and
-  // copy), plus LSE (scaled to log2 units) and delta of the stage on threads 0 .. 2*BQ-1
-  bf16x8 qreg[kCopies], doreg[kCopies];
-  float stat = 0.f;
-  auto fetch_stat = [&](Pos x) {
+  // asynchronous global -> LDS copy of the Q and dO tiles of one stage (4 rows per wavefront and copy)
+  auto copy_stage = [&](Pos x, int slot) {
+    lds_char* qt = smem + slot * kStageBytes;
 #pragma unroll
     for (int i = 0; i < kCopies; ++i) {
-      const int src_row = min(x.r0 + 4 * (wave + NW * i) + (lane >> 4), p.C - 1), ch = lane & 15;
-      qreg[i] = *reinterpret_cast<const bf16x8*>(qbase + x.hg * p.qs[1] + (int64_t)src_row * p.qs[2] + ch * 8);
-      doreg[i] = *reinterpret_cast<const bf16x8*>(dobase + x.hg * p.os[1] + (int64_t)src_row * p.os[2] + ch * 8);
+      const int r = 4 * (wave + NW * i);
+      const int src_row = min(x.r0 + r + (lane >> 4), p.C - 1);
+      dma4rows(qt, r, qbase + x.hg * p.qs[1] + (int64_t)src_row * p.qs[2], lane);
+      dma4rows(qt + kTileBytes, r, dobase + x.hg * p.os[1] + (int64_t)src_row * p.os[2], lane);
     }
+  };
+  // LSE (scaled to log2 units) and delta of the stage go through a register: threads 0 .. 2*BQ-1
+  float stat = 0.f;
+  auto fetch_stat = [&](Pos x) {
     if (tid < 2 * BQ) {
       const int rr = x.r0 + (tid % BQ);
       const int64_t idx = stat_base + (int64_t)x.hg * p.C + min(rr, p.C - 1);
@@ -120,13 +124,6 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     }
   };
   auto stash_stat = [&](int slot) {
-    lds_char* qt = smem + slot * kStageBytes;
-#pragma unroll
-    for (int i = 0; i < kCopies; ++i) {
-      const int r = 4 * (wave + NW * i) + (lane >> 4);
-      lds_store16(qt, r, lane & 15, qreg[i]);
-      lds_store16(qt + kTileBytes, r, lane & 15, doreg[i]);
-    }
     if (tid < 2 * BQ) *reinterpret_cast<SECO_LDS float*>(smem + slot * kStageBytes + 2 * kTileBytes + tid * 4) = stat;
   };
 
@@ -171,12 +168,15 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 
   Pos cur{0, rt0 * BQ};
   Pos nxt = advance(cur);
+  copy_stage(cur, 0);
   fetch_stat(cur);
   stash_stat(0);
   if (n_iter > 1) {
+    copy_stage(nxt, 1);
     fetch_stat(nxt);
     stash_stat(1);
   }
+  dma_wait_all();
   __syncthreads();
   // first chunk-local row from which a stage has a row able to see this wavefront's cache rows
   const int live_from = n0 - p.q_start - (BQ - 1);
@@ -191,7 +191,10 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   for (int it = 0; it < n_iter; ++it) {
     const int slot1 = slot + 1 == kStages ? 0 : slot + 1;
     const int slot2 = slot1 + 1 == kStages ? 0 : slot1 + 1;
-    if (it + 2 < n_iter) fetch_stat(nxt2);
+    if (it + 2 < n_iter) {
+      copy_stage(nxt2, slot2);
+      fetch_stat(nxt2);
+    }
     lds_char* qt = smem + slot * kStageBytes;
     lds_char* dot = qt + kTileBytes;
     const bool live = cur.r0 >= live_from;
@@ -245,6 +248,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       }
     }
     if (it + 2 < n_iter) stash_stat(slot2);
+    dma_wait_all();
     __syncthreads();
     cur = nxt;
     nxt = nxt2;

@@ -4,7 +4,7 @@
 //
 // Same row-parallel decomposition as the forward, in the same two workgroup shapes: a workgroup
 // owns 128 query rows of one head, a wavefront 32 of them; K and V tiles stream through
-// swizzled, double-buffered LDS; with KH = 2 (8 wavefronts, 128-row tiles) the two wavefronts
+// swizzled, double-buffered LDS, copied global -> LDS directly one tile ahead; with KH = 2 (8 wavefronts, 128-row tiles) the two wavefronts
 // of a row block take one 64-row half of every tile each and their partial dQ are added
 // through LDS at the end.  Scores are again computed transposed (S^T = K Q^T, dP^T = V dO^T)
 // so that LSE and delta are per-lane scalars and dS^T feeds dQ^T += K^T dS^T from registers;
@@ -22,7 +22,6 @@ template <int KH>
 __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
   constexpr int BN = BNW * KH;
   constexpr int kTileBytes = BN * kRowBytes;
-  constexpr int kThreads = 256 * KH;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];   // 4 * kTileBytes: [buf][K|V]
   lds_char* smem = (lds_char*)smem_raw;
 
@@ -62,24 +61,16 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
   const int n_tiles = (wg_kv_end + BN - 1) / BN;
   const int wave_kv_end = m0 < p.C ? p.q_start + min(m0 + 32, p.C) : 0;
 
-  bf16x8 kreg[4], vreg[4];
-  auto fetch = [&](int n) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int cid = tid + kThreads * i, r = cid >> 4, ch = cid & 15;
-      const int64_t off = (int64_t)min(n * BN + r, kv_len - 1) * p.kvs[2] + ch * 8;
-      kreg[i] = *reinterpret_cast<const bf16x8*>(kbase + off);
-      vreg[i] = *reinterpret_cast<const bf16x8*>(vbase + off);
-    }
-  };
-  auto stash = [&](int buf) {
+  // asynchronous global -> LDS copy of one K and one V tile: each wavefront copies 4 groups of 4 rows of each
+  auto copy_tile = [&](int n, int buf) {
     lds_char* kt = smem + buf * 2 * kTileBytes;
     lds_char* vt = kt + kTileBytes;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int cid = tid + kThreads * i, r = cid >> 4, ch = cid & 15;
-      lds_store16(kt, r, ch, kreg[i]);
-      lds_store16(vt, r, ch, vreg[i]);
+      const int r = 4 * (wave + 4 * KH * i);
+      const int64_t off = (int64_t)min(n * BN + r + (lane >> 4), kv_len - 1) * p.kvs[2];
+      dma4rows(kt, r, kbase + off, lane);
+      dma4rows(vt, r, vbase + off, lane);
     }
   };
 
@@ -89,13 +80,13 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
 
-  fetch(0);
-  stash(0);
+  copy_tile(0, 0);
+  dma_wait_all();
   __syncthreads();
 
   for (int n = 0; n < n_tiles; ++n) {
     const int buf = n & 1;
-    if (n + 1 < n_tiles) fetch(n + 1);
+    if (n + 1 < n_tiles) copy_tile(n + 1, buf ^ 1);
     lds_char* kt = smem + buf * 2 * kTileBytes + kh * BNW * kRowBytes;
     lds_char* vt = kt + kTileBytes;
 #pragma unroll
@@ -125,7 +116,7 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
         }
       }
     }
-    if (n + 1 < n_tiles) stash(buf ^ 1);
+    dma_wait_all();
     __syncthreads();
   }
 

@@ -5,7 +5,7 @@
 // Decomposition.  A workgroup owns 128 query rows of one head; a wavefront owns 32 of them and
 // keeps Q^T fragments, the running max / sum and the O^T accumulator (128 x 32, fp32) in
 // registers.  K and V tiles stream through a double-buffered, swizzled LDS tile shared by the
-// workgroup; the next tile is fetched into registers while the current one is consumed.
+// workgroup; the next tile is copied global -> LDS directly while the current one is consumed.
 // Two shapes of workgroup (template parameter KH):
 //   KH = 1: 4 wavefronts, tiles of 64 cache rows, 64 KiB of LDS -> two workgroups per CU;
 //   KH = 2: 8 wavefronts, tiles of 128 cache rows; wavefront (rb, kh) handles row block rb and
@@ -32,7 +32,6 @@ template <int KH>
 __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
   constexpr int BN = BNW * KH;                 // cache rows per tile
   constexpr int kTileBytes = BN * kRowBytes;
-  constexpr int kThreads = 256 * KH;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];   // 4 * kTileBytes: [buf][K|V]
   lds_char* smem = (lds_char*)smem_raw;
 
@@ -65,25 +64,16 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
   const int n_tiles = (wg_kv_end + BN - 1) / BN;
   const int wave_kv_end = m0 < p.C ? p.q_start + min(m0 + 32, p.C) : 0;  // columns this wavefront sees
 
-  // global -> register staging of one K and one V tile: thread owns chunks tid + kThreads*i
-  bf16x8 kreg[4], vreg[4];
-  auto fetch = [&](int n) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int cid = tid + kThreads * i, r = cid >> 4, ch = cid & 15;
-      const int64_t off = (int64_t)min(n * BN + r, kv_len - 1) * p.kvs[2] + ch * 8;
-      kreg[i] = *reinterpret_cast<const bf16x8*>(kbase + off);
-      vreg[i] = *reinterpret_cast<const bf16x8*>(vbase + off);
-    }
-  };
-  auto stash = [&](int buf) {
+  // asynchronous global -> LDS copy of one K and one V tile: each wavefront copies 4 groups of 4 rows of each
+  auto copy_tile = [&](int n, int buf) {
     lds_char* kt = smem + buf * 2 * kTileBytes;
     lds_char* vt = kt + kTileBytes;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int cid = tid + kThreads * i, r = cid >> 4, ch = cid & 15;
-      lds_store16(kt, r, ch, kreg[i]);
-      lds_store16(vt, r, ch, vreg[i]);
+      const int r = 4 * (wave + 4 * KH * i);
+      const int64_t off = (int64_t)min(n * BN + r + (lane >> 4), kv_len - 1) * p.kvs[2];
+      dma4rows(kt, r, kbase + off, lane);
+      dma4rows(vt, r, vbase + off, lane);
     }
   };
 
@@ -95,13 +85,13 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
   float m_run = -INFINITY, l_run = 0.f;
   const float c = p.scale * kLog2e;
 
-  fetch(0);
-  stash(0);
+  copy_tile(0, 0);
+  dma_wait_all();
   __syncthreads();
 
   for (int n = 0; n < n_tiles; ++n) {
     const int buf = n & 1;
-    if (n + 1 < n_tiles) fetch(n + 1);
+    if (n + 1 < n_tiles) copy_tile(n + 1, buf ^ 1);
     const int col0 = n * BN + kh * BNW;        // first cache row of this wavefront's part of the tile
     if (col0 < wave_kv_end) {
       lds_char* kt = smem + buf * 2 * kTileBytes + kh * BNW * kRowBytes;
@@ -158,7 +148,7 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
           for (int db = 0; db < 4; ++db) o[db] = mfma(lds_tr8(vt, kvb * 32 + 16 * t, db, lane), pb, o[db]);
         }
     }
-    if (n + 1 < n_tiles) stash(buf ^ 1);
+    dma_wait_all();
     __syncthreads();
   }
 

@@ -83,16 +83,21 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int t) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
-// Asynchronous copy of four 256-byte rows (rows r .. r+3 of a swizzled tile) from global memory
-// straight into LDS (global_load_lds_dwordx4: lane i's 16 bytes land at dst + 16*i).  `row_ptr`
-// is this lane's source row (lane / 16 selects the row), already clamped by the caller; the
-// swizzle is applied by choosing which 16-byte chunk of the row the lane fetches.
-__device__ __forceinline__ void copy4rows_g2lds(lds_char* dst_tile, int r, const __bf16* row_ptr, int lane) {
+// Asynchronous copy of four 256-byte rows (rows r .. r+3 of a swizzled tile, r wavefront-uniform)
+// from global memory straight into LDS with global_load_lds_dwordx4: lane i's 16 bytes land at
+// dst + 16*i, so the swizzle is applied by choosing which 16-byte chunk of its source row the
+// lane fetches.  `row_ptr` is this lane's source row (lane / 16 selects the row), already
+// clamped by the caller.  The copy is tracked by vmcnt only: the issuing wavefront must call
+// dma_wait_all() before the barrier that publishes the tile.  (Issued as inline assembly on
+// purpose: with the compiler builtin every later LDS read in the loop is made to wait for the
+// copy, because the destination cannot be told apart from the tiles being read.)
+__device__ __forceinline__ void dma4rows(lds_char* dst_tile, int r, const __bf16* row_ptr, int lane) {
   const int row = r + (lane >> 4);
   const int chunk = (lane & 15) ^ swz(row);
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(row_ptr + chunk * 8),
-                                   reinterpret_cast<SECO_LDS void*>(dst_tile + r * kRowBytes), 16, 0, 0);
+  const uint32_t m = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(dst_tile + r * kRowBytes));
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(row_ptr + chunk * 8), "s"(m) : "memory", "m0");
 }
+__device__ __forceinline__ void dma_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
