@@ -50,6 +50,7 @@ struct DkdvCfg {
   static constexpr int kCols = NCB * 32;                                // cache rows per workgroup
 };
 
+// (RB is fixed to 2 by the hand-pipelined main loop.)
 template <int NCB, int RB>
 __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, SegTable seg, int total_items) {
   using Cfg = DkdvCfg<NCB, RB>;
@@ -135,6 +136,17 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 
   auto pslot = [&](int parity, int rb) { return pbuf + ((parity * NCB + cb) * RB + rb) * kPBytes; };
 
+  // zero the probabilities of a 32x32 block (first query position qpos0) that lie above the diagonal
+  auto mask_above_diagonal = [&](f32x16& s, int qpos0) {
+    if (n0 + 31 > qpos0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
+        if (col > qpos0 + qr) s[r] = 0.f;
+      }
+    }
+  };
+
   // role A: S = Q K^T for row block rb of the stage in `slot`, P = exp2(S*c - LSE) with the causal mask;
   // P goes to pbuf as two operand halves (lane-contiguous 16-byte words)
   auto scores = [&](int slot, int parity, int r0, int rb) {
@@ -153,14 +165,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
       s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_s[qr]));
     }
-    const int qpos0 = p.q_start + r0 + 32 * rb;
-    if (n0 + 31 > qpos0) {   // the block touches the diagonal: zero what lies above it
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
-        if (col > qpos0 + qr) s[r] = 0.f;
-      }
-    }
+    mask_above_diagonal(s, p.q_start + r0 + 32 * rb);
     lds_char* pb = pslot(parity, rb);
     *reinterpret_cast<SECO_LDS bf16x8*>(pb + lane * 16) = pack8(s, 0);
     *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 + lane * 16) = pack8(s, 1);
@@ -176,11 +181,11 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     fetch_stat(nxt);
     stash_stat(1);
   }
+#pragma unroll
+  for (int t = 0; t < 8; ++t) settle(frag[t]);
   dma_wait_all();
   __syncthreads();
-  // first chunk-local row from which a stage has a row able to see this wavefront's cache rows
-  const int live_from = n0 - p.q_start - (BQ - 1);
-  if (role == 0 && cur.r0 >= live_from) {
+  if (role == 0) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) scores(0, 0, cur.r0, rb);
   }
@@ -197,54 +202,112 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     }
     lds_char* qt = smem + slot * kStageBytes;
     lds_char* dot = qt + kTileBytes;
-    const bool live = cur.r0 >= live_from;
-    if (role == 0) {
-      const bool live1 = it + 1 < n_iter && nxt.r0 >= live_from;
+    // The two 32-row blocks of the stage are software-pipelined by hand: LDS operands of a phase are
+    // requested one phase ahead of the MFMA chain that consumes them.  Row blocks above the diagonal are
+    // not skipped: their probabilities are masked to zero and contribute nothing (only the first stages of
+    // a diagonal column tile are affected).
+    {
+      // One operand buffer x[8] rotates through the four phases of the iteration: while the MFMA chain of a
+      // phase consumes x[t], the operand of the next phase is requested into the same register.
+      bf16x8 x[8];
+      auto p_half = [&](lds_char* pb, int t) { return *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 * t + lane * 16); };
+      if (role == 0) {
+        lds_char* qt1 = smem + slot1 * kStageBytes;
+        SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt1 + 2 * kTileBytes);
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        if (live1) scores(slot1, (it + 1) & 1, nxt.r0, rb);
-        if (live) {
-          lds_char* pb = pslot(it & 1, rb);
+        for (int t = 0; t < 8; ++t) x[t] = lds_row8(qt1, l32, 2 * t + g);
+        f32x16 s;
 #pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            const bf16x8 pa = *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 * t + lane * 16);
-            bf16x8 bo[4];
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+        // S of row block 0; Q rows of row block 1 come in behind
 #pragma unroll
-            for (int db = 0; db < 4; ++db) bo[db] = lds_tr8(dot, 32 * rb + 16 * t, db, lane);
-#pragma unroll
-            for (int db = 0; db < 4; ++db) acc[db] = mfma(pa, bo[db], acc[db]);
-          }
+        for (int t = 0; t < 8; ++t) {
+          s = mfma(x[t], frag[t], s);
+          x[t] = lds_row8(qt1, 32 + l32, 2 * t + g);
         }
-      }
-    } else if (live) {
-      SECO_LDS float* delta_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + BQ;
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        bf16x8 a[8];
-#pragma unroll
-        for (int t = 0; t < 8; ++t) a[t] = lds_row8(dot, 32 * rb + l32, 2 * t + g);
-        f32x16 dp;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dp[r] = 0.f;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) dp = mfma(a[t], frag[t], dp);
-        lds_char* pb = pslot(it & 1, rb);
-        const bf16x8 ph[2] = {*reinterpret_cast<SECO_LDS bf16x8*>(pb + lane * 16),
-                              *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 + lane * 16)};
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int qr = 32 * rb + 8 * (r >> 2) + 4 * g + (r & 3);
-          dp[r] = (float)ph[r >> 3][r & 7] * (dp[r] - delta_s[qr]);
+          const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
+          s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_s[qr]));
+        }
+        mask_above_diagonal(s, p.q_start + nxt.r0);
+        lds_char* pn0 = pslot((it + 1) & 1, 0);
+        *reinterpret_cast<SECO_LDS bf16x8*>(pn0 + lane * 16) = pack8(s, 0);
+        *reinterpret_cast<SECO_LDS bf16x8*>(pn0 + 1024 + lane * 16) = pack8(s, 1);
+        lds_char* pb0 = pslot(it & 1, 0);
+        const bf16x8 pa0[2] = {p_half(pb0, 0), p_half(pb0, 1)};
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+        // S of row block 1; dO^T of row block 0 (stage `it`) comes in behind
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          s = mfma(x[t], frag[t], s);
+          x[t] = lds_tr8(dot, 16 * (t >> 2), t & 3, lane);
         }
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 dsa = pack8(dp, t);
-          bf16x8 bq[4];
-#pragma unroll
-          for (int db = 0; db < 4; ++db) bq[db] = lds_tr8(qt, 32 * rb + 16 * t, db, lane);
-#pragma unroll
-          for (int db = 0; db < 4; ++db) acc[db] = mfma(dsa, bq[db], acc[db]);
+        for (int r = 0; r < 16; ++r) {
+          const int qr = 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_s[qr]));
         }
+        mask_above_diagonal(s, p.q_start + nxt.r0 + 32);
+        lds_char* pn1 = pslot((it + 1) & 1, 1);
+        *reinterpret_cast<SECO_LDS bf16x8*>(pn1 + lane * 16) = pack8(s, 0);
+        *reinterpret_cast<SECO_LDS bf16x8*>(pn1 + 1024 + lane * 16) = pack8(s, 1);
+        lds_char* pb1 = pslot(it & 1, 1);
+        const bf16x8 pa1[2] = {p_half(pb1, 0), p_half(pb1, 1)};
+        // dV of row block 0; dO^T of row block 1 comes in behind
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          acc[i & 3] = mfma(pa0[i >> 2], x[i], acc[i & 3]);
+          x[i] = lds_tr8(dot, 32 + 16 * (i >> 2), i & 3, lane);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i & 3] = mfma(pa1[i >> 2], x[i], acc[i & 3]);
+      } else {
+        SECO_LDS float* delta_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + BQ;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) x[t] = lds_row8(dot, l32, 2 * t + g);
+        lds_char* pb0 = pslot(it & 1, 0);
+        const bf16x8 ph0[2] = {p_half(pb0, 0), p_half(pb0, 1)};
+        f32x16 d;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) d[r] = 0.f;
+        // dP of row block 0; dO rows of row block 1 come in behind
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          d = mfma(x[t], frag[t], d);
+          x[t] = lds_row8(dot, 32 + l32, 2 * t + g);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
+          d[r] = (float)ph0[r >> 3][r & 7] * (d[r] - delta_s[qr]);
+        }
+        const bf16x8 ds0[2] = {pack8(d, 0), pack8(d, 1)};
+        lds_char* pb1 = pslot(it & 1, 1);
+        const bf16x8 ph1[2] = {p_half(pb1, 0), p_half(pb1, 1)};
+#pragma unroll
+        for (int r = 0; r < 16; ++r) d[r] = 0.f;
+        // dP of row block 1; Q^T of row block 0 comes in behind
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          d = mfma(x[t], frag[t], d);
+          x[t] = lds_tr8(qt, 16 * (t >> 2), t & 3, lane);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int qr = 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          d[r] = (float)ph1[r >> 3][r & 7] * (d[r] - delta_s[qr]);
+        }
+        const bf16x8 ds1[2] = {pack8(d, 0), pack8(d, 1)};
+        // dK of row block 0; Q^T of row block 1 comes in behind
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          acc[i & 3] = mfma(ds0[i >> 2], x[i], acc[i & 3]);
+          x[i] = lds_tr8(qt, 32 + 16 * (i >> 2), i & 3, lane);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i & 3] = mfma(ds1[i >> 2], x[i], acc[i & 3]);
       }
     }
     if (it + 2 < n_iter) stash_stat(slot2);

@@ -81,6 +81,11 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
     for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
 
   copy_tile(0, 0);
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    settle(qf[t]);
+    settle(dof[t]);
+  }
   dma_wait_all();
   __syncthreads();
 

@@ -86,6 +86,8 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
   const float c = p.scale * kLog2e;
 
   copy_tile(0, 0);
+#pragma unroll
+  for (int t = 0; t < 8; ++t) settle(qf[t]);
   dma_wait_all();
   __syncthreads();
 

@@ -99,6 +99,11 @@ __device__ __forceinline__ void dma4rows(lds_char* dst_tile, int r, const __bf16
 }
 __device__ __forceinline__ void dma_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Make the compiler wait, here, for the load that produces `v`.  Used on operand fragments that are
+// loaded once before a loop: otherwise the first use inside the loop carries a conservative vmcnt wait
+// on every iteration, which would also wait for the asynchronous tile copies issued in the loop.
+__device__ __forceinline__ void settle(const bf16x8& v) { asm volatile("" : : "v"(v)); }
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // XCD-aware work mapping: consecutive workgroup ids go round-robin over the 8 XCDs, each
