@@ -22,6 +22,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak (published)
+# HBM bytes per launch (mean over the 16 calls of cfg2) from rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0; the
+# factors come from a streaming kernel of known size in the same runs (profiles/cfg2_hbm_traffic_pmc.txt).
+HBM_TRAFFIC_PER_LAUNCH = {("cfg2", "dkdv"): 221.1e6}
 
 
 def pairs(j, C):
@@ -146,7 +149,8 @@ def main():
         achieved = alg[dom] * args.steps / (ms * 1e-3) / 1e12
         out["roofline"] = {"bound": "mfma", "kernel": dom + "_bf16_kernel" if cfg.dtype == "bf16" else dom + "_f32_kernel",
                            "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                           "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                           "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                           "traffic": HBM_TRAFFIC_PER_LAUNCH.get((cfg.name, dom)),
                            "avg_launch_ms": round(ms / n, 5), "launches": int(n)}
         out["kernels"] = kern
 
