@@ -41,6 +41,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-layer32k", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events in the timed region")
+    ap.add_argument("--calls", default="",
+                    help="comma-separated chunk indices: instead of whole steps, time the forward + backward call pair "
+                         "of just these chunks (per-kernel event times; used for counter collection)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch kvgrad_accumulate on a 1 GiB pair of buffers (a plain streaming kernel of known "
                          "size: reads 2 GiB, writes 1 GiB) so that rocprofv3 FETCH_SIZE / WRITE_SIZE can be scaled")
@@ -108,6 +111,28 @@ def main():
     flops_dq = sum(6 * pairs(j, C) for j in range(k_chunks)) * per_pair
     flops_dkdv = sum(4 * pairs(j, C) for j in range(k_chunks)) * per_pair
     flops_step = flops_fwd + flops_dq + flops_dkdv
+
+    if args.calls:
+        per_call = {}
+        for j in [int(x) for x in args.calls.split(",")]:
+            for _ in range(max(args.warmup, 1)):
+                L.fwd(j)
+                L.bwd(j)
+            torch.cuda.synchronize()
+            seco.seco_profile_enable(True)
+            for _ in range(args.steps):
+                L.fwd(j)
+                L.bwd(j)
+            torch.cuda.synchronize()
+            prof = seco.seco_profile_read()
+            seco.seco_profile_enable(False)
+            alg = {"fwd": 4, "dq": 6, "dkdv": 4}
+            per_call[str(j)] = {k: {"avg_ms": round(prof[k][0] / args.steps, 5),
+                                    "tflops": round(f * pairs(j, C) * per_pair * args.steps / (prof[k][0] * 1e-3) / 1e12, 1)}
+                                for k, f in alg.items()}
+        print(json.dumps({"metric": "per_call_kernel_times", "config": {"workload": cfg.name, "chunk_len": C,
+                                                                       "seq_len": N}, "per_call": per_call}))
+        return
 
     for _ in range(args.warmup):
         step()

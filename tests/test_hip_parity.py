@@ -203,45 +203,114 @@ def test_cfg2_full_size_slice_parity():
     check(got, ref, "bf16", "cfg2 slice")
 
 
-def test_cfg3_spaco_sampled_parity():
-    """32K tokens, 16 chunks of 2048, 4 selected chunks, factor k/t = 4: one (batch, KV head)
-    unit on the GPU; the oracle evaluates sampled query rows (O, LSE, dQ need one row each)
-    and the top selected chunk's own rows of gK/gV (which only that call touches)."""
-    cfg = CONFIGS["cfg3"]
+def _spaco_sampled_check(cfg, kvh, n_rows_per_chunk=3):
+    """SpaCO (Alg. 2) at full sequence length on one (batch, KV head) unit: the oracle evaluates sampled
+    query rows (O, LSE, dQ need one row each) and the top selected chunk's own rows of gK/gV, which only
+    that chunk's call touches."""
     k, t, C = cfg.n_chunks, cfg.spaco_t, cfg.chunk_len
     sel = S.select_chunks(cfg.seed, 0, k, t).tolist()
     assert sel == seco.spaco_select_chunks(cfg.seed, 0, k, t)
     lam = float(np.float32(S.compensation_factor(k, t)))
-    x = _device_group(cfg, 0, 2)
+    x = _device_group(cfg, 0, kvh)
     got = run_layer(x, C, cfg.scale, "bf16", selected=sel, factor=lam)
     rng = np.random.default_rng(7)
     q64, k64, v64, do64 = (x[n].astype(np.float64) for n in ("q", "k", "v", "do"))
     for j in sel:
-        for r in rng.integers(0, C, size=3):
+        for r in rng.integers(0, C, size=n_rows_per_chunk):
             p = j * C + int(r)
             o_r, lse_r = A.chunk_attn_fwd(q64[:, :, p:p + 1], k64, v64, p, cfg.scale)
-            dq_r, dk_r, dv_r = A.chunk_attn_bwd(q64[:, :, p:p + 1], k64, v64, o_r, lse_r, do64[:, :, p:p + 1], p, cfg.scale)
+            dq_r, _, _ = A.chunk_attn_bwd(q64[:, :, p:p + 1], k64, v64, o_r, lse_r, do64[:, :, p:p + 1], p, cfg.scale)
             assert np.abs(got["o"][:, :, p] - o_r[:, :, 0]).max() <= 1e-2 * np.abs(o_r).max()
             assert np.abs(got["lse"][:, :, p] - lse_r[:, :, 0]).max() <= 1e-2 * np.abs(lse_r).max()
             assert np.abs(got["dq"][:, :, p] - dq_r[:, :, 0]).max() <= 2e-2 * np.abs(dq_r).max()
+    # The top selected chunk's own rows receive only that call's diagonal block.  The oracle backward takes LSE
+    # and O as inputs, so with the true LSE and O of the chunk and a cache cut down to the chunk's own rows it
+    # returns exactly that block.
     top = sel[0]
     rows = slice(top * C, (top + 1) * C)
-    # own block of the top selected chunk: restrict the cache to that chunk and pass the true LSE / O
     o_ref, lse_ref = A.chunk_attn_fwd(q64[:, :, rows], k64, v64, top * C, cfg.scale)
-    qs, dos = q64[:, :, rows], do64[:, :, rows]
-    G = qs.shape[1]
-    dk_own = np.zeros((C, cfg.head_dim))
-    dv_own = np.zeros((C, cfg.head_dim))
-    for h in range(G):
-        sc = cfg.scale * qs[0, h] @ k64[0, 0, rows].T
-        vis = np.arange(C)[None, :] <= np.arange(C)[:, None]
-        P = np.where(vis, np.exp(sc - lse_ref[0, h][:, None]), 0.0)
-        dP = dos[0, h] @ v64[0, 0, rows].T
-        dS = P * (dP - (dos[0, h] * o_ref[0, h]).sum(1, keepdims=True))
-        dk_own += cfg.scale * dS.T @ qs[0, h]
-        dv_own += P.T @ dos[0, h]
-    assert max_rel(got["gk"][0, 0, rows], dk_own) <= 2e-2
-    assert max_rel(got["gv"][0, 0, rows], dv_own) <= 2e-2
+    _, dk_own, dv_own = A.chunk_attn_bwd(q64[:, :, rows], k64[:, :, rows], v64[:, :, rows], o_ref, lse_ref,
+                                         do64[:, :, rows], 0, cfg.scale)
+    assert max_rel(got["gk"][:, :, rows], dk_own) <= 2e-2
+    assert max_rel(got["gv"][:, :, rows], dv_own) <= 2e-2
     for i in range(k):
         if i not in sel:
             assert not got["gk"][:, :, i * C:(i + 1) * C].any() and not got["gv"][:, :, i * C:(i + 1) * C].any()
+            assert not got["dq"][:, :, i * C:(i + 1) * C].any()
+    # lower selected chunks: rows hold their own block plus factor x the blocks of the higher selected calls
+    # restricted to those rows; check the lowest one in full against the oracle, call by call
+    low = sel[-1]
+    rows = slice(low * C, (low + 1) * C)
+    want_k = np.zeros_like(got["gk"][:, :, rows])
+    want_v = np.zeros_like(want_k)
+    for j in sel:
+        qr = slice(j * C, (j + 1) * C)
+        o_j, lse_j = A.chunk_attn_fwd(q64[:, :, qr], k64, v64, j * C, cfg.scale)
+        if j == low:
+            _, dk, dv = A.chunk_attn_bwd(q64[:, :, qr], k64[:, :, rows], v64[:, :, rows], o_j, lse_j, do64[:, :, qr], 0, cfg.scale)
+            want_k += dk
+            want_v += dv
+        else:
+            # rows of chunk `low` are entirely below the diagonal of call j: a cache holding only those rows,
+            # with q_start moved past them, makes every one of them visible to every query row
+            _, dk, dv = A.chunk_attn_bwd(q64[:, :, qr], np.concatenate([k64[:, :, rows], k64[:, :, qr]], axis=2),
+                                         np.concatenate([v64[:, :, rows], v64[:, :, qr]], axis=2), o_j, lse_j,
+                                         do64[:, :, qr], C, cfg.scale)
+            want_k += lam * dk[:, :, :C]
+            want_v += lam * dv[:, :, :C]
+    assert max_rel(got["gk"][:, :, rows], want_k) <= 2e-2
+    assert max_rel(got["gv"][:, :, rows], want_v) <= 2e-2
+
+
+def test_cfg3_spaco_sampled_parity():
+    """32K tokens, 16 chunks of 2048, 4 selected chunks, factor k/t = 4."""
+    _spaco_sampled_check(CONFIGS["cfg3"], 2)
+
+
+def test_cfg4_spaco_sampled_parity():
+    """64K tokens, 32 chunks of 2048, 8 selected chunks, factor k/t = 4."""
+    _spaco_sampled_check(CONFIGS["cfg4"], 6, n_rows_per_chunk=2)
+
+
+def test_cfg5_like_batch2_rope_inputs():
+    """Batch 2 with RoPE-like structured Q/K (sin/cos-modulated, per-head mean), a scaled-down cfg5:
+    SeCO and SpaCO with a quarter of the chunks selected."""
+    cfg = Config("cfg5_small", "bf16", 2, 8, 2, 128, 2048, 256, seed=4, rope_like=True, spaco_t=2)
+    x = full_layer(cfg)
+    got = run_layer(x, cfg.chunk_len, cfg.scale, "bf16")
+    ref = A.seco_layer(x["q"], x["k"], x["v"], x["do"], cfg.chunk_len, cfg.scale)
+    check(got, ref, "bf16", "cfg5-like seco")
+    sel = S.select_chunks(cfg.seed, 3, cfg.n_chunks, cfg.spaco_t).tolist()
+    lam = float(np.float32(S.compensation_factor(cfg.n_chunks, cfg.spaco_t)))
+    got = run_layer(x, cfg.chunk_len, cfg.scale, "bf16", selected=sel, factor=lam)
+    ref = A.spaco_layer(x["q"], x["k"], x["v"], x["do"], cfg.chunk_len, cfg.scale, sel, lam)
+    check(got, ref, "bf16", f"cfg5-like spaco {sel}")
+
+
+def test_cfg2_whole_layer_identities_in_the_benchmark_configuration():
+    """The benchmark's launch configuration (all 32 heads, 16 calls of 1024 rows, device-generated inputs),
+    checked with identities that hold at any size: rows of P sum to one, so sum_c gV[c] = sum_{h,r} dO[h,r];
+    and sum_r Q.dQ = sum_c K.gK (both equal s * sum dS * QK^T)."""
+    cfg = CONFIGS["cfg2"]
+    B, Hq, Hkv, D, N, C = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.seq_len, cfg.chunk_len
+    gen = torch.Generator(device=DEV).manual_seed(5)
+    mk = lambda h: torch.randn(B, h, N, D, generator=gen, device=DEV).to(torch.bfloat16)
+    q, k, v, do = mk(Hq), mk(Hkv), mk(Hkv), mk(Hq)
+    o, dq = torch.empty_like(q), torch.empty_like(q)
+    gk = torch.empty(B, Hkv, N, D, device=DEV)
+    gv = torch.empty_like(gk)
+    seco.kvgrad_zero(gk, gv)
+    for j in range(cfg.n_chunks - 1, -1, -1):
+        rows = slice(j * C, (j + 1) * C)
+        _, lse = seco.seco_chunk_attn_fwd(q[:, :, rows], k, v, j * C, cfg.scale, o=o[:, :, rows])
+        seco.seco_chunk_attn_bwd(q[:, :, rows], k, v, o[:, :, rows], lse, do[:, :, rows], gk, gv, j * C, cfg.scale,
+                                 d_q=dq[:, :, rows])
+    torch.cuda.synchronize()
+    G = Hq // Hkv
+    lhs = gv.double().sum(dim=2)
+    rhs = do.double().view(B, Hkv, G, N, D).sum(dim=(2, 3))
+    assert (lhs - rhs).abs().max() <= 2e-2 * rhs.abs().max()
+    qdq = (q.double() * dq.double()).view(B, Hkv, G, N, D).sum(dim=(2, 3, 4))
+    kgk = (k.double() * gk.double()).sum(dim=(2, 3))
+    assert (qdq - kgk).abs().max() <= 2e-2 * kgk.abs().max().clamp_min(1.0)
+    assert torch.isfinite(gk).all() and torch.isfinite(dq.float()).all()
