@@ -27,6 +27,7 @@ namespace {
 
 constexpr int BM = 128;  // query rows per workgroup
 constexpr int BNW = 64;  // cache rows per wavefront and tile
+constexpr float kLazy = 8.f;   // threshold of the lazy O rescale, in log2 units
 
 template <int KH>
 __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
@@ -121,11 +122,24 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      // a part of a tile can be fully masked for a row (only when kh > 0 or q_start is unaligned);
-      // keep the running max finite-or-unchanged so that exp2(-inf - (-inf)) never appears
-      const float m_new = fmaxf(m_run, mx * c);
-      const float m_use = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = fast_exp2(m_run - m_use);
+      // Lazy rescaling: the reference maximum of a row moves only when the tile maximum exceeds it by more
+      // than kLazy (log2 units), so exponentials stay below 2^kLazy and the rescale of the O^T accumulator
+      // runs a handful of times per kernel instead of once per tile.
+      const float m_blk = mx * c;
+      const bool bump = m_blk > m_run + kLazy;
+      if (__builtin_amdgcn_ballot_w64(bump) != 0) {
+        const float m_new = bump ? m_blk : m_run;
+        const float alpha = bump ? fast_exp2(m_run - m_new) : 1.f;   // exp2(-inf) = 0 on a row's first visible tile
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        m_run = m_new;
+      }
+      // a part of a tile can be fully masked for a row (only when kh > 0 or q_start is unaligned): such a row
+      // has seen nothing yet and keeps m_run = -inf; use 0 so that exp2(-inf - (-inf)) never appears
+      const float m_use = m_run == -INFINITY ? 0.f : m_run;
       float sum = 0.f;
 #pragma unroll
       for (int kvb = 0; kvb < 2; ++kvb)
@@ -135,12 +149,7 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
           s[kvb][r] = e;
           sum += e;
         }
-      l_run = l_run * alpha + sum;
-      m_run = m_new;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+      l_run += sum;
 #pragma unroll
       for (int kvb = 0; kvb < 2; ++kvb)
 #pragma unroll
