@@ -86,12 +86,20 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   bf16x8 frag[8];
 #pragma unroll
   for (int t = 0; t < 8; ++t) frag[t] = *reinterpret_cast<const bf16x8*>(fptr + 16 * t + 8 * g);
+  // Role A folds the softmax scale and the change to base 2 into its K^T fragments (one rounding to bf16, once
+  // per workgroup), so that its MFMA chains, started from -LSE instead of zero, deliver log2 P directly; role B
+  // starts its chains from -delta.  Neither needs a subtraction or a multiply-add per score afterwards.
+  if (role == 0) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) frag[t][i] = (__bf16)((float)frag[t][i] * (p.scale * kLog2e));
+  }
 
   // query-row stages that see at least one cache row of this workgroup; iteration = (head of the group, stage)
   const int rt0 = max(0, c0 - p.q_start) / BQ;
   const int n_rt = (p.C + BQ - 1) / BQ - rt0;
   const int n_iter = n_rt * p.G;
-  const float c = p.scale * kLog2e;
   struct Pos { int hg, r0; };   // head within the group, first chunk-local row of the stage
   auto advance = [&](Pos x) {
     x.r0 += BQ;
@@ -113,15 +121,15 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       dma4rows(qt + kTileBytes, r, dobase + x.hg * p.os[1] + (int64_t)src_row * p.os[2], lane);
     }
   };
-  // LSE (scaled to log2 units) and delta of the stage go through a register: threads 0 .. 2*BQ-1
+  // -LSE (in log2 units) and -delta of the stage go through a register: threads 0 .. 2*BQ-1
   float stat = 0.f;
   auto fetch_stat = [&](Pos x) {
     if (tid < 2 * BQ) {
       const int rr = x.r0 + (tid % BQ);
       const int64_t idx = stat_base + (int64_t)x.hg * p.C + min(rr, p.C - 1);
-      // rows past the chunk get LSE = +inf so that their probabilities vanish
-      if (tid < BQ) stat = rr < p.C ? p.lse[idx] * kLog2e : INFINITY;
-      else stat = p.delta[idx];
+      // stored negated (they start the MFMA chains); rows past the chunk get -LSE = -inf so that their probabilities vanish
+      if (tid < BQ) stat = rr < p.C ? -p.lse[idx] * kLog2e : -INFINITY;
+      else stat = -p.delta[idx];
     }
   };
   auto stash_stat = [&](int slot) {
@@ -157,14 +165,11 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     for (int t = 0; t < 8; ++t) a[t] = lds_row8(qt, 32 * rb + l32, 2 * t + g);
     f32x16 s;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    for (int r = 0; r < 16; ++r) s[r] = lse_s[8 * (r >> 2) + 4 * g + (r & 3)];
 #pragma unroll
     for (int t = 0; t < 8; ++t) s = mfma(a[t], frag[t], s);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
-      s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_s[qr]));
-    }
+    for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r]);
     mask_above_diagonal(s, p.q_start + r0 + 32 * rb);
     lds_char* pb = pslot(parity, rb);
     *reinterpret_cast<SECO_LDS bf16x8*>(pb + lane * 16) = pack8(s, 0);
@@ -218,18 +223,15 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
         for (int t = 0; t < 8; ++t) x[t] = lds_row8(qt1, l32, 2 * t + g);
         f32x16 s;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-        // S of row block 0; Q rows of row block 1 come in behind
+        for (int r = 0; r < 16; ++r) s[r] = lse_s[8 * (r >> 2) + 4 * g + (r & 3)];
+        // log2 P of row block 0 (chain started from -LSE); Q rows of row block 1 come in behind
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
           s = mfma(x[t], frag[t], s);
           x[t] = lds_row8(qt1, 32 + l32, 2 * t + g);
         }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
-          s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_s[qr]));
-        }
+        for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r]);
         mask_above_diagonal(s, p.q_start + nxt.r0);
         lds_char* pn0 = pslot((it + 1) & 1, 0);
         *reinterpret_cast<SECO_LDS bf16x8*>(pn0 + lane * 16) = pack8(s, 0);
@@ -237,18 +239,15 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
         lds_char* pb0 = pslot(it & 1, 0);
         const bf16x8 pa0[2] = {p_half(pb0, 0), p_half(pb0, 1)};
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-        // S of row block 1; dO^T of row block 0 (stage `it`) comes in behind
+        for (int r = 0; r < 16; ++r) s[r] = lse_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
+        // log2 P of row block 1; dO^T of row block 0 (stage `it`) comes in behind
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
           s = mfma(x[t], frag[t], s);
           x[t] = lds_tr8(dot, 16 * (t >> 2), t & 3, lane);
         }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int qr = 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-          s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_s[qr]));
-        }
+        for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r]);
         mask_above_diagonal(s, p.q_start + nxt.r0 + 32);
         lds_char* pn1 = pslot((it + 1) & 1, 1);
         *reinterpret_cast<SECO_LDS bf16x8*>(pn1 + lane * 16) = pack8(s, 0);
@@ -271,34 +270,28 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
         const bf16x8 ph0[2] = {p_half(pb0, 0), p_half(pb0, 1)};
         f32x16 d;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) d[r] = 0.f;
-        // dP of row block 0; dO rows of row block 1 come in behind
+        for (int r = 0; r < 16; ++r) d[r] = delta_s[8 * (r >> 2) + 4 * g + (r & 3)];
+        // dP - delta of row block 0 (chain started from -delta); dO rows of row block 1 come in behind
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
           d = mfma(x[t], frag[t], d);
           x[t] = lds_row8(dot, 32 + l32, 2 * t + g);
         }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
-          d[r] = (float)ph0[r >> 3][r & 7] * (d[r] - delta_s[qr]);
-        }
+        for (int r = 0; r < 16; ++r) d[r] *= (float)ph0[r >> 3][r & 7];
         const bf16x8 ds0[2] = {pack8(d, 0), pack8(d, 1)};
         lds_char* pb1 = pslot(it & 1, 1);
         const bf16x8 ph1[2] = {p_half(pb1, 0), p_half(pb1, 1)};
 #pragma unroll
-        for (int r = 0; r < 16; ++r) d[r] = 0.f;
-        // dP of row block 1; Q^T of row block 0 comes in behind
+        for (int r = 0; r < 16; ++r) d[r] = delta_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
+        // dP - delta of row block 1; Q^T of row block 0 comes in behind
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
           d = mfma(x[t], frag[t], d);
           x[t] = lds_tr8(qt, 16 * (t >> 2), t & 3, lane);
         }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int qr = 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-          d[r] = (float)ph1[r >> 3][r & 7] * (d[r] - delta_s[qr]);
-        }
+        for (int r = 0; r < 16; ++r) d[r] *= (float)ph1[r >> 3][r & 7];
         const bf16x8 ds1[2] = {pack8(d, 0), pack8(d, 1)};
         // dK of row block 0; Q^T of row block 1 comes in behind
 #pragma unroll
