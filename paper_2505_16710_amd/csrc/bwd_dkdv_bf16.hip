@@ -110,15 +110,35 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   const __bf16* qbase = static_cast<const __bf16*>(p.q) + b * p.qs[0] + (int64_t)kvh * p.G * p.qs[1];
   const __bf16* dobase = static_cast<const __bf16*>(p.d_o) + b * p.os[0] + (int64_t)kvh * p.G * p.os[1];
   const int64_t stat_base = ((int64_t)b * p.Hq + (int64_t)kvh * p.G) * p.C;
-  // asynchronous global -> LDS copy of the Q and dO tiles of one stage (4 rows per wavefront and copy)
-  auto copy_stage = [&](Pos x, int slot) {
-    lds_char* qt = smem + slot * kStageBytes;
+  // asynchronous global -> LDS copy of the Q and dO tiles of one stage (4 rows per wavefront and copy).  A stage
+  // that lies entirely inside the chunk is copied from scalar base addresses with constant per-lane offsets (no
+  // vector arithmetic); the last, ragged one uses clamped per-lane addresses.
+  uint32_t q_lane_off[kCopies], do_lane_off[kCopies];
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) {
-      const int r = 4 * (wave + NW * i);
-      const int src_row = min(x.r0 + r + (lane >> 4), p.C - 1);
-      dma4rows(qt, r, qbase + x.hg * p.qs[1] + (int64_t)src_row * p.qs[2], lane);
-      dma4rows(qt + kTileBytes, r, dobase + x.hg * p.os[1] + (int64_t)src_row * p.os[2], lane);
+  for (int i = 0; i < kCopies; ++i) {
+    q_lane_off[i] = dma_lane_offset(4 * (wave + NW * i), p.qs[2] * 2, lane);
+    do_lane_off[i] = dma_lane_offset(4 * (wave + NW * i), p.os[2] * 2, lane);
+  }
+  const uint32_t lds_wave = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + wave * 4 * kRowBytes);
+  auto copy_stage = [&](Pos x, int slot) {
+    if (x.r0 + BQ <= p.C) {
+      const __bf16* q_src = qbase + x.hg * p.qs[1] + (int64_t)x.r0 * p.qs[2];
+      const __bf16* do_src = dobase + x.hg * p.os[1] + (int64_t)x.r0 * p.os[2];
+#pragma unroll
+      for (int i = 0; i < kCopies; ++i) {
+        const uint32_t dst = lds_wave + slot * kStageBytes + i * (4 * NW * kRowBytes);
+        dma16_sbase(q_src, q_lane_off[i], dst);
+        dma16_sbase(do_src, do_lane_off[i], dst + kTileBytes);
+      }
+    } else {
+      lds_char* qt = smem + slot * kStageBytes;
+#pragma unroll
+      for (int i = 0; i < kCopies; ++i) {
+        const int r = 4 * (wave + NW * i);
+        const int src_row = min(x.r0 + r + (lane >> 4), p.C - 1);
+        dma4rows(qt, r, qbase + x.hg * p.qs[1] + (int64_t)src_row * p.qs[2], lane);
+        dma4rows(qt + kTileBytes, r, dobase + x.hg * p.os[1] + (int64_t)src_row * p.os[2], lane);
+      }
     }
   };
   // -LSE (in log2 units) and -delta of the stage go through a register: threads 0 .. 2*BQ-1

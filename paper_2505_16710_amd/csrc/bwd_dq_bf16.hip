@@ -61,16 +61,33 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
   const int n_tiles = (wg_kv_end + BN - 1) / BN;
   const int wave_kv_end = m0 < p.C ? p.q_start + min(m0 + 32, p.C) : 0;
 
-  // asynchronous global -> LDS copy of one K and one V tile: each wavefront copies 4 groups of 4 rows of each
-  auto copy_tile = [&](int n, int buf) {
-    lds_char* kt = smem + buf * 2 * kTileBytes;
-    lds_char* vt = kt + kTileBytes;
+  // asynchronous global -> LDS copy of one K and one V tile: each wavefront copies 4 groups of 4 rows of each.
+  // The per-lane byte offsets inside a tile never change; a tile that lies entirely inside the cache is copied
+  // from a scalar base address with no vector arithmetic, the last (ragged) one with clamped per-lane addresses.
+  uint32_t lane_off[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = 4 * (wave + 4 * KH * i);
-      const int64_t off = (int64_t)min(n * BN + r + (lane >> 4), kv_len - 1) * p.kvs[2];
-      dma4rows(kt, r, kbase + off, lane);
-      dma4rows(vt, r, vbase + off, lane);
+  for (int i = 0; i < 4; ++i) lane_off[i] = dma_lane_offset(4 * (wave + 4 * KH * i), p.kvs[2] * 2, lane);
+  const uint32_t lds_wave = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + wave * 4 * kRowBytes);
+  auto copy_tile = [&](int n, int buf) {
+    if ((n + 1) * BN <= kv_len) {
+      const __bf16* kt_src = kbase + (int64_t)n * BN * p.kvs[2];
+      const __bf16* vt_src = vbase + (int64_t)n * BN * p.kvs[2];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t dst = lds_wave + buf * 2 * kTileBytes + i * (16 * KH * kRowBytes);
+        dma16_sbase(kt_src, lane_off[i], dst);
+        dma16_sbase(vt_src, lane_off[i], dst + kTileBytes);
+      }
+    } else {
+      lds_char* kt = smem + buf * 2 * kTileBytes;
+      lds_char* vt = kt + kTileBytes;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = 4 * (wave + 4 * KH * i);
+        const int64_t off = (int64_t)min(n * BN + r + (lane >> 4), kv_len - 1) * p.kvs[2];
+        dma4rows(kt, r, kbase + off, lane);
+        dma4rows(vt, r, vbase + off, lane);
+      }
     }
   };
 

@@ -97,6 +97,18 @@ __device__ __forceinline__ void dma4rows(lds_char* dst_tile, int r, const __bf16
   const uint32_t m = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(dst_tile + r * kRowBytes));
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(row_ptr + chunk * 8), "s"(m) : "memory", "m0");
 }
+// Same copy with the address split into a wavefront-uniform 64-bit base (held in scalar registers) and a per-lane
+// 32-bit byte offset that does not change from tile to tile: no vector arithmetic per copy.  `lds_dst` must be
+// wavefront-uniform and already in a scalar register (e.g. derived from __builtin_amdgcn_readfirstlane).
+__device__ __forceinline__ void dma16_sbase(const void* base_uniform, uint32_t lane_off_bytes, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off_bytes), "s"(base_uniform), "s"(lds_dst) : "memory", "m0");
+}
+// per-lane byte offset of the 16-byte chunk this lane fetches when rows r .. r+3 (r % 4 == 0) of a tile whose
+// source rows are `row_stride_bytes` apart are copied by one dma16_sbase
+__device__ __forceinline__ uint32_t dma_lane_offset(int r, int64_t row_stride_bytes, int lane) {
+  const int row = r + (lane >> 4);
+  return (uint32_t)(row * row_stride_bytes) + (uint32_t)((((lane & 15) ^ swz(row))) << 4);
+}
 __device__ __forceinline__ void dma_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Make the compiler wait, here, for the load that produces `v`.  Used on operand fragments that are
