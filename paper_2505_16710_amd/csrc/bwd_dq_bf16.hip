@@ -1,5 +1,5 @@
 // dQ of one chunk, bf16 matrix cores: dQ = s * dS K over ALL visible cache rows, with
-// P = exp(S - LSE), dS = P * (dO V^T - delta).  (SpaCO keeps dQ exact: a selected chunk's
+// P = exp(S - LSE), dS = P * (dO V^T - delta), delta = rowsum(dO * O) (computed in this kernel's prologue).  (SpaCO keeps dQ exact: a selected chunk's
 // graph is rebuilt against every earlier cache, Alg. 2.)
 //
 // Same row-parallel decomposition as the forward, in the same two workgroup shapes: a workgroup
@@ -52,7 +52,21 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
   }
   const int64_t stat = ((int64_t)b * p.Hq + h) * p.C + crow;
   const float lse_c = p.lse[stat] * kLog2e;
-  const float delta = p.delta[stat];
+  // delta = rowsum(dO * O) is computed here, from the dO fragments already in registers and the matching O
+  // fragments: a lane holds half of its row's head_dim (the other half is in lane ^ 32).  It is also written to
+  // the workspace for the dK/dV kernel that follows on the same stream.
+  float delta = 0.f;
+  {
+    const __bf16* optr = static_cast<const __bf16*>(p.o) + b * p.os[0] + h * p.os[1] + (int64_t)crow * p.os[2];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const bf16x8 of = *reinterpret_cast<const bf16x8*>(optr + 16 * t + 8 * g);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) delta = __builtin_fmaf((float)of[i], (float)dof[t][i], delta);
+    }
+    delta += __shfl_xor(delta, 32);
+    if (kh == 0 && g == 0 && row < p.C) p.delta[stat] = delta;
+  }
   const float c = p.scale * kLog2e;
 
   const __bf16* kbase = static_cast<const __bf16*>(p.k) + b * p.kvs[0] + kvh * p.kvs[1];

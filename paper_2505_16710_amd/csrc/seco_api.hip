@@ -115,7 +115,8 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
   p.gk = gk; p.gv = gv;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = d->dtype == SECO_BF16;
-  if ((rc = launch_delta(p, d->dtype, s))) return rc;
+  // delta = rowsum(dO * O): the bf16 dQ kernel computes it in its prologue (and stores it for the dK/dV kernel)
+  if (!bf16 && (rc = launch_delta(p, d->dtype, s))) return rc;
   if ((rc = bf16 ? launch_dq_bf16(p, s) : launch_dq_f32(p, s))) return rc;
   for (size_t first = 0; first < runs.size(); first += kMaxSegments) {
     SegTable seg;
