@@ -1,0 +1,176 @@
+"""SeCO / SpaCO over a small multi-layer transformer, CPU fp64 oracle (Alg. 1 and Alg. 2 end to end).
+
+TEST INFRASTRUCTURE ONLY (see the package docstring).  fp64 PyTorch on the CPU; autograd
+supplies the per-layer derivatives, this file supplies the schedules of the paper:
+
+  * `monolithic_grads`  - ordinary training step on the whole sequence: the reference the
+    paper compares SeCO with (Sec. 4, "match those from naive parallel training");
+  * `seco_grads`        - Alg. 1: stage 1 runs the chunks in inference mode and keeps the KV
+    caches m'_1..m'_k of every layer as checkpoints; stage 2 rebuilds each chunk's graph in
+    reverse order against those checkpoints, hands the gradient collected on m'_i over to
+    the recomputed m_i, and back-propagates J_i, which deposits gradient on the earlier
+    checkpoints;
+  * `spaco_grads`       - Alg. 2: only the selected chunks are rebuilt, and the gradient handed
+    over from m'_i to m_i is multiplied by the compensation factor, so that a chain through p
+    caches carries factor^p (Sec. 5, "Compensation Factor" and "Implementation").
+
+The model is a plain pre-norm decoder: RMSNorm, grouped-query causal attention (no positional
+encoding), RMSNorm, two-matrix MLP with SiLU, tied to nothing, cross-entropy loss summed over
+tokens; J_j is the loss of chunk j's tokens.  The chunk-level error components of Eq. 1 add
+up to the sequence loss.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import torch
+import torch.nn.functional as F
+
+
+@dataclass(frozen=True)
+class ModelConfig:
+    n_layers: int = 3
+    d_model: int = 32
+    n_q_heads: int = 4
+    n_kv_heads: int = 2
+    head_dim: int = 8
+    d_ff: int = 48
+    vocab: int = 17
+
+    @property
+    def scale(self):
+        return float(self.head_dim) ** -0.5
+
+
+def init_params(cfg: ModelConfig, seed: int, dtype=torch.float64):
+    """Seeded random parameters (dict name -> tensor, requires_grad)."""
+    g = torch.Generator().manual_seed(seed)
+    def rnd(*shape, std):
+        return (torch.randn(*shape, generator=g, dtype=torch.float64) * std).to(dtype).requires_grad_()
+    p = {"emb": rnd(cfg.vocab, cfg.d_model, std=1.0), "head": rnd(cfg.d_model, cfg.vocab, std=cfg.d_model ** -0.5),
+         "norm_f": (1 + 0.1 * torch.randn(cfg.d_model, generator=g, dtype=torch.float64)).to(dtype).requires_grad_()}
+    for l in range(cfg.n_layers):
+        s = cfg.d_model ** -0.5
+        p[f"l{l}.norm1"] = (1 + 0.1 * torch.randn(cfg.d_model, generator=g, dtype=torch.float64)).to(dtype).requires_grad_()
+        p[f"l{l}.norm2"] = (1 + 0.1 * torch.randn(cfg.d_model, generator=g, dtype=torch.float64)).to(dtype).requires_grad_()
+        p[f"l{l}.wq"] = rnd(cfg.d_model, cfg.n_q_heads * cfg.head_dim, std=2 * s)
+        p[f"l{l}.wk"] = rnd(cfg.d_model, cfg.n_kv_heads * cfg.head_dim, std=2 * s)
+        p[f"l{l}.wv"] = rnd(cfg.d_model, cfg.n_kv_heads * cfg.head_dim, std=s)
+        p[f"l{l}.wo"] = rnd(cfg.n_q_heads * cfg.head_dim, cfg.d_model, std=(cfg.n_q_heads * cfg.head_dim) ** -0.5)
+        p[f"l{l}.w1"] = rnd(cfg.d_model, cfg.d_ff, std=s)
+        p[f"l{l}.w2"] = rnd(cfg.d_ff, cfg.d_model, std=cfg.d_ff ** -0.5)
+    return p
+
+
+def _rmsnorm(x, g):
+    return x * torch.rsqrt((x * x).mean(dim=-1, keepdim=True) + 1e-6) * g
+
+
+def _attend(q, k_all, v_all, q_start, scale):
+    """q [B,Hq,C,D] against cache rows 0 .. q_start+C-1 ([B,Hkv,L,D]), causal with the diagonal included."""
+    G = q.shape[1] // k_all.shape[1]
+    C, L = q.shape[2], k_all.shape[2]
+    s = scale * torch.einsum("bhrd,bhcd->bhrc", q, k_all.repeat_interleave(G, 1))
+    vis = torch.arange(L)[None, :] <= (q_start + torch.arange(C))[:, None]
+    p = torch.softmax(s.masked_fill(~vis, float("-inf")), dim=-1)
+    return torch.einsum("bhrc,bhcd->bhrd", p, v_all.repeat_interleave(G, 1))
+
+
+def _chunk_forward(cfg, params, tokens, targets, q_start, caches):
+    """One chunk through all layers (Eq. 1): returns (J_j, [(k_l, v_l)] of this chunk).
+
+    caches[l] = (K_prefix, V_prefix) of the earlier chunks at layer l, [B,Hkv,q_start,D] (may be empty)."""
+    B, C = tokens.shape
+    x = params["emb"][tokens]
+    new_kv = []
+    for l in range(cfg.n_layers):
+        h = _rmsnorm(x, params[f"l{l}.norm1"])
+        q = (h @ params[f"l{l}.wq"]).view(B, C, cfg.n_q_heads, cfg.head_dim).transpose(1, 2)
+        k = (h @ params[f"l{l}.wk"]).view(B, C, cfg.n_kv_heads, cfg.head_dim).transpose(1, 2)
+        v = (h @ params[f"l{l}.wv"]).view(B, C, cfg.n_kv_heads, cfg.head_dim).transpose(1, 2)
+        new_kv.append((k, v))
+        k_all = torch.cat([caches[l][0], k], dim=2)
+        v_all = torch.cat([caches[l][1], v], dim=2)
+        o = _attend(q, k_all, v_all, q_start, cfg.scale)
+        x = x + o.transpose(1, 2).reshape(B, C, -1) @ params[f"l{l}.wo"]
+        h = _rmsnorm(x, params[f"l{l}.norm2"])
+        x = x + F.silu(h @ params[f"l{l}.w1"]) @ params[f"l{l}.w2"]
+    logits = _rmsnorm(x, params["norm_f"]) @ params["head"]
+    loss = F.cross_entropy(logits.reshape(B * C, -1), targets.reshape(B * C), reduction="sum")
+    return loss, new_kv
+
+
+def _empty_caches(cfg, B, dtype):
+    z = torch.zeros(B, cfg.n_kv_heads, 0, cfg.head_dim, dtype=dtype)
+    return [(z, z) for _ in range(cfg.n_layers)]
+
+
+def _zero_grads(params):
+    for t in params.values():
+        t.grad = None
+
+
+def _collect(params):
+    return {n: (t.grad.clone() if t.grad is not None else torch.zeros_like(t)) for n, t in params.items()}
+
+
+def monolithic_grads(cfg, params, tokens, targets):
+    """Loss and parameter gradients of the whole sequence processed at once."""
+    _zero_grads(params)
+    loss, _ = _chunk_forward(cfg, params, tokens, targets, 0, _empty_caches(cfg, tokens.shape[0], params["emb"].dtype))
+    loss.backward()
+    return loss.detach(), _collect(params)
+
+
+def _stage1(cfg, params, tokens, targets, chunk_len):
+    """Alg. 1 / Alg. 2, first loop: all chunks in inference mode; returns the checkpoints
+    ckpt[j][l] = (K, V) of chunk j at layer l as detached leaves that can collect gradient."""
+    B, N = tokens.shape
+    ckpt, total = [], 0.0
+    with torch.no_grad():
+        for s0 in range(0, N, chunk_len):
+            caches = [(torch.cat([c[l][0] for c in ckpt], 2), torch.cat([c[l][1] for c in ckpt], 2)) if ckpt
+                      else _empty_caches(cfg, B, params["emb"].dtype)[l] for l in range(cfg.n_layers)]
+            loss, new_kv = _chunk_forward(cfg, params, tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, caches)
+            total += float(loss)
+            ckpt.append([(k.detach().clone(), v.detach().clone()) for k, v in new_kv])
+    for c in ckpt:
+        for k, v in c:
+            k.requires_grad_()
+            v.requires_grad_()
+    return ckpt, total
+
+
+def _stage2(cfg, params, tokens, targets, chunk_len, ckpt, order, factor):
+    """Second loop: for every chunk in `order` (descending) rebuild its graph against the checkpoints,
+    hand factor * m'_i.grad to the recomputed m_i and back-propagate J_i."""
+    B, N = tokens.shape
+    starts = list(range(0, N, chunk_len))
+    for i in order:
+        s0 = starts[i]
+        caches = [(torch.cat([c[l][0] for c in ckpt[:i]], 2), torch.cat([c[l][1] for c in ckpt[:i]], 2)) if i
+                  else _empty_caches(cfg, B, params["emb"].dtype)[l] for l in range(cfg.n_layers)]
+        loss, new_kv = _chunk_forward(cfg, params, tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, caches)
+        roots, grads = [loss], [torch.ones_like(loss)]
+        for l, (k, v) in enumerate(new_kv):
+            gk, gv = ckpt[i][l][0].grad, ckpt[i][l][1].grad
+            if gk is not None:            # gradient that later chunks left on the checkpoint m'_i
+                roots += [k, v]
+                grads += [factor * gk, factor * gv]
+        torch.autograd.backward(roots, grads)
+
+
+def seco_grads(cfg, params, tokens, targets, chunk_len):
+    """Alg. 1: exact gradients with one chunk's graph alive at a time."""
+    _zero_grads(params)
+    ckpt, total = _stage1(cfg, params, tokens, targets, chunk_len)
+    _stage2(cfg, params, tokens, targets, chunk_len, ckpt, range(len(ckpt) - 1, -1, -1), 1.0)
+    return total, _collect(params)
+
+
+def spaco_grads(cfg, params, tokens, targets, chunk_len, selected, factor):
+    """Alg. 2: back-propagate only the selected chunks, relayed KV gradient scaled by `factor`."""
+    _zero_grads(params)
+    ckpt, total = _stage1(cfg, params, tokens, targets, chunk_len)
+    _stage2(cfg, params, tokens, targets, chunk_len, ckpt, sorted({int(i) for i in selected}, reverse=True), float(factor))
+    return total, _collect(params)

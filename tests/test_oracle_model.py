@@ -1,0 +1,176 @@
+"""Pins for oracle/model.py: Alg. 1 and Alg. 2 run over a small multi-layer decoder.
+
+What fixes the expected values here is not the oracle itself:
+  * Alg. 1 must reproduce the gradient of ordinary whole-sequence training (Sec. 4 / Appendix on gradient
+    exactness: agreement to about 12 decimals in fp64) - the whole-sequence gradient comes from one plain
+    autograd pass that knows nothing of chunks;
+  * Alg. 2 under independent inclusion of every chunk with probability q, relay factor 1/q and an overall
+    1/q, is an unbiased estimator of that same gradient in EVERY layer (Sec. 5: a chain through p caches
+    survives with probability q^(p+1) and carries q^-(p+1)); the expectation is computed by enumerating all
+    2^k selections, so a factor applied once instead of per hop, or to the chunk's own rows, fails it;
+  * Alg. 2 with every chunk selected and factor 1 is Alg. 1; with a single selected chunk it is the plain
+    gradient of that chunk's loss with the caches treated as constants.
+"""
+import itertools
+
+import pytest
+import torch
+
+from oracle import model as om
+
+CFG = om.ModelConfig()
+
+
+def _data(seed, B, N, cfg=CFG):
+    g = torch.Generator().manual_seed(seed)
+    tok = torch.randint(0, cfg.vocab, (B, N), generator=g)
+    tgt = torch.randint(0, cfg.vocab, (B, N), generator=g)
+    return tok, tgt
+
+
+def _max_abs_diff(a, b):
+    return max(float((a[n] - b[n]).abs().max()) for n in a)
+
+
+def _scale_of(a):
+    return max(float(v.abs().max()) for v in a.values())
+
+
+@pytest.mark.parametrize("chunk_len,N", [(4, 16), (5, 15), (16, 16), (3, 12)])
+def test_seco_matches_whole_sequence_training(chunk_len, N):
+    p = om.init_params(CFG, seed=1)
+    tok, tgt = _data(2, 2, N)
+    loss_m, g_m = om.monolithic_grads(CFG, p, tok, tgt)
+    loss_s, g_s = om.seco_grads(CFG, p, tok, tgt, chunk_len)
+    assert abs(float(loss_m) - loss_s) < 1e-10 * abs(float(loss_m))
+    assert _max_abs_diff(g_m, g_s) < 1e-11 * _scale_of(g_m)
+    # every parameter really gets gradient (a dropped relay would zero none of them but shrink wk/wv: checked above)
+    assert all(float(v.abs().max()) > 0 for v in g_m.values())
+
+
+def test_seco_ragged_last_chunk():
+    p = om.init_params(CFG, seed=3)
+    tok, tgt = _data(4, 1, 14)
+    _, g_m = om.monolithic_grads(CFG, p, tok, tgt)
+    _, g_s = om.seco_grads(CFG, p, tok, tgt, 4)          # chunks 4,4,4,2
+    assert _max_abs_diff(g_m, g_s) < 1e-11 * _scale_of(g_m)
+
+
+def test_dropping_the_relay_is_detected():
+    """Sanity of the pin itself: SpaCO with all chunks and factor 0 (no relay) must NOT match."""
+    p = om.init_params(CFG, seed=1)
+    tok, tgt = _data(2, 2, 16)
+    _, g_m = om.monolithic_grads(CFG, p, tok, tgt)
+    _, g_0 = om.spaco_grads(CFG, p, tok, tgt, 4, range(4), 0.0)
+    assert _max_abs_diff(g_m, g_0) > 1e-3 * _scale_of(g_m)
+
+
+def test_spaco_all_chunks_factor_one_is_seco():
+    p = om.init_params(CFG, seed=5)
+    tok, tgt = _data(6, 2, 12)
+    _, g_s = om.seco_grads(CFG, p, tok, tgt, 3)
+    _, g_a = om.spaco_grads(CFG, p, tok, tgt, 3, [3, 0, 2, 1], 1.0)
+    assert _max_abs_diff(g_s, g_a) == 0.0
+
+
+def test_spaco_single_chunk_is_local_gradient():
+    """One selected chunk: nothing is relayed, so the factor cannot matter, and the result is the gradient
+    of J_i with the earlier chunks' KV held constant."""
+    p = om.init_params(CFG, seed=7)
+    tok, tgt = _data(8, 1, 12)
+    _, g_a = om.spaco_grads(CFG, p, tok, tgt, 4, [2], 1.0)
+    _, g_b = om.spaco_grads(CFG, p, tok, tgt, 4, [2], 5.0)
+    assert _max_abs_diff(g_a, g_b) == 0.0
+    # independent construction: whole-sequence graph, loss of chunk 2 only, K/V of rows < 8 detached
+    for t in p.values():
+        t.grad = None
+    with torch.no_grad():
+        _, kv01 = om._chunk_forward(CFG, p, tok[:, :8], tgt[:, :8], 0, om._empty_caches(CFG, 1, torch.float64))
+    loss, _ = om._chunk_forward(CFG, p, tok[:, 8:], tgt[:, 8:], 8, [(k.detach(), v.detach()) for k, v in kv01])
+    loss.backward()
+    g_c = om._collect(p)
+    assert _max_abs_diff(g_a, g_c) < 1e-12 * _scale_of(g_c)
+
+
+@pytest.mark.parametrize("q", [0.5, 0.25])
+def test_spaco_unbiased_in_every_layer_by_enumeration(q):
+    cfg = om.ModelConfig(n_layers=3, d_model=16, n_q_heads=2, n_kv_heads=1, head_dim=8, d_ff=24, vocab=11)
+    p = om.init_params(cfg, seed=11)
+    tok, tgt = _data(12, 1, 8, cfg)
+    k, C = 4, 2
+    _, g_m = om.monolithic_grads(cfg, p, tok, tgt)
+    mean = {n: torch.zeros_like(v) for n, v in g_m.items()}
+    for r in range(1, k + 1):
+        for sel in itertools.combinations(range(k), r):
+            prob = q ** r * (1 - q) ** (k - r)
+            _, g = om.spaco_grads(cfg, p, tok, tgt, C, sel, 1.0 / q)
+            for n in mean:
+                mean[n] += prob * g[n] / q
+    assert _max_abs_diff(mean, g_m) < 1e-11 * _scale_of(g_m)
+    # and a relay factor applied only once per chain (not per hop) would be biased: with factor 1 the mean differs
+    mean1 = {n: torch.zeros_like(v) for n, v in g_m.items()}
+    for r in range(1, k + 1):
+        for sel in itertools.combinations(range(k), r):
+            _, g = om.spaco_grads(cfg, p, tok, tgt, C, sel, 1.0)
+            for n in mean1:
+                mean1[n] += q ** r * (1 - q) ** (k - r) * g[n] / q
+    assert _max_abs_diff(mean1, g_m) > 1e-3 * _scale_of(g_m)
+
+
+def test_one_layer_model_matches_attention_oracle():
+    """With one layer the KV-gradient relay of the model oracle and the kernel-level oracle (oracle.attention)
+    describe the same quantity: the gradient on the layer's K and V under SpaCO weights."""
+    import numpy as np
+    from oracle import attention as oa
+    from oracle.selection import chunk_weights
+    cfg = om.ModelConfig(n_layers=1, d_model=16, n_q_heads=4, n_kv_heads=2, head_dim=8, d_ff=24, vocab=11)
+    p = om.init_params(cfg, seed=21)
+    tok, tgt = _data(22, 1, 12, cfg)
+    C, sel, f = 3, [3, 1, 0], 2.5
+    # model oracle: gradient reaching wk via the relay == h^T (relayed dK); recover dK itself through a probe:
+    # run stage 1/2 by hand and read the per-chunk gradient handed to the recomputed k, v.
+    ckpt, _ = om._stage1(cfg, p, tok, tgt, C)
+    handed = {}
+    for i in sorted(sel, reverse=True):
+        caches = [(torch.cat([c[0][0] for c in ckpt[:i]], 2), torch.cat([c[0][1] for c in ckpt[:i]], 2))] if i \
+            else om._empty_caches(cfg, 1, torch.float64)
+        loss, new_kv = om._chunk_forward(cfg, p, tok[:, i * C:(i + 1) * C], tgt[:, i * C:(i + 1) * C], i * C, caches)
+        k, v = new_kv[0]
+        k.retain_grad(); v.retain_grad()
+        roots, grads = [loss], [torch.ones_like(loss)]
+        if ckpt[i][0][0].grad is not None:
+            roots += [k, v]; grads += [f * ckpt[i][0][0].grad, f * ckpt[i][0][1].grad]
+        torch.autograd.backward(roots, grads)
+        handed[i] = (k.grad.clone(), v.grad.clone())
+    # kernel-level oracle on the same q, k, v, dO: build them from a whole-sequence pass
+    for t in p.values():
+        t.grad = None
+    x = p["emb"][tok]
+    h = om._rmsnorm(x, p["l0.norm1"])
+    q_ = (h @ p["l0.wq"]).view(1, 12, 4, 8).transpose(1, 2)
+    k_ = (h @ p["l0.wk"]).view(1, 12, 2, 8).transpose(1, 2)
+    v_ = (h @ p["l0.wv"]).view(1, 12, 2, 8).transpose(1, 2)
+    o_ = om._attend(q_, k_, v_, 0, cfg.scale)
+    o_.retain_grad()
+    x2 = x + o_.transpose(1, 2).reshape(1, 12, -1) @ p["l0.wo"]
+    x3 = x2 + torch.nn.functional.silu(om._rmsnorm(x2, p["l0.norm2"]) @ p["l0.w1"]) @ p["l0.w2"]
+    logits = om._rmsnorm(x3, p["norm_f"]) @ p["head"]
+    torch.nn.functional.cross_entropy(logits.reshape(12, -1), tgt.reshape(12), reduction="sum").backward()
+    dO = o_.grad.numpy()
+    qn, kn, vn = q_.detach().numpy(), k_.detach().numpy(), v_.detach().numpy()
+    gk = np.zeros_like(kn); gv = np.zeros_like(vn)
+    for i in sorted(sel, reverse=True):
+        w = chunk_weights(sel, i, f)
+        wrow = np.repeat(np.asarray(w, dtype=np.float64), C)
+        L, sl = (i + 1) * C, slice(i * C, (i + 1) * C)
+        o_i, lse_i = oa.chunk_attn_fwd(qn[:, :, sl], kn[:, :, :L], vn[:, :, :L], i * C, cfg.scale)
+        _, dk, dv = oa.chunk_attn_bwd(qn[:, :, sl], kn[:, :, :L], vn[:, :, :L], o_i, lse_i, dO[:, :, sl], i * C, cfg.scale)
+        gk[:, :, :L] += wrow[None, None, :, None] * dk
+        gv[:, :, :L] += wrow[None, None, :, None] * dv
+    # In a one-layer model the loss of chunk i reaches K/V rows only through attention, and dO of chunk i's rows
+    # is the same in the whole-sequence pass (rows are independent after attention), so the buffers must agree
+    # with what the model oracle handed to each selected chunk's recomputed k, v.
+    for i in sel:
+        sl = slice(i * C, (i + 1) * C)
+        np.testing.assert_allclose(handed[i][0].numpy(), gk[:, :, sl], rtol=0, atol=1e-12 * np.abs(gk).max())
+        np.testing.assert_allclose(handed[i][1].numpy(), gv[:, :, sl], rtol=0, atol=1e-12 * np.abs(gv).max())
