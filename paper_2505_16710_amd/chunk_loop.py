@@ -1,0 +1,122 @@
+"""SeCO / SpaCO training step of a small decoder, driven through the C ABI (Alg. 1 and Alg. 2 end to end).
+
+The attention of every layer, its backward and the whole KV-gradient relay run in the HIP library:
+each layer owns a KV cache and a pair of fp32 KV-gradient buffers that live for the whole step, the
+forward of a chunk is `seco_chunk_attn_fwd` against the cache, its backward is `seco_chunk_attn_bwd` /
+`spaco_chunk_attn_bwd`, which deposits the chunk's dK/dV on every visible cache row, and the gradient
+handed to the chunk's own recomputed K/V is simply the chunk's rows of those buffers (they hold what
+the later chunks deposited plus the chunk's own diagonal block: the relay of Alg. 1, `m_i.grad <-
+m'_i.grad`, with no copy).  Under SpaCO the deposits on earlier selected chunks carry the compensation
+factor, so a chain through p caches is scaled by factor^p (Sec. 5).
+
+The projections, norms, MLP and loss around the attention are ordinary PyTorch GPU ops with autograd
+(library GEMMs); only one chunk's graph is alive at a time, as in the paper.  There is no CPU path.
+
+Model (fixed here so that a checker can build the same function): pre-norm decoder, RMSNorm with
+eps 1e-6, grouped-query causal attention without positional encoding, MLP x + silu(h W1) W2, final
+RMSNorm, linear head, cross-entropy summed over tokens.  Parameter names: emb, head, norm_f and
+l{i}.norm1, l{i}.norm2, l{i}.wq, l{i}.wk, l{i}.wv, l{i}.wo, l{i}.w1, l{i}.w2, all stored [in, out].
+"""
+from __future__ import annotations
+
+import torch
+import torch.nn.functional as F
+
+from . import binding as _b
+
+
+class LayerState:
+    """KV cache (storage dtype) and fp32 KV-gradient buffers of one layer, [B, Hkv, N, D]."""
+
+    def __init__(self, B, Hkv, N, D, dtype, device):
+        self.k = torch.zeros(B, Hkv, N, D, dtype=dtype, device=device)
+        self.v = torch.zeros_like(self.k)
+        self.gk = torch.empty(B, Hkv, N, D, dtype=torch.float32, device=device)
+        self.gv = torch.empty_like(self.gk)
+
+
+class ChunkAttention(torch.autograd.Function):
+    """Attention of one chunk against a layer's cache; backward deposits into the layer's KV-gradient buffers."""
+
+    @staticmethod
+    def forward(ctx, q, k_new, v_new, state, q_start, scale, weights, weight_chunk_len):
+        C = q.shape[2]
+        state.k[:, :, q_start:q_start + C].copy_(k_new)
+        state.v[:, :, q_start:q_start + C].copy_(v_new)
+        o, lse = _b.seco_chunk_attn_fwd(q, state.k, state.v, q_start, scale,
+                                        o=torch.empty(q.shape, dtype=q.dtype, device=q.device))
+        ctx.save_for_backward(q, o, lse)
+        ctx.state, ctx.q_start, ctx.scale, ctx.weights, ctx.wlen = state, q_start, scale, weights, weight_chunk_len
+        return o
+
+    @staticmethod
+    def backward(ctx, d_o):
+        q, o, lse = ctx.saved_tensors
+        st, s0, C = ctx.state, ctx.q_start, q.shape[2]
+        d_o = d_o.contiguous()
+        if ctx.weights is None:
+            d_q = _b.seco_chunk_attn_bwd(q, st.k, st.v, o, lse, d_o, st.gk, st.gv, s0, ctx.scale)
+        else:
+            d_q = _b.spaco_chunk_attn_bwd(q, st.k, st.v, o, lse, d_o, st.gk, st.gv, s0, ctx.scale,
+                                          ctx.weights, ctx.wlen)
+        d_k = st.gk[:, :, s0:s0 + C].to(q.dtype, copy=True)
+        d_v = st.gv[:, :, s0:s0 + C].to(q.dtype, copy=True)
+        return d_q, d_k, d_v, None, None, None, None, None
+
+
+def _rmsnorm(x, g):
+    xf = x.float()
+    return (xf * torch.rsqrt((xf * xf).mean(dim=-1, keepdim=True) + 1e-6)).to(x.dtype) * g
+
+
+class ChunkedDecoder:
+    """Holds the parameters (dict name -> leaf tensor on the GPU) and runs SeCO / SpaCO steps."""
+
+    def __init__(self, params, n_layers, n_q_heads, n_kv_heads, head_dim):
+        self.p = params
+        self.n_layers, self.Hq, self.Hkv, self.D = n_layers, n_q_heads, n_kv_heads, head_dim
+        self.scale = float(head_dim) ** -0.5
+        _b.load_library()          # fail here, loudly, if the HIP library has not been built
+
+    def _chunk(self, tokens, targets, q_start, states, weights, wlen):
+        p, B, C = self.p, tokens.shape[0], tokens.shape[1]
+        x = p["emb"][tokens]
+        for l in range(self.n_layers):
+            h = _rmsnorm(x, p[f"l{l}.norm1"])
+            q = (h @ p[f"l{l}.wq"]).view(B, C, self.Hq, self.D).transpose(1, 2)
+            k = (h @ p[f"l{l}.wk"]).view(B, C, self.Hkv, self.D).transpose(1, 2)
+            v = (h @ p[f"l{l}.wv"]).view(B, C, self.Hkv, self.D).transpose(1, 2)
+            o = ChunkAttention.apply(q, k, v, states[l], q_start, self.scale, weights, wlen)
+            x = x + o.transpose(1, 2).reshape(B, C, self.Hq * self.D) @ p[f"l{l}.wo"]
+            h = _rmsnorm(x, p[f"l{l}.norm2"])
+            x = x + F.silu(h @ p[f"l{l}.w1"]) @ p[f"l{l}.w2"]
+        logits = _rmsnorm(x, p["norm_f"]) @ p["head"]
+        return F.cross_entropy(logits.reshape(B * C, -1).float(), targets.reshape(B * C), reduction="sum")
+
+    def step(self, tokens, targets, chunk_len, selected=None, factor=1.0):
+        """One SeCO step (selected is None: Alg. 1) or SpaCO step (Alg. 2, `selected` chunk indices,
+        relay factor `factor`).  Returns (sum of the chunk losses from stage 1, {name: gradient})."""
+        p = self.p
+        B, N = tokens.shape
+        dtype, dev = p["emb"].dtype, p["emb"].device
+        starts = list(range(0, N, chunk_len))
+        states = [LayerState(B, self.Hkv, N, self.D, dtype, dev) for _ in range(self.n_layers)]
+        for t in p.values():
+            t.grad = None
+        total = torch.zeros((), dtype=torch.float32, device=dev)
+        with torch.no_grad():                                           # stage 1: inference over all chunks
+            for s0 in starts:
+                total += self._chunk(tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, states, None, 0)
+        for st in states:
+            _b.kvgrad_zero(st.gk, st.gv)
+        if selected is None:
+            order = list(range(len(starts) - 1, -1, -1))
+        else:
+            order = sorted({int(i) for i in selected}, reverse=True)
+        for j in order:                                                 # stage 2: rebuild + back-propagate
+            w = None if selected is None else _b.spaco_chunk_weights(order, j, factor)
+            s0 = starts[j]
+            loss = self._chunk(tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, states, w, chunk_len)
+            loss.backward()
+        grads = {n: (t.grad if t.grad is not None else torch.zeros_like(t)) for n, t in p.items()}
+        return float(total), grads
