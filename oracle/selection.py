@@ -85,3 +85,20 @@ def chunk_weights(selected, j, factor):
             w[int(i)] = factor
     w[j] = 1.0
     return w
+
+
+def path_count(n, p):
+    """Number of gradient chains of length p (p edges, p + 1 nodes) in the complete DAG on n chunks
+    (Sec. 5, "Challenges in Unbiased Estimation", the binomial formula for d_p)."""
+    from math import comb
+    return comb(n, p + 1)
+
+
+def path_ratio(k, t, p):
+    """Dense-to-sparse ratio of the chain counts, k(k-1)...(k-p) / (t(t-1)...(t-p)) (same passage);
+    its reciprocal is the probability that one given chain survives a uniform draw of t of the k chunks."""
+    num = den = 1
+    for i in range(p + 1):
+        num *= k - i
+        den *= t - i
+    return num / den

@@ -174,3 +174,55 @@ def test_one_layer_model_matches_attention_oracle():
         sl = slice(i * C, (i + 1) * C)
         np.testing.assert_allclose(handed[i][0].numpy(), gk[:, :, sl], rtol=0, atol=1e-12 * np.abs(gk).max())
         np.testing.assert_allclose(handed[i][1].numpy(), gv[:, :, sl], rtol=0, atol=1e-12 * np.abs(gv).max())
+
+
+# ---- gradient chains: count, survival, and the bound by the number of layers (Sec. 5) ----------------------------
+
+def _count_paths_bruteforce(n, p):
+    """p-edge paths in the DAG with an edge i -> j for every i < j, by explicit walk."""
+    def walk(node, left):
+        if left == 0:
+            return 1
+        return sum(walk(nxt, left - 1) for nxt in range(node + 1, n))
+    return sum(walk(s, p) for s in range(n))
+
+
+def test_path_count_and_survival_probability():
+    from math import comb
+    from oracle.selection import path_count, path_ratio
+    for n in range(1, 8):
+        for p in range(0, n):
+            assert path_count(n, p) == _count_paths_bruteforce(n, p)
+    # the paper's figure: k = 6 dense, t = 4 sparse
+    assert path_count(6, 1) == 15 and path_count(4, 1) == 6
+    for k, t, p in [(6, 4, 1), (6, 4, 2), (8, 3, 2), (5, 5, 3)]:
+        assert abs(path_ratio(k, t, p) - path_count(k, p) / path_count(t, p)) < 1e-12
+        # survival of one fixed chain with p+1 nodes under a uniform t-subset, by enumeration
+        chain = set(range(p + 1))
+        hits = sum(1 for s in itertools.combinations(range(k), t) if chain <= set(s))
+        assert abs(hits / comb(k, t) - 1.0 / path_ratio(k, t, p)) < 1e-12
+    # t >> p limit: ratio -> (k/t)^(p+1)
+    assert abs(path_ratio(4000, 1000, 2) / 4.0 ** 3 - 1) < 1e-2
+
+
+@pytest.mark.parametrize("n_layers", [1, 2, 3])
+def test_chain_length_is_bounded_by_the_number_of_layers(n_layers):
+    """A chain through p caches carries factor^p, and a hop always leads to a lower layer, so the gradient is a
+    polynomial in the factor of degree min(n_layers, k - 1): its finite differences of that order are non-zero and
+    those of the next order vanish."""
+    cfg = om.ModelConfig(n_layers=n_layers, d_model=16, n_q_heads=2, n_kv_heads=1, head_dim=8, d_ff=24, vocab=11)
+    p = om.init_params(cfg, seed=31)
+    k, C = 5, 2
+    tok, tgt = _data(32, 1, k * C, cfg)
+    deg = min(n_layers, k - 1)
+    fs = [0.0, 1.0, 2.0, 3.0, 4.0][: deg + 2]
+    gs = [om.spaco_grads(cfg, p, tok, tgt, C, range(k), f)[1] for f in fs]
+    def diff(vals):
+        return [{n: b[n] - a[n] for n in a} for a, b in zip(vals[:-1], vals[1:])]
+    d = gs
+    for _ in range(deg):
+        d = diff(d)
+    top = max(_scale_of(x) for x in d)                     # order-`deg` differences: present
+    assert top > 1e-6 * _scale_of(gs[1])
+    d = diff(d)                                            # order deg+1: must vanish
+    assert max(_scale_of(x) for x in d) < 1e-9 * _scale_of(gs[-1])
