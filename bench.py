@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--calls", default="",
                     help="comma-separated chunk indices: instead of whole steps, time the forward + backward call pair "
                          "of just these chunks (per-kernel event times; used for counter collection)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time replays of it (removes the dispatch gaps between "
+                         "the short kernels of small chunks); no per-kernel events in this mode")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch kvgrad_accumulate on a 1 GiB pair of buffers (a plain streaming kernel of known "
                          "size: reads 2 GiB, writes 1 GiB) so that rocprofv3 FETCH_SIZE / WRITE_SIZE can be scaled")
@@ -81,14 +84,19 @@ def main():
             self.dq = torch.empty_like(self.q)
             self.gk = torch.empty(B, Hkv, N, D, device=dev, dtype=torch.float32)
             self.gv = torch.empty_like(self.gk)
-            self.ws = torch.empty(max(B * Hq * C * 4, 256), device=dev, dtype=torch.uint8)
+            # workspaces sized by the library for this shape (delta; partial results of the short-chunk path)
+            d = seco.binding.make_desc(self.rows(self.q, 0), self.kc, 0, scale, o=self.rows(self.o, 0), g=self.gk)
+            nf = seco.seco_workspace_bytes(d, seco.binding.SECO_OP_FWD)
+            nb = seco.seco_workspace_bytes(d, seco.binding.SECO_OP_BWD)
+            self.ws_fwd = torch.empty(nf, device=dev, dtype=torch.uint8) if nf else False
+            self.ws = torch.empty(max(nb, 256), device=dev, dtype=torch.uint8)
 
         def rows(self, t, j):
             return t[:, :, j * self.C:(j + 1) * self.C]
 
         def fwd(self, j):
             seco.seco_chunk_attn_fwd(self.rows(self.q, j), self.kc, self.vc, j * self.C, scale,
-                                     o=self.rows(self.o, j), lse=self.lse)
+                                     o=self.rows(self.o, j), lse=self.lse, ws=self.ws_fwd)
 
         def bwd(self, j, weights=None):
             args = (self.rows(self.q, j), self.kc, self.vc, self.rows(self.o, j), self.lse, self.rows(self.do, j),
@@ -134,14 +142,29 @@ def main():
                                                                        "seq_len": N}, "per_call": per_call}))
         return
 
+    run_step = step
+    if args.graph:
+        # the library allocates nothing, never synchronises and clears gK/gV with a kernel, so a step can be captured
+        args.no_profile = True
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run_step = graph.replay
+
     for _ in range(args.warmup):
-        step()
+        run_step()
     torch.cuda.synchronize()
     if not args.no_profile:
         seco.seco_profile_enable(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = None
@@ -159,6 +182,7 @@ def main():
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "seq_len": N, "chunk_len": C,
                    "n_chunks": k_chunks, "flops_per_step": flops_step},
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
+        "launch_mode": "hip_graph_replay" if args.graph else "eager",
     }
 
     if prof is not None:

@@ -88,7 +88,11 @@ typedef struct seco_desc {
  * k_cache  in   [B, Hkv, >= q_start + C, D]   (kv_stride); v_cache alike
  * o        out  [B, Hq, C, D]   (o_stride), overwritten
  * lse      out  fp32 [B, Hq, C] contiguous, overwritten
- * ws       workspace of seco_workspace_bytes(desc, SECO_OP_FWD) bytes (may be NULL when that is 0)
+ * ws       optional workspace, 256-byte aligned.  seco_workspace_bytes(desc, SECO_OP_FWD) is non-zero only for
+ *          bf16 calls with so few query rows that the row tiles cannot fill the GPU (short chunks, as in the
+ *          chunk-size study of Sec. 6.3); given at least that many bytes, the visible cache rows are divided
+ *          among several workgroups whose partial results are merged in a fixed order.  With ws NULL or smaller
+ *          the call computes the same O and LSE (to rounding) without the division, only slower.
  */
 int seco_chunk_attn_fwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
                         void* o, float* lse, void* ws, size_t ws_bytes, void* hip_stream);
@@ -102,7 +106,8 @@ int seco_chunk_attn_fwd(const seco_desc* desc, const void* q, const void* k_cach
  * for every visible cache row c.  gk/gv are accumulated into, never overwritten; rows at or
  * beyond q_start + C are not touched.  o, lse are the outputs of seco_chunk_attn_fwd for the
  * same desc; d_o has o's layout.
- * ws: seco_workspace_bytes(desc, SECO_OP_BWD) bytes, 256-byte aligned.
+ * ws: seco_workspace_bytes(desc, SECO_OP_BWD) bytes, 256-byte aligned (delta, plus the partial dQ of the
+ *     short-chunk path described at seco_chunk_attn_fwd); SECO_ERR_WORKSPACE if NULL, misaligned or smaller.
  */
 int seco_chunk_attn_bwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
                         const void* o, const float* lse, const void* d_o,
@@ -172,7 +177,8 @@ typedef enum seco_profile_kind {
   SECO_PROFILE_DQ = 2,      /* dQ kernel */
   SECO_PROFILE_DKDV = 3,    /* dK/dV kernel with the gK/gV accumulation */
   SECO_PROFILE_KVGRAD = 4,  /* kvgrad_zero / kvgrad_accumulate */
-  SECO_PROFILE_KINDS = 5
+  SECO_PROFILE_MERGE = 5,   /* merge of partial O / dQ on the short-chunk path */
+  SECO_PROFILE_KINDS = 6
 } seco_profile_kind;
 int seco_profile_enable(int on);
 int seco_profile_read(double* total_ms_host, int64_t* launches_host);

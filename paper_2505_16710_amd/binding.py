@@ -131,8 +131,11 @@ def _workspace(desc, op, like):
     return (torch.empty(max(n, 256), dtype=torch.uint8, device=like.device), n)
 
 
-def seco_chunk_attn_fwd(q, k_cache, v_cache, q_start, scale, o=None, lse=None, stream=None):
-    """O, LSE of one chunk against cache rows [0, q_start + C).  Returns (o, lse)."""
+def seco_chunk_attn_fwd(q, k_cache, v_cache, q_start, scale, o=None, lse=None, stream=None, ws=None):
+    """O, LSE of one chunk against cache rows [0, q_start + C).  Returns (o, lse).
+
+    ws: optional uint8 workspace tensor (see seco_workspace_bytes); allocated here when the shape wants one,
+    False to pass none."""
     import torch
     lib = load_library()
     if o is None:
@@ -140,8 +143,13 @@ def seco_chunk_attn_fwd(q, k_cache, v_cache, q_start, scale, o=None, lse=None, s
     if lse is None:
         lse = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
     d = make_desc(q, k_cache, q_start, scale, o=o)
+    if ws is False:            # explicitly none: the library then takes the direct path
+        ws = None
+    elif ws is None and seco_workspace_bytes(d, SECO_OP_FWD) > 0:
+        ws, _ = _workspace(d, SECO_OP_FWD, q)
     _check(lib.seco_chunk_attn_fwd(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(o), _ptr(lse),
-                                   None, 0, _stream(stream)), "seco_chunk_attn_fwd")
+                                   _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
+           "seco_chunk_attn_fwd")
     return o, lse
 
 
@@ -229,7 +237,7 @@ def spaco_chunk_weights(selected, j, factor):
     return list(w)
 
 
-PROFILE_KINDS = ("fwd", "delta", "dq", "dkdv", "kvgrad")
+PROFILE_KINDS = ("fwd", "delta", "dq", "dkdv", "kvgrad", "merge")
 
 
 def seco_profile_enable(on=True):

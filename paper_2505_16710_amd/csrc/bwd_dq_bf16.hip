@@ -9,6 +9,10 @@
 // through LDS at the end.  Scores are again computed transposed (S^T = K Q^T, dP^T = V dO^T)
 // so that LSE and delta are per-lane scalars and dS^T feeds dQ^T += K^T dS^T from registers;
 // K^T comes from the same K tile through the LDS transpose read.
+//
+// Short chunks (SPLIT = true): as in the forward, the rows of the G heads of a KV head are packed into one row
+// space and the visible cache rows of a row tile are divided among n_splits workgroups; each writes its partial
+// dQ (fp32, unscaled) to the workspace and dq_merge_kernel adds the partials in split order.
 #include "mfma_tiles.h"
 #include "seco_internal.h"
 
@@ -18,8 +22,9 @@ namespace {
 constexpr int BM = 128;
 constexpr int BNW = 64;   // cache rows per wavefront and tile
 
-template <int KH>
+template <int KH, bool SPLIT>
 __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
+  static_assert(!SPLIT || KH == 1, "the split variant uses the 4-wavefront shape");
   constexpr int BN = BNW * KH;
   constexpr int kTileBytes = BN * kRowBytes;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];   // 4 * kTileBytes: [buf][K|V]
@@ -30,15 +35,34 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int rb = wave & 3, kh = wave >> 2;
-  const int hg = item % p.G;
-  int rest = item / p.G;
-  const int mt = n_mtiles - 1 - rest % n_mtiles;
-  rest /= n_mtiles;
-  const int kvh = rest % p.Hkv, b = rest / p.Hkv;
-  const int h = kvh * p.G + hg;
+  int b, kvh, h, mt, m0, sp = 0;              // m0: first chunk-local row of this wavefront
+  if constexpr (SPLIT) {
+    sp = item % p.n_splits;
+    int rest = item / p.n_splits;
+    mt = n_mtiles - 1 - rest % n_mtiles;
+    rest /= n_mtiles;
+    kvh = rest % p.Hkv;
+    b = rest / p.Hkv;
+    const int v0 = mt * BM + rb * 32;          // packed row: head v0 / Cpad of the group, row v0 % Cpad
+    int hg = v0 / p.Cpad;
+    m0 = v0 - hg * p.Cpad;
+    if (hg >= p.G) {                           // past the last head of the group: idle wavefront (m0 >= C)
+      hg = p.G - 1;
+      m0 = p.Cpad;
+    }
+    h = kvh * p.G + hg;
+  } else {
+    const int hg = item % p.G;
+    int rest = item / p.G;
+    mt = n_mtiles - 1 - rest % n_mtiles;
+    rest /= n_mtiles;
+    kvh = rest % p.Hkv;
+    b = rest / p.Hkv;
+    h = kvh * p.G + hg;
+    m0 = mt * BM + rb * 32;
+  }
 
   const int kv_len = p.q_start + p.C;
-  const int m0 = mt * BM + rb * 32;
   const int row = m0 + l32;
   const int crow = min(row, p.C - 1);
   const int qpos = p.q_start + row;
@@ -65,15 +89,32 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
       for (int i = 0; i < 8; ++i) delta = __builtin_fmaf((float)of[i], (float)dof[t][i], delta);
     }
     delta += __shfl_xor(delta, 32);
-    if (kh == 0 && g == 0 && row < p.C) p.delta[stat] = delta;
+    if (kh == 0 && sp == 0 && g == 0 && row < p.C) p.delta[stat] = delta;
   }
   const float c = p.scale * kLog2e;
 
   const __bf16* kbase = static_cast<const __bf16*>(p.k) + b * p.kvs[0] + kvh * p.kvs[1];
   const __bf16* vbase = static_cast<const __bf16*>(p.v) + b * p.kvs[0] + kvh * p.kvs[1];
-  const int wg_kv_end = p.q_start + min((mt + 1) * BM, p.C);
+  int wg_kv_end;                               // columns any row of the workgroup sees
+  if constexpr (SPLIT) {
+    int rows_end = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int v = mt * BM + r * 32, hh = v / p.Cpad, mm = v - hh * p.Cpad;
+      if (hh < p.G && mm < p.C) rows_end = max(rows_end, min(mm + 32, p.C));
+    }
+    wg_kv_end = rows_end ? p.q_start + rows_end : 0;
+  } else {
+    wg_kv_end = p.q_start + min((mt + 1) * BM, p.C);
+  }
   const int n_tiles = (wg_kv_end + BN - 1) / BN;
   const int wave_kv_end = m0 < p.C ? p.q_start + min(m0 + 32, p.C) : 0;
+  int n_begin = 0, n_end = n_tiles;            // tiles of this workgroup
+  if constexpr (SPLIT) {
+    const int per = (n_tiles + p.n_splits - 1) / p.n_splits;
+    n_begin = sp * per;
+    n_end = min(n_tiles, n_begin + per);       // may be empty: the partial written below is then all zero
+  }
 
   // asynchronous global -> LDS copy of one K and one V tile: each wavefront copies 4 groups of 4 rows of each.
   // The per-lane byte offsets inside a tile never change; a tile that lies entirely inside the cache is copied
@@ -111,7 +152,7 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
 
-  copy_tile(0, 0);
+  if (n_begin < n_end) copy_tile(n_begin, 0);
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
     settle(qf[t]);
@@ -120,9 +161,9 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
   dma_wait_all();
   __syncthreads();
 
-  for (int n = 0; n < n_tiles; ++n) {
-    const int buf = n & 1;
-    if (n + 1 < n_tiles) copy_tile(n + 1, buf ^ 1);
+  for (int n = n_begin; n < n_end; ++n) {
+    const int buf = (n - n_begin) & 1;
+    if (n + 1 < n_end) copy_tile(n + 1, buf ^ 1);
     lds_char* kt = smem + buf * 2 * kTileBytes + kh * BNW * kRowBytes;
     lds_char* vt = kt + kTileBytes;
 #pragma unroll
@@ -181,6 +222,21 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
       }
   }
 
+  if constexpr (SPLIT) {
+    if (row < p.C) {
+      typedef float f32x4 __attribute__((ext_vector_type(4)));
+      float* po = p.part + ((int64_t)sp * p.B * p.Hq * p.C + stat) * kHeadDim;   // row < C: stat is this row's index
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x4 v = {dq[db][4 * r4], dq[db][4 * r4 + 1], dq[db][4 * r4 + 2], dq[db][4 * r4 + 3]};
+          *reinterpret_cast<f32x4*>(po + 32 * db + 8 * r4 + 4 * g) = v;
+        }
+    }
+    return;
+  }
+
   if (row < p.C) {
     __bf16* out = static_cast<__bf16*>(p.d_q) + b * p.qs[0] + h * p.qs[1] + (int64_t)row * p.qs[2];
 #pragma unroll
@@ -195,10 +251,10 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
   }
 }
 
-template <int KH>
+template <int KH, bool SPLIT>
 int launch_kh(const AttnParams& p, int n_mtiles, int total, hipStream_t s) {
   constexpr int smem = 4 * BNW * KH * kRowBytes;
-  auto kern = dq_bf16_kernel<KH>;
+  auto kern = dq_bf16_kernel<KH, SPLIT>;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
       hipSuccess)
     return SECO_ERR_LAUNCH;
@@ -212,9 +268,14 @@ int launch_kh(const AttnParams& p, int n_mtiles, int total, hipStream_t s) {
 }  // namespace
 
 int launch_dq_bf16(const AttnParams& p, hipStream_t s) {
+  if (p.n_splits > 1) {
+    const SplitPlan plan = split_plan(p.B, p.Hkv, p.G, p.C);
+    int rc = launch_kh<1, true>(p, plan.n_mtiles, plan.items * p.n_splits, s);
+    return rc ? rc : launch_dq_merge(p, s);
+  }
   const int n_mtiles = (p.C + BM - 1) / BM;
   const int total = p.B * p.Hq * n_mtiles;
-  return total < 2 * kNumCUs ? launch_kh<2>(p, n_mtiles, total, s) : launch_kh<1>(p, n_mtiles, total, s);
+  return total < 2 * kNumCUs ? launch_kh<2, false>(p, n_mtiles, total, s) : launch_kh<1, false>(p, n_mtiles, total, s);
 }
 
 }  // namespace seco

@@ -1,6 +1,6 @@
 // Bandwidth-bound helpers: KV-gradient buffer zero / axpy (the gradient relay of the
 // paper's appendix listing, "grad + base * scaler") and the softmax-gradient row term
-// delta = rowsum(dO * O).
+// delta = rowsum(dO * O); and the merge steps of the split forward / dQ kernels (short chunks).
 #include "seco_internal.h"
 
 namespace seco {
@@ -72,6 +72,63 @@ __global__ __launch_bounds__(256) void delta_kernel(AttnParams p) {
   if (lane == 0) p.delta[row] = acc;
 }
 
+// Merge of the split forward: thread (row, d4) combines the n_splits partial rows in split order,
+//   M = max m_s,  L = sum l_s 2^(m_s - M),  O = sum o_s 2^(m_s - M) / L,  LSE = (M + log2 L) ln 2;
+// a partial with m_s = -inf is empty (nothing was written for its O) and is skipped.
+__global__ __launch_bounds__(256) void fwd_merge_kernel(AttnParams p) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t R = (int64_t)p.B * p.Hq * p.C;
+  const int64_t rowid = i >> 5;
+  if (rowid >= R) return;
+  const int d4 = (int)(i & 31);
+  float M = -INFINITY;
+  for (int sp = 0; sp < p.n_splits; ++sp) M = fmaxf(M, p.part_ml[2 * (sp * R + rowid)]);
+  float L = 0.f;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int sp = 0; sp < p.n_splits; ++sp) {
+    const float m = p.part_ml[2 * (sp * R + rowid)];
+    if (m == -INFINITY) continue;
+    const float w = exp2f(m - M);
+    L += w * p.part_ml[2 * (sp * R + rowid) + 1];
+    const float4 x = *reinterpret_cast<const float4*>(p.part + (sp * R + rowid) * 128 + 4 * d4);
+    acc.x += w * x.x;
+    acc.y += w * x.y;
+    acc.z += w * x.z;
+    acc.w += w * x.w;
+  }
+  const float inv = 1.f / L;
+  const int row = (int)(rowid % p.C);
+  const int h = (int)((rowid / p.C) % p.Hq);
+  const int b = (int)(rowid / ((int64_t)p.C * p.Hq));
+  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  const bf16x4 v = {(__bf16)(acc.x * inv), (__bf16)(acc.y * inv), (__bf16)(acc.z * inv), (__bf16)(acc.w * inv)};
+  *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.o_out) + b * p.os[0] + h * p.os[1] + (int64_t)row * p.os[2] + 4 * d4) = v;
+  if (d4 == 0) p.lse[rowid] = (M + log2f(L)) * 0.6931471805599453f;
+}
+
+// Merge of the split dQ: dQ = scale * (sum of the partials in split order), rounded to bf16.
+__global__ __launch_bounds__(256) void dq_merge_kernel(AttnParams p) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t R = (int64_t)p.B * p.Hq * p.C;
+  const int64_t rowid = i >> 5;
+  if (rowid >= R) return;
+  const int d4 = (int)(i & 31);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int sp = 0; sp < p.n_splits; ++sp) {
+    const float4 x = *reinterpret_cast<const float4*>(p.part + (sp * R + rowid) * 128 + 4 * d4);
+    acc.x += x.x;
+    acc.y += x.y;
+    acc.z += x.z;
+    acc.w += x.w;
+  }
+  const int row = (int)(rowid % p.C);
+  const int h = (int)((rowid / p.C) % p.Hq);
+  const int b = (int)(rowid / ((int64_t)p.C * p.Hq));
+  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  const bf16x4 v = {(__bf16)(acc.x * p.scale), (__bf16)(acc.y * p.scale), (__bf16)(acc.z * p.scale), (__bf16)(acc.w * p.scale)};
+  *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.d_q) + b * p.qs[0] + h * p.qs[1] + (int64_t)row * p.qs[2] + 4 * d4) = v;
+}
+
 int grid_for(int64_t total) {
   const int64_t blocks = (total + 255) / 256;
   return (int)(blocks < 65536 ? blocks : 65536);  // grid-stride loop covers the rest
@@ -98,6 +155,24 @@ int launch_kvgrad_axpy(float* dst, const float* src, float scale, int B, int H, 
     ProfScope prof(kKernelKvgrad, s);
     hipLaunchKernelGGL(kvgrad_kernel<true>, dim3(grid_for(total)), dim3(256), 0, s, dst, src, scale, H, D / 4, gs[0],
                      gs[1], gs[2], r0, r1 - r0, total);
+  }
+  return launch_status();
+}
+
+int launch_fwd_merge(const AttnParams& p, hipStream_t s) {
+  const int64_t threads = (int64_t)p.B * p.Hq * p.C * 32;
+  {
+    ProfScope prof(kKernelMerge, s);
+    hipLaunchKernelGGL(fwd_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p);
+  }
+  return launch_status();
+}
+
+int launch_dq_merge(const AttnParams& p, hipStream_t s) {
+  const int64_t threads = (int64_t)p.B * p.Hq * p.C * 32;
+  {
+    ProfScope prof(kKernelMerge, s);
+    hipLaunchKernelGGL(dq_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p);
   }
   return launch_status();
 }

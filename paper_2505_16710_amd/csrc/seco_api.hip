@@ -64,6 +64,27 @@ size_t delta_bytes(const seco_desc* d) {
   return (n + 255) & ~(size_t)255;
 }
 
+size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+// workspace of the short-chunk (split) path; 0 when the shape never uses it
+size_t split_part_bytes(const seco_desc* d) {   // partial O or partial dQ, fp32
+  if (d->dtype != SECO_BF16) return 0;
+  const SplitPlan pl = split_plan(d->batch, d->n_kv_heads, d->n_q_heads / d->n_kv_heads, d->chunk_len);
+  if (pl.max_splits < 2) return 0;
+  return round256((size_t)pl.max_splits * d->batch * d->n_q_heads * d->chunk_len * d->head_dim * sizeof(float));
+}
+size_t split_ml_bytes(const seco_desc* d) {     // (max, sum) of the forward partials
+  if (split_part_bytes(d) == 0) return 0;
+  const SplitPlan pl = split_plan(d->batch, d->n_kv_heads, d->n_q_heads / d->n_kv_heads, d->chunk_len);
+  return round256((size_t)pl.max_splits * d->batch * d->n_q_heads * d->chunk_len * 2 * sizeof(float));
+}
+// number of splits of this call (1: direct path)
+int splits_for(const seco_desc* d) {
+  if (split_part_bytes(d) == 0) return 1;
+  const SplitPlan pl = split_plan(d->batch, d->n_kv_heads, d->n_q_heads / d->n_kv_heads, d->chunk_len);
+  return split_count(pl, d->q_start + d->chunk_len);
+}
+
 int check_fwd_like(const seco_desc* d) {
   int rc = check_desc(d);
   if (rc) return rc;
@@ -84,7 +105,6 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(d_q) ||
       !aligned16(gk) || !aligned16(gv) || !aligned16(lse))
     return SECO_ERR_ALIGN;
-  if (!ws || ws_bytes < delta_bytes(d) || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SECO_ERR_WORKSPACE;
   const int kv_len = d->q_start + d->chunk_len;
   const int tile = d->dtype == SECO_BF16 ? kColTileBf16 : kColTileF32;
 
@@ -108,11 +128,17 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
     }
   }
 
+  if (!ws || ws_bytes < delta_bytes(d) + split_part_bytes(d) || (reinterpret_cast<uintptr_t>(ws) & 255u))
+    return SECO_ERR_WORKSPACE;
+
   AttnParams p = make_params(d);
   p.q = q; p.k = k; p.v = v; p.o = o; p.d_o = d_o; p.d_q = d_q;
   p.lse = const_cast<float*>(lse);
   p.delta = static_cast<float*>(ws);
   p.gk = gk; p.gv = gv;
+  p.n_splits = splits_for(d);
+  p.Cpad = (d->chunk_len + 31) / 32 * 32;
+  p.part = reinterpret_cast<float*>(static_cast<char*>(ws) + delta_bytes(d));
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = d->dtype == SECO_BF16;
   // delta = rowsum(dO * O): the bf16 dQ kernel computes it in its prologue (and stores it for the dK/dV kernel)
@@ -194,15 +220,13 @@ extern "C" int seco_profile_read(double* total_ms, int64_t* launches) {
 
 extern "C" size_t seco_workspace_bytes(const seco_desc* desc, int op) {
   if (check_desc(desc) != SECO_OK) return (size_t)-1;
-  if (op == SECO_OP_FWD) return 0;
-  if (op == SECO_OP_BWD) return delta_bytes(desc);
+  if (op == SECO_OP_FWD) return split_part_bytes(desc) + split_ml_bytes(desc);
+  if (op == SECO_OP_BWD) return delta_bytes(desc) + split_part_bytes(desc);
   return (size_t)-1;
 }
 
 extern "C" int seco_chunk_attn_fwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
                                    void* o, float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
-  (void)ws;
-  (void)ws_bytes;
   int rc = check_fwd_like(desc);
   if (rc) return rc;
   if (!q || !k_cache || !v_cache || !o || !lse) return SECO_ERR_NULL;
@@ -210,6 +234,14 @@ extern "C" int seco_chunk_attn_fwd(const seco_desc* desc, const void* q, const v
     return SECO_ERR_ALIGN;
   AttnParams p = make_params(desc);
   p.q = q; p.k = k_cache; p.v = v_cache; p.o_out = o; p.lse = lse;
+  p.n_splits = 1;
+  p.Cpad = (desc->chunk_len + 31) / 32 * 32;
+  const size_t part_bytes = split_part_bytes(desc);
+  if (part_bytes && ws && !(reinterpret_cast<uintptr_t>(ws) & 255u) && ws_bytes >= part_bytes + split_ml_bytes(desc)) {
+    p.n_splits = splits_for(desc);
+    p.part = static_cast<float*>(ws);
+    p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + part_bytes);
+  }
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   return desc->dtype == SECO_BF16 ? launch_fwd_bf16(p, s) : launch_fwd_f32(p, s);
 }

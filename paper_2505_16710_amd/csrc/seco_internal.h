@@ -19,6 +19,10 @@ struct AttnParams {
   float* delta;      // [B, Hq, C] contiguous (workspace), backward only
   float* gk;
   float* gv;
+  float* part;       // split path: partial O (forward) or partial dQ (backward), fp32 [n_splits, B, Hq, C, D]
+  float* part_ml;    // split path, forward: (reference max in log2 units, sum) per partial row, [n_splits, B, Hq, C, 2]
+  int n_splits;      // > 1 selects the split path
+  int Cpad;          // C rounded up to 32: rows per head in the packed row space of the split path
   int B, Hq, Hkv, D, C, q_start, G;
   float scale;
   int64_t qs[3], os[3], kvs[3], gs[3];
@@ -35,6 +39,31 @@ struct SegTable {
   float weight[kMaxSegments];
   int tile_begin[kMaxSegments + 1];  // prefix sum of column tiles, in units of the launcher's tile width
 };
+
+// Split path of the bf16 forward and dQ kernels (short chunks): the rows of the G heads of a KV head are packed
+// into row tiles of 128, and the visible cache rows of a tile are divided among several workgroups.
+struct SplitPlan {
+  int n_mtiles;     // row tiles per (batch, KV head)
+  int items;        // B * Hkv * n_mtiles
+  int max_splits;   // 1: the split path is never used for this shape
+};
+inline SplitPlan split_plan(int B, int Hkv, int G, int C) {
+  SplitPlan pl;
+  const int cpad = (C + 31) / 32 * 32;
+  pl.n_mtiles = (G * cpad + 127) / 128;
+  pl.items = B * Hkv * pl.n_mtiles;
+  pl.max_splits = pl.items >= 256 ? 1 : (512 + pl.items - 1) / pl.items;
+  if (pl.max_splits > 64) pl.max_splits = 64;
+  return pl;
+}
+// number of splits for a call that sees kv_len cache rows: every split gets at least 4 tiles of 64 rows
+inline int split_count(const SplitPlan& pl, int kv_len) {
+  const int by_len = (kv_len + 63) / 64 / 4;
+  const int n = pl.max_splits < by_len ? pl.max_splits : by_len;
+  return n < 2 ? 1 : n;
+}
+int launch_fwd_merge(const AttnParams& p, hipStream_t s);   // O, LSE from the partials
+int launch_dq_merge(const AttnParams& p, hipStream_t s);    // dQ = scale * sum of the partials, in split order
 
 // fp32 reference-grade kernels (any head_dim that is a multiple of 4, up to 256)
 int launch_fwd_f32(const AttnParams& p, hipStream_t s);
@@ -60,7 +89,7 @@ int launch_kvgrad_axpy(float* dst, const float* src, float scale, int B, int H, 
 
 // Optional per-kernel timing (seco_profile_enable): a scope brackets one launch with HIP events
 // on the launch stream.  Disabled by default; then a scope costs one branch.
-enum KernelKind { kKernelFwd = 0, kKernelDelta, kKernelDq, kKernelDkdv, kKernelKvgrad, kKernelKinds };
+enum KernelKind { kKernelFwd = 0, kKernelDelta, kKernelDq, kKernelDkdv, kKernelKvgrad, kKernelMerge, kKernelKinds };
 struct ProfScope {
   ProfScope(KernelKind kind, hipStream_t s);
   ~ProfScope();

@@ -44,7 +44,7 @@ def fwd(d, q=FAKE, k=FAKE, v=FAKE, o=FAKE, lse=FAKE):
     return seco.load_library().seco_chunk_attn_fwd(C.byref(d), q, k, v, o, lse, None, 0, None)
 
 
-def bwd(d, ws=C.c_void_p(0x1000), ws_bytes=1 << 20, gk=FAKE):
+def bwd(d, ws=C.c_void_p(0x1000), ws_bytes=1 << 30, gk=FAKE):
     return seco.load_library().seco_chunk_attn_bwd(C.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, gk, FAKE,
                                                    ws, ws_bytes, None)
 
@@ -77,14 +77,14 @@ def test_spaco_weight_validation():
     def call(w, n, wlen):
         arr = (C.c_float * max(len(w), 1))(*w)
         return lib.spaco_chunk_attn_bwd(C.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
-                                        arr, n, wlen, C.c_void_p(0x1000), 1 << 20, None)
+                                        arr, n, wlen, C.c_void_p(0x1000), 1 << 30, None)
     assert call([1.0], 1, 256) == -7             # does not cover 512 rows
     assert call([1.0, 1.0, 1.0], 3, 256) == -7   # one chunk too many
     assert call([1.0, float("nan")], 2, 256) == -7
     assert call([1.0, float("inf")], 2, 256) == -7
     assert call([1.0, 1.0], 2, 0) == -7
     assert lib.spaco_chunk_attn_bwd(C.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
-                                    None, 2, 256, C.c_void_p(0x1000), 1 << 20, None) == -1
+                                    None, 2, 256, C.c_void_p(0x1000), 1 << 30, None) == -1
 
 
 def test_kvgrad_validation_and_workspace_size():
@@ -96,9 +96,18 @@ def test_kvgrad_validation_and_workspace_size():
     assert lib.kvgrad_accumulate(C.byref(d), FAKE, None, None, None, 1.0, 0, 4, None) == -1
     assert lib.kvgrad_accumulate(C.byref(d), FAKE, None, FAKE, None, 1.0, 0, 4, None) == -8   # dst aliases src
     assert lib.kvgrad_zero(C.byref(d), None, None, 0, 4, None) == 0                           # nothing to do
-    assert seco.seco_workspace_bytes(d, B.SECO_OP_FWD) == 0
-    assert seco.seco_workspace_bytes(d, B.SECO_OP_BWD) == 1 * 4 * 256 * 4
-    assert seco.seco_workspace_bytes(desc(chunk_len=3), B.SECO_OP_BWD) == 256
+    # long chunks (enough row tiles to fill the GPU): no forward workspace, delta only for the backward
+    big = desc(n_q_heads=32, n_kv_heads=8, chunk_len=1024)
+    assert seco.seco_workspace_bytes(big, B.SECO_OP_FWD) == 0
+    assert seco.seco_workspace_bytes(big, B.SECO_OP_BWD) == 1 * 32 * 1024 * 4
+    # fp32 never uses the split path
+    assert seco.seco_workspace_bytes(desc(dtype=B.SECO_F32), B.SECO_OP_FWD) == 0
+    # short chunk: 2 KV heads x 4 packed row tiles = 8 work items -> up to 64 splits of fp32 partials
+    rows = 1 * 4 * 256
+    assert seco.seco_workspace_bytes(d, B.SECO_OP_FWD) == 64 * rows * 128 * 4 + 64 * rows * 2 * 4
+    assert seco.seco_workspace_bytes(d, B.SECO_OP_BWD) == rows * 4 + 64 * rows * 128 * 4
+    assert bwd(d, ws_bytes=rows * 4) == -6            # delta alone is no longer enough for this shape
+    assert seco.seco_workspace_bytes(desc(dtype=B.SECO_F32, chunk_len=3), B.SECO_OP_BWD) == 256   # rounded up to 256
     assert "head_dim" in seco.seco_strerror(-3) and seco.seco_strerror(0) == "ok"
     assert seco.seco_strerror(-99) == "unknown status"
 

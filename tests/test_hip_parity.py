@@ -314,3 +314,104 @@ def test_cfg2_whole_layer_identities_in_the_benchmark_configuration():
     kgk = (k.double() * gk.double()).sum(dim=(2, 3))
     assert (qdq - kgk).abs().max() <= 2e-2 * kgk.abs().max().clamp_min(1.0)
     assert torch.isfinite(gk).all() and torch.isfinite(dq.float()).all()
+
+
+# ---- short chunks: packed heads + split cache range (the chunk sizes of the paper's Sec. 6.3 study) -------------
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,C", [
+    (1, 8, 2, 1024, 32),     # G = 4, one packed row tile per KV head, up to 4 splits
+    (1, 8, 2, 1184, 96),     # row tiles that straddle two heads
+    (1, 6, 2, 1100, 100),    # G = 3, chunk not a multiple of 32, idle wavefronts in the last tile
+    (2, 4, 4, 1024, 64),     # G = 1: half of every row tile idle
+    (1, 16, 2, 1536, 40),    # G = 8, second wavefront of each head partly valid
+    (1, 32, 8, 2048, 128),   # the benchmark's head counts
+])
+def test_bf16_short_chunks_seco_parity(B, Hq, Hkv, N, C):
+    x = small_layer(40, B, Hq, Hkv, N, 128, "bf16")
+    s = 1 / np.sqrt(128)
+    got = run_layer(x, C, s, "bf16")
+    ref = A.seco_layer(x["q"], x["k"], x["v"], x["do"], C, s)
+    check(got, ref, "bf16", f"bf16 short chunks {B,Hq,Hkv,N,C}")
+
+
+def test_bf16_short_chunks_spaco_parity():
+    N, C, sel, lam = 1024, 64, [15, 9, 3, 0], 4.0
+    x = small_layer(41, 1, 8, 2, N, 128, "bf16")
+    s = 1 / np.sqrt(128)
+    got = run_layer(x, C, s, "bf16", selected=sel, factor=lam)
+    ref = A.spaco_layer(x["q"], x["k"], x["v"], x["do"], C, s, sel, lam)
+    for n, r in zip(("dq", "gk", "gv"), ref[2:]):
+        assert max_rel(got[n], r) <= TOL["bf16"][n], n
+
+
+def test_short_chunk_forward_with_and_without_workspace():
+    """The split path (workspace given) and the direct path (none) are two evaluation orders of the same O, LSE."""
+    B, Hq, Hkv, N, C, q_start = 1, 8, 2, 1600, 64, 1536
+    x = small_layer(42, B, Hq, Hkv, N, 128, "bf16")
+    s = 1 / np.sqrt(128)
+    q, k, v = (to_dev(x[n], "bf16") for n in ("q", "k", "v"))
+    qc = q[:, :, q_start:q_start + C]
+    d = seco.binding.make_desc(qc, k, q_start, s)
+    assert seco.seco_workspace_bytes(d, seco.binding.SECO_OP_FWD) > 0
+    o1, l1 = seco.seco_chunk_attn_fwd(qc, k, v, q_start, s)
+    o2, l2 = seco.seco_chunk_attn_fwd(qc, k, v, q_start, s, ws=False)
+    o3, l3 = seco.seco_chunk_attn_fwd(qc, k, v, q_start, s)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o3) and torch.equal(l1, l3)             # the split path is deterministic
+    ref_o, ref_l = A.chunk_attn_fwd(x["q"][:, :, q_start:q_start + C], x["k"][:, :, :q_start + C],
+                                    x["v"][:, :, :q_start + C], q_start, s)
+    for o, l in ((o1, l1), (o2, l2)):
+        assert max_rel(to_host(o), ref_o) <= 1e-2
+        assert max_rel(to_host(l), ref_l) <= 1e-2
+
+
+def test_step_captured_in_a_hip_graph_replays_identically():
+    """The library allocates nothing, never synchronises and clears gK/gV with a kernel, so a whole SeCO step can be
+    captured into a HIP graph.  Every replay (with eager work and synchronisations in between, and the outputs
+    poisoned before each replay) must reproduce the eager result bit for bit (the kernels are deterministic)."""
+    B, Hq, Hkv, N, C = 1, 8, 2, 768, 128           # short chunks: split kernels and merges are in the graph too
+    x = small_layer(50, B, Hq, Hkv, N, 128, "bf16")
+    s = 1 / np.sqrt(128)
+    q, k, v, do = (to_dev(x[n], "bf16") for n in ("q", "k", "v", "do"))
+    o = torch.empty_like(q)
+    dq = torch.empty_like(q)
+    lse = torch.empty(B, Hq, C, dtype=torch.float32, device=DEV)
+    gk = torch.empty(B, Hkv, N, 128, dtype=torch.float32, device=DEV)
+    gv = torch.empty_like(gk)
+    d0 = seco.binding.make_desc(q[:, :, :C], k, 0, s, g=gk)
+    ws_f = torch.empty(max(seco.seco_workspace_bytes(d0, seco.binding.SECO_OP_FWD), 256), dtype=torch.uint8, device=DEV)
+    ws_b = torch.empty(max(seco.seco_workspace_bytes(d0, seco.binding.SECO_OP_BWD), 256), dtype=torch.uint8, device=DEV)
+
+    def step():
+        seco.kvgrad_zero(gk, gv)
+        for j in range(N // C - 1, -1, -1):
+            sl = slice(j * C, (j + 1) * C)
+            seco.seco_chunk_attn_fwd(q[:, :, sl], k, v, j * C, s, o=o[:, :, sl], lse=lse, ws=ws_f)
+            seco.seco_chunk_attn_bwd(q[:, :, sl], k, v, o[:, :, sl], lse, do[:, :, sl], gk, gv, j * C, s,
+                                     d_q=dq[:, :, sl], ws=ws_b)
+
+    outs = (o, dq, gk, gv)
+    step()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in outs]
+    ref = A.seco_layer(x["q"], x["k"], x["v"], x["do"], C, s)
+    assert max_rel(to_host(gk), ref[3]) <= 2e-2 and max_rel(to_host(dq), ref[2]) <= 2e-2
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in outs:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, e in zip(outs, eager):
+            assert torch.equal(t, e), rep
+        (q.float() @ q.float().transpose(-1, -2)).sum().item()      # unrelated eager work between replays

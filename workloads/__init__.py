@@ -55,6 +55,12 @@ CONFIGS = {
     "cfg5_c1024": Config("cfg5_c1024", "bf16", 2, 32, 8, 128, 32768, 1024, seed=4, rope_like=True, spaco_t=8),
     "cfg5_c2048": Config("cfg5_c2048", "bf16", 2, 32, 8, 128, 32768, 2048, seed=4, rope_like=True, spaco_t=4),
     "cfg5_c4096": Config("cfg5_c4096", "bf16", 2, 32, 8, 128, 32768, 4096, seed=4, rope_like=True, spaco_t=2),
+    # the paper's own chunk-size sweep (Sec. 6.3: 16K tokens, chunks of 32 .. 512, SpaCO with t = 8)
+    "small_c32": Config("small_c32", "bf16", 1, 32, 8, 128, 16384, 32, seed=5, spaco_t=8),
+    "small_c64": Config("small_c64", "bf16", 1, 32, 8, 128, 16384, 64, seed=5, spaco_t=8),
+    "small_c128": Config("small_c128", "bf16", 1, 32, 8, 128, 16384, 128, seed=5, spaco_t=8),
+    "small_c256": Config("small_c256", "bf16", 1, 32, 8, 128, 16384, 256, seed=5, spaco_t=8),
+    "small_c512": Config("small_c512", "bf16", 1, 32, 8, 128, 16384, 512, seed=5, spaco_t=8),
 }
 
 
