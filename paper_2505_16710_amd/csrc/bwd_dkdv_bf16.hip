@@ -335,13 +335,23 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   // exclusive read-modify-write of this workgroup's gK/gV rows: role A adds dV, role B adds s * dK
   float* gbase = (role == 0 ? p.gv : p.gk) + b * p.gs[0] + kvh * p.gs[1];
   const float wf = role == 0 ? weight : weight * p.scale;
+  // All 64 old values are requested before the first one is used (rows past the tile's end read a clamped
+  // address and are not written back): one memory round trip instead of one per group of rows.
+  float old[16][4];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int kvrow = min(n0 + 8 * (r >> 2) + 4 * g + (r & 3), c_end - 1);
+    const float* gr = gbase + (int64_t)kvrow * p.gs[2] + l32;
+#pragma unroll
+    for (int db = 0; db < 4; ++db) old[r][db] = gr[32 * db];
+  }
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int kvrow = n0 + 8 * (r >> 2) + 4 * g + (r & 3);
     if (kvrow < c_end) {
       float* gr = gbase + (int64_t)kvrow * p.gs[2] + l32;
 #pragma unroll
-      for (int db = 0; db < 4; ++db) gr[32 * db] += wf * acc[db][r];
+      for (int db = 0; db < 4; ++db) gr[32 * db] = old[r][db] + wf * acc[db][r];
     }
   }
 }
