@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--calls", default="",
                     help="comma-separated chunk indices: instead of whole steps, time the forward + backward call pair "
                          "of just these chunks (per-kernel event times; used for counter collection)")
+    ap.add_argument("--schedules", action="store_true",
+                    help="also time a whole layer of --config under Alg. 1 and Alg. 2 (needs a config with spaco_t)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time replays of it (removes the dispatch gaps between "
                          "the short kernels of small chunks); no per-kernel events in this mode")
@@ -157,11 +159,26 @@ def main():
             step()
         run_step = graph.replay
 
-    for _ in range(args.warmup):
+    # Per-kernel event times come from the warm-up steps (every launch bracketed); in the timed steps only the
+    # launches of the dominant kernel are bracketed, because a pair of events costs a few microseconds per launch
+    # and would otherwise slow the very region that gives `value` by about 3 %.
+    warm_prof = None
+    for i in range(args.warmup):
+        if not args.no_profile and i == args.warmup - 1:      # the last warm-up step is the profiled one
+            torch.cuda.synchronize()
+            seco.seco_profile_enable(True)
         run_step()
     torch.cuda.synchronize()
+    if not args.no_profile and args.warmup > 0:
+        warm_prof = seco.seco_profile_read()
+        seco.seco_profile_enable(False)
+    dom = None
     if not args.no_profile:
-        seco.seco_profile_enable(True)
+        if warm_prof is not None:
+            dom = max(("fwd", "dq", "dkdv"), key=lambda kd: warm_prof[kd][0])
+            seco.seco_profile_enable(kinds=[dom])
+        else:
+            seco.seco_profile_enable(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         run_step()
@@ -188,50 +205,52 @@ def main():
     if prof is not None:
         alg = {"fwd": flops_fwd, "dq": flops_dq, "dkdv": flops_dkdv}
         kern = {}
-        for kind, (ms, n) in prof.items():
+        kprof, ksteps = (warm_prof, 1) if warm_prof is not None else (prof, args.steps)
+        for kind, (ms, n) in kprof.items():
             if n:
-                kern[kind] = {"launches": int(n), "avg_ms": round(ms / n, 5), "total_ms_per_step": round(ms / args.steps, 4)}
+                kern[kind] = {"launches": int(n), "avg_ms": round(ms / n, 5), "total_ms_per_step": round(ms / ksteps, 4)}
                 if kind in alg:
-                    kern[kind]["tflops"] = round(alg[kind] * args.steps / (ms * 1e-3) / 1e12, 2)
-        dom = max(alg, key=lambda kd: prof[kd][0])
+                    kern[kind]["tflops"] = round(alg[kind] * ksteps / (ms * 1e-3) / 1e12, 2)
+        kern["measured_in"] = "last warm-up step (every launch bracketed by events)" if warm_prof is not None else "timed steps"
+        if dom is None:
+            dom = max(alg, key=lambda kd: prof[kd][0])
         ms, n = prof[dom]
         achieved = alg[dom] * args.steps / (ms * 1e-3) / 1e12
         out["roofline"] = {"bound": "mfma", "kernel": dom + "_bf16_kernel" if cfg.dtype == "bf16" else dom + "_f32_kernel",
                            "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                            "traffic": HBM_TRAFFIC_PER_LAUNCH.get((cfg.name, dom)),
-                           "avg_launch_ms": round(ms / n, 5), "launches": int(n)}
+                           "avg_launch_ms": round(ms / n, 5), "launches": int(n),
+                           "measured_in": "timed steps (HIP events around every launch of this kernel)"}
         out["kernels"] = kern
 
-    if not args.no_layer32k and cfg.dtype == "bf16":
-        # seconds per 32K-token layer under the two schedules (Alg. 1: 2 fwd + bwd per chunk;
-        # Alg. 2: k fwd, then fwd + bwd for the t selected chunks), 16 chunks of 2048, t = 4
-        del L
-        torch.cuda.empty_cache()
-        c3 = CONFIGS["cfg3"]
-        L3 = Layer(c3.seq_len, c3.chunk_len)
-        k3, t3 = c3.n_chunks, c3.spaco_t
-        sel = seco.spaco_select_chunks(c3.seed, 0, k3, t3)
-        lam = k3 / t3
+    def layer_seconds(cx):
+        """Seconds per layer of configuration cx under the two schedules (Alg. 1: k forwards, then forward +
+        backward per chunk in reverse order; Alg. 2: k forwards, then forward + backward for the t selected
+        chunks with factor k/t), best of 3."""
+        Lx = Layer(cx.seq_len, cx.chunk_len)
+        kx, tx = cx.n_chunks, cx.spaco_t
+        sel = seco.spaco_select_chunks(cx.seed, 0, kx, tx)
+        lam = kx / tx
 
         def seco_layer():
-            for j in range(k3):
-                L3.fwd(j)
-            seco.kvgrad_zero(L3.gk, L3.gv)
-            for j in range(k3 - 1, -1, -1):
-                L3.fwd(j)
-                L3.bwd(j)
+            for j in range(kx):
+                Lx.fwd(j)
+            seco.kvgrad_zero(Lx.gk, Lx.gv)
+            for j in range(kx - 1, -1, -1):
+                Lx.fwd(j)
+                Lx.bwd(j)
 
         def spaco_layer():
-            for j in range(k3):
-                L3.fwd(j)
-            seco.kvgrad_zero(L3.gk, L3.gv)
+            for j in range(kx):
+                Lx.fwd(j)
+            seco.kvgrad_zero(Lx.gk, Lx.gv)
             for j in sel:
-                L3.fwd(j)
-                L3.bwd(j, seco.spaco_chunk_weights(sel, j, lam))
+                Lx.fwd(j)
+                Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam))
 
         res = {}
-        for name, fn in (("seco", seco_layer), ("spaco_t4", spaco_layer)):
+        for name, fn in (("seco", seco_layer), (f"spaco_t{tx}", spaco_layer)):
             fn()
             torch.cuda.synchronize()
             best = 1e9
@@ -242,8 +261,17 @@ def main():
                 best = min(best, time.perf_counter() - a)
             res[name] = round(best, 5)
         res["selected_chunks"] = sel
-        out["sec_per_32k_layer"] = res
-        del L3
+        return res
+
+    if args.schedules and cfg.dtype == "bf16" and cfg.spaco_t > 0:
+        # the two schedules on the benchmarked configuration itself
+        out["sec_per_layer"] = dict(layer_seconds(cfg), seq_len=N, chunk_len=C)
+
+    if not args.no_layer32k and cfg.dtype == "bf16":
+        # seconds per 32K-token layer: 16 chunks of 2048, t = 4
+        del L
+        torch.cuda.empty_cache()
+        out["sec_per_32k_layer"] = layer_seconds(CONFIGS["cfg3"])
 
     if not args.no_cpu_baseline:
         # the oracle, as it stands, on one independent (batch, KV head) unit of the same workload

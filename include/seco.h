@@ -180,7 +180,10 @@ typedef enum seco_profile_kind {
   SECO_PROFILE_MERGE = 5,   /* merge of partial O / dQ on the short-chunk path */
   SECO_PROFILE_KINDS = 6
 } seco_profile_kind;
-int seco_profile_enable(int on);
+int seco_profile_enable(int on);                    /* all kinds on / off; forgets recorded events */
+int seco_profile_enable_kinds(uint32_t kind_mask);  /* bit k set: time kernels of kind k only (events cost a few
+                                                       microseconds per launch, so a benchmark brackets only what
+                                                       it reports) */
 int seco_profile_read(double* total_ms_host, int64_t* launches_host);
 
 /* Workspace bytes an entry point needs for this desc (0 if none; (size_t)-1 on an invalid desc). */

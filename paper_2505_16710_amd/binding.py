@@ -62,7 +62,8 @@ def load_library():
     lib.seco_strerror.restype = C.c_char_p
     lib.seco_profile_enable.argtypes = [C.c_int]
     lib.seco_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
-    lib.seco_profile_enable.restype = lib.seco_profile_read.restype = C.c_int
+    lib.seco_profile_enable_kinds.argtypes = [C.c_uint32]
+    lib.seco_profile_enable.restype = lib.seco_profile_read.restype = lib.seco_profile_enable_kinds.restype = C.c_int
     for name in ("seco_chunk_attn_fwd", "seco_chunk_attn_bwd", "spaco_chunk_attn_bwd", "kvgrad_zero",
                  "kvgrad_accumulate", "spaco_select_chunks", "spaco_chunk_weights"):
         getattr(lib, name).restype = C.c_int
@@ -240,8 +241,15 @@ def spaco_chunk_weights(selected, j, factor):
 PROFILE_KINDS = ("fwd", "delta", "dq", "dkdv", "kvgrad", "merge")
 
 
-def seco_profile_enable(on=True):
-    _check(load_library().seco_profile_enable(1 if on else 0), "seco_profile_enable")
+def seco_profile_enable(on=True, kinds=None):
+    """Time every kernel launch (on=True), none (False), or only the named kinds (subset of PROFILE_KINDS)."""
+    if kinds is not None:
+        mask = 0
+        for k in kinds:
+            mask |= 1 << PROFILE_KINDS.index(k)
+        _check(load_library().seco_profile_enable_kinds(mask), "seco_profile_enable_kinds")
+    else:
+        _check(load_library().seco_profile_enable(1 if on else 0), "seco_profile_enable")
 
 
 def seco_profile_read():

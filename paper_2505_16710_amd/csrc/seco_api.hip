@@ -167,12 +167,12 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
 namespace seco {
 namespace {
 struct ProfRecord { int kind; hipEvent_t start, stop; };
-bool g_prof_on = false;
+unsigned g_prof_mask = 0;   // bit k set: kernels of kind k are timed
 std::vector<ProfRecord> g_prof;
 }  // namespace
 
 ProfScope::ProfScope(KernelKind kind, hipStream_t s) : stream(s), slot(-1) {
-  if (!g_prof_on) return;
+  if (!(g_prof_mask >> (unsigned)kind & 1u)) return;
   ProfRecord r;
   r.kind = kind;
   if (hipEventCreate(&r.start) != hipSuccess) return;
@@ -188,15 +188,17 @@ ProfScope::~ProfScope() {
 
 using namespace seco;
 
-extern "C" int seco_profile_enable(int on) {
+extern "C" int seco_profile_enable_kinds(uint32_t kind_mask) {
   for (ProfRecord& r : g_prof) {
     (void)hipEventDestroy(r.start);
     (void)hipEventDestroy(r.stop);
   }
   g_prof.clear();
-  g_prof_on = on != 0;
+  g_prof_mask = kind_mask & ((1u << SECO_PROFILE_KINDS) - 1u);
   return SECO_OK;
 }
+
+extern "C" int seco_profile_enable(int on) { return seco_profile_enable_kinds(on ? ~0u : 0u); }
 
 extern "C" int seco_profile_read(double* total_ms, int64_t* launches) {
   if (!total_ms || !launches) return SECO_ERR_NULL;
