@@ -157,6 +157,24 @@ int kvgrad_accumulate(const seco_desc* desc, float* dst_k, float* dst_v, const f
 int spaco_select_chunks(uint64_t seed, uint64_t step, int32_t k, int32_t t, int32_t* out_host);
 
 /*
+ * Selection by independent inclusion, host only: every chunk 0..k-1 is selected with probability q, independently
+ * (the sampling law under which the survival argument of Sec. 5, "Compensation Factor", holds exactly: a chain
+ * through p+1 chunks survives with probability q^(p+1); with relay factor 1/q and an overall 1/q the gradient
+ * estimate is unbiased).  Same generator and key as spaco_select_chunks; chunk i is selected iff the i-th 64-bit
+ * draw is below floor(q * 2^64).  0 < q <= 1.
+ * out_host: HOST array of k int32; the selected indices, DESCENDING, are written to its front and their number
+ * (possibly 0) to *n_selected_host.
+ */
+int spaco_select_bernoulli(uint64_t seed, uint64_t step, int32_t k, double q, int32_t* out_host,
+                           int32_t* n_selected_host);
+
+/*
+ * The compensation factor k/t of Sec. 5, limited to `cap` when cap > 0 (Sec. 6.4 trains with a cap of 2).
+ * Returns a negative value on invalid arguments (k < 1, t < 1, t > k).
+ */
+float spaco_compensation_factor(int32_t k, int32_t t, float cap);
+
+/*
  * Weight vector for the backward call of chunk j under the paper's policy, host only:
  * w[i] = factor for i in selected, i < j;  w[j] = 1;  0 otherwise.
  * factor is k/t (Sec. 5), optionally capped by the caller (Sec. 6.4).

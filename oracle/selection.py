@@ -66,6 +66,18 @@ def select_chunks(seed, step, k, t):
     return np.array(sorted(perm[:t], reverse=True), dtype=np.int32)
 
 
+def select_bernoulli(seed, step, k, q):
+    """Independent inclusion of every chunk with probability q (the law under which the survival argument of
+    Sec. 5, "Compensation Factor", is exact): chunk i is selected iff the i-th draw of the (seed, step) stream is
+    below floor(q * 2^64).  Returns the selected indices, descending (possibly empty)."""
+    if not (0.0 < q <= 1.0):
+        raise ValueError("need 0 < q <= 1")
+    rng = stream_for(seed, step)
+    threshold = int(q * 2.0 ** 64) if q < 1.0 else 1 << 64     # exact: scaling a double by a power of two
+    picked = [i for i in range(k) if rng.next() < threshold]
+    return np.array(picked[::-1], dtype=np.int32)
+
+
 def compensation_factor(k, t, cap=None):
     """k/t (Sec. 5, "Compensation Factor"), optionally limited to `cap` (Sec. 6.4)."""
     lam = k / t

@@ -19,5 +19,7 @@ from .binding import (  # noqa: F401
     seco_workspace_bytes,
     spaco_chunk_attn_bwd,
     spaco_chunk_weights,
+    spaco_compensation_factor,
+    spaco_select_bernoulli,
     spaco_select_chunks,
 )

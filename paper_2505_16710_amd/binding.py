@@ -56,6 +56,10 @@ def load_library():
     lib.kvgrad_accumulate.argtypes = [dp, fp, fp, fp, fp, C.c_float, i64, i64, vp]
     lib.spaco_select_chunks.argtypes = [C.c_uint64, C.c_uint64, i32, i32, C.POINTER(i32)]
     lib.spaco_chunk_weights.argtypes = [C.POINTER(i32), i32, i32, C.c_float, C.POINTER(C.c_float)]
+    lib.spaco_select_bernoulli.argtypes = [C.c_uint64, C.c_uint64, i32, C.c_double, C.POINTER(i32), C.POINTER(i32)]
+    lib.spaco_select_bernoulli.restype = C.c_int
+    lib.spaco_compensation_factor.argtypes = [i32, i32, C.c_float]
+    lib.spaco_compensation_factor.restype = C.c_float
     lib.seco_workspace_bytes.argtypes = [dp, C.c_int]
     lib.seco_workspace_bytes.restype = sz
     lib.seco_strerror.argtypes = [C.c_int]
@@ -228,6 +232,23 @@ def spaco_select_chunks(seed, step, k, t):
     out = (C.c_int32 * max(int(t), 1))()
     _check(load_library().spaco_select_chunks(int(seed), int(step), int(k), int(t), out), "spaco_select_chunks")
     return list(out[:t])
+
+
+def spaco_select_bernoulli(seed, step, k, q):
+    """Every chunk of 0..k-1 selected independently with probability q; indices descending (list of int)."""
+    out = (C.c_int32 * max(int(k), 1))()
+    n = C.c_int32(0)
+    _check(load_library().spaco_select_bernoulli(int(seed), int(step), int(k), float(q), out, C.byref(n)),
+           "spaco_select_bernoulli")
+    return list(out[:n.value])
+
+
+def spaco_compensation_factor(k, t, cap=0.0):
+    """k/t, limited to cap when cap > 0."""
+    lam = load_library().spaco_compensation_factor(int(k), int(t), float(cap))
+    if lam < 0:
+        raise SecoError(-8, "spaco_compensation_factor")
+    return lam
 
 
 def spaco_chunk_weights(selected, j, factor):

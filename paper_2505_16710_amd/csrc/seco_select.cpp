@@ -2,6 +2,7 @@
 // distinct indices"), the per-call chunk weight vector (Alg. 2 with the compensation
 // factor of Sec. 5), and status strings.
 #include <algorithm>
+#include <cmath>
 #include <functional>
 #include <vector>
 
@@ -49,6 +50,30 @@ extern "C" int spaco_select_chunks(uint64_t seed, uint64_t step, int32_t k, int3
   std::sort(perm.begin(), perm.begin() + t, std::greater<int32_t>());
   std::copy(perm.begin(), perm.begin() + t, out_host);
   return SECO_OK;
+}
+
+extern "C" int spaco_select_bernoulli(uint64_t seed, uint64_t step, int32_t k, double q, int32_t* out_host,
+                                      int32_t* n_selected_host) {
+  if (!out_host || !n_selected_host) return SECO_ERR_NULL;
+  if (k < 1 || !(q > 0.0) || !(q <= 1.0)) return SECO_ERR_RANGE;
+  SplitMix64 rng{finalise(seed ^ finalise(step + kGolden))};
+  // q * 2^64 is exact in double (a power-of-two scaling); below 1 it fits 64 bits and converts by truncation
+  const bool all = q >= 1.0;
+  const uint64_t threshold = all ? 0 : (uint64_t)std::ldexp(q, 64);
+  int32_t n = 0;
+  for (int32_t i = 0; i < k; ++i) {
+    const uint64_t u = rng.next();
+    if (all || u < threshold) out_host[n++] = i;
+  }
+  std::reverse(out_host, out_host + n);
+  *n_selected_host = n;
+  return SECO_OK;
+}
+
+extern "C" float spaco_compensation_factor(int32_t k, int32_t t, float cap) {
+  if (k < 1 || t < 1 || t > k) return -1.f;
+  const float lam = (float)((double)k / (double)t);
+  return cap > 0.f && cap < lam ? cap : lam;
 }
 
 extern "C" int spaco_chunk_weights(const int32_t* selected_host, int32_t n_selected, int32_t j, float factor,

@@ -134,3 +134,46 @@ def test_chunk_weights_match_oracle():
     w = (C.c_float * 4)()
     assert lib.spaco_chunk_weights(None, 0, -1, 1.0, w) == -8
     assert lib.spaco_chunk_weights(None, 2, 1, 1.0, w) == -1
+
+
+def test_bernoulli_selection_matches_oracle_bit_exactly_and_has_the_right_rate():
+    for k in (1, 5, 16, 128, 512):
+        for q in (1.0, 0.5, 0.25, 1 / 3, 0.9, 1e-3, 8 / 128):
+            for seed in (0, 7, 2 ** 64 - 1):
+                for step in (0, 3, 2 ** 33):
+                    got = seco.spaco_select_bernoulli(seed, step, k, q)
+                    assert got == S.select_bernoulli(seed, step, k, q).tolist()
+                    assert got == sorted(set(got), reverse=True) and all(0 <= i < k for i in got)
+    assert seco.spaco_select_bernoulli(1, 2, 9, 1.0) == list(range(8, -1, -1))
+    # inclusion frequency of every chunk over many steps ~ q (binomial, 6 sigma)
+    k, q, n = 16, 0.25, 4000
+    counts = np.zeros(k)
+    for step in range(n):
+        counts[seco.spaco_select_bernoulli(123, step, k, q)] += 1
+    assert np.all(np.abs(counts - n * q) < 6 * np.sqrt(n * q * (1 - q)))
+    # pairs are independent: joint frequency of chunks 2 and 11 ~ q^2
+    joint = sum(1 for step in range(n) if {2, 11} <= set(seco.spaco_select_bernoulli(123, step, k, q)))
+    assert abs(joint - n * q * q) < 6 * np.sqrt(n * q * q * (1 - q * q))
+    lib = seco.load_library()
+    out, cnt = (C.c_int32 * 4)(), C.c_int32(0)
+    assert lib.spaco_select_bernoulli(0, 0, 4, 0.0, out, C.byref(cnt)) == -8
+    assert lib.spaco_select_bernoulli(0, 0, 4, 1.5, out, C.byref(cnt)) == -8
+    assert lib.spaco_select_bernoulli(0, 0, 4, float("nan"), out, C.byref(cnt)) == -8
+    assert lib.spaco_select_bernoulli(0, 0, 4, 0.5, None, C.byref(cnt)) == -1
+
+
+def test_compensation_factor_with_cap():
+    """The library's factor against the values the paper states (tests/golden/compensation_factor.txt: k t cap factor)."""
+    golden = os.path.join(ROOT, "tests", "golden", "compensation_factor.txt")
+    rows = 0
+    for line in open(golden):
+        f = line.split("#")[0].split()
+        if len(f) == 4:
+            k, t, cap, lam = int(f[0]), int(f[1]), (0.0 if f[2] == "-" else float(f[2])), float(f[3])
+            assert seco.spaco_compensation_factor(k, t, cap=cap) == np.float32(lam)
+            assert S.compensation_factor(k, t, cap=None if cap == 0.0 else cap) == lam
+            rows += 1
+    assert rows >= 8
+    assert abs(seco.spaco_compensation_factor(7, 3) - 7 / 3) < 1e-6
+    with pytest.raises(seco.SecoError):
+        seco.spaco_compensation_factor(4, 5)

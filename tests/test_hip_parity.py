@@ -415,3 +415,30 @@ def test_step_captured_in_a_hip_graph_replays_identically():
         for t, e in zip(outs, eager):
             assert torch.equal(t, e), rep
         (q.float() @ q.float().transpose(-1, -2)).sum().item()      # unrelated eager work between replays
+
+
+def test_more_weight_runs_than_one_segment_table_holds():
+    """110 chunks of 32 rows with every second weight zero and the others all different: 55 runs of columns, more
+    than the 48 a single launch of the dK/dV kernel takes by value, so the call is issued as two launches."""
+    B, Hq, Hkv, C, k = 1, 2, 1, 32, 110
+    N, j = k * C, k - 1
+    x = small_layer(60, B, Hq, Hkv, N, 128, "bf16")
+    s = 1 / np.sqrt(128)
+    w = np.array([0.0 if i % 2 else 1.0 + 0.05 * i for i in range(k)], dtype=np.float32)
+    w[j] = 1.0
+    q, kc, vc, do = (to_dev(x[n], "bf16") for n in ("q", "k", "v", "do"))
+    sl = slice(j * C, N)
+    o, lse = seco.seco_chunk_attn_fwd(q[:, :, sl], kc, vc, j * C, s)
+    gk = torch.zeros(B, Hkv, N, 128, dtype=torch.float32, device=DEV)
+    gv = torch.zeros_like(gk)
+    dq = seco.spaco_chunk_attn_bwd(q[:, :, sl], kc, vc, o, lse, do[:, :, sl].contiguous(), gk, gv, j * C, s,
+                                   w.tolist(), C)
+    torch.cuda.synchronize()
+    ro, rl = A.chunk_attn_fwd(x["q"][:, :, sl], x["k"], x["v"], j * C, s)
+    rdq, rdk, rdv = A.chunk_attn_bwd(x["q"][:, :, sl], x["k"], x["v"], ro, rl, x["do"][:, :, sl], j * C, s)
+    wrow = np.repeat(w.astype(np.float64), C)[None, None, :, None]
+    assert max_rel(to_host(dq), rdq) <= 2e-2
+    assert max_rel(to_host(gk), wrow * rdk) <= 2e-2
+    assert max_rel(to_host(gv), wrow * rdv) <= 2e-2
+    zero_rows = np.repeat(w == 0.0, C)
+    assert not to_host(gk)[:, :, zero_rows].any() and not to_host(gv)[:, :, zero_rows].any()
