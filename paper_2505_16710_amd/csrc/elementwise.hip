@@ -72,38 +72,54 @@ __global__ __launch_bounds__(256) void delta_kernel(AttnParams p) {
   if (lane == 0) p.delta[row] = acc;
 }
 
-// Merge of the split forward: thread (row, d4) combines the n_splits partial rows in split order,
-//   M = max m_s,  L = sum l_s 2^(m_s - M),  O = sum o_s 2^(m_s - M) / L,  LSE = (M + log2 L) ln 2;
-// a partial with m_s = -inf is empty (nothing was written for its O) and is skipped.
+// Merge of the split forward: the 32 threads of a row (thread = 4 consecutive head_dim elements) combine the
+// n_splits (<= 64) partial rows in split order,
+//   M = max m_s,  L = sum l_s 2^(m_s - M),  O = sum o_s 2^(m_s - M) / L,  LSE = (M + log2 L) ln 2.
+// Lane i of the row's group loads (m, l) of splits i and i + 32 once; max, sum and the per-split weights then
+// travel by cross-lane shuffles.  A partial with m_s = -inf is empty (nothing was written for its O): weight 0,
+// its O is not read.
 __global__ __launch_bounds__(256) void fwd_merge_kernel(AttnParams p) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t R = (int64_t)p.B * p.Hq * p.C;
-  const int64_t rowid = i >> 5;
-  if (rowid >= R) return;
-  const int d4 = (int)(i & 31);
-  float M = -INFINITY;
-  for (int sp = 0; sp < p.n_splits; ++sp) M = fmaxf(M, p.part_ml[2 * (sp * R + rowid)]);
-  float L = 0.f;
+  const int64_t rowid = min(i >> 5, R - 1);      // surplus threads of the last block repeat the last row, no store
+  const bool live = (i >> 5) < R;
+  const int l32 = (int)(i & 31);
+  float m0 = -INFINITY, m1 = -INFINITY, s0 = 0.f, s1 = 0.f;
+  if (l32 < p.n_splits) {
+    m0 = p.part_ml[2 * (l32 * R + rowid)];
+    s0 = p.part_ml[2 * (l32 * R + rowid) + 1];
+  }
+  if (l32 + 32 < p.n_splits) {
+    m1 = p.part_ml[2 * ((l32 + 32) * R + rowid)];
+    s1 = p.part_ml[2 * ((l32 + 32) * R + rowid) + 1];
+  }
+  float M = fmaxf(m0, m1);
+#pragma unroll
+  for (int sh = 16; sh > 0; sh >>= 1) M = fmaxf(M, __shfl_xor(M, sh, 32));
+  const float w0 = m0 == -INFINITY ? 0.f : exp2f(m0 - M);
+  const float w1 = m1 == -INFINITY ? 0.f : exp2f(m1 - M);
+  float L = w0 * s0 + w1 * s1;
+#pragma unroll
+  for (int sh = 16; sh > 0; sh >>= 1) L += __shfl_xor(L, sh, 32);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int sp = 0; sp < p.n_splits; ++sp) {
-    const float m = p.part_ml[2 * (sp * R + rowid)];
-    if (m == -INFINITY) continue;
-    const float w = exp2f(m - M);
-    L += w * p.part_ml[2 * (sp * R + rowid) + 1];
-    const float4 x = *reinterpret_cast<const float4*>(p.part + (sp * R + rowid) * 128 + 4 * d4);
+    const float w = __shfl(sp < 32 ? w0 : w1, sp & 31, 32);
+    if (w == 0.f) continue;
+    const float4 x = *reinterpret_cast<const float4*>(p.part + (sp * R + rowid) * 128 + 4 * l32);
     acc.x += w * x.x;
     acc.y += w * x.y;
     acc.z += w * x.z;
     acc.w += w * x.w;
   }
+  if (!live) return;
   const float inv = 1.f / L;
   const int row = (int)(rowid % p.C);
   const int h = (int)((rowid / p.C) % p.Hq);
   const int b = (int)(rowid / ((int64_t)p.C * p.Hq));
   typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
   const bf16x4 v = {(__bf16)(acc.x * inv), (__bf16)(acc.y * inv), (__bf16)(acc.z * inv), (__bf16)(acc.w * inv)};
-  *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.o_out) + b * p.os[0] + h * p.os[1] + (int64_t)row * p.os[2] + 4 * d4) = v;
-  if (d4 == 0) p.lse[rowid] = (M + log2f(L)) * 0.6931471805599453f;
+  *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.o_out) + b * p.os[0] + h * p.os[1] + (int64_t)row * p.os[2] + 4 * l32) = v;
+  if (l32 == 0) p.lse[rowid] = (M + log2f(L)) * 0.6931471805599453f;
 }
 
 // Merge of the split dQ: dQ = scale * (sum of the partials in split order), rounded to bf16.
