@@ -148,6 +148,25 @@ int kvgrad_accumulate(const seco_desc* desc, float* dst_k, float* dst_v, const f
                       float scale, int64_t row_begin, int64_t row_end, void* hip_stream);
 
 /*
+ * Cache append (appendix listing, update_kv_cache): writes the chunk's keys and values into rows
+ * [q_start, q_start + chunk_len) of the preallocated caches, after which rows [0, q_start + chunk_len) are what
+ * the listing obtains by concatenation.  Uses batch, n_kv_heads, head_dim, dtype, chunk_len, q_start;
+ * k_new, v_new: [B, Hkv, C, D] with q_stride; k_cache, v_cache: kv_stride.  Either pair may be NULL (skipped).
+ */
+int kv_append(const seco_desc* desc, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+              void* hip_stream);
+
+/*
+ * Gradient hand-over to a recomputed chunk (appendix listing, copy_grad / grad_hook's "base * scaler"):
+ *   d_k_new[b, h, r, :] = (dtype)(scaler * gk[b, h, q_start + r, :]),   d_v_new likewise from gv,
+ * product in fp32, rounded to nearest-even for bf16.  gk, gv: fp32 with g_stride; d_k_new, d_v_new: [B, Hkv, C, D]
+ * with q_stride, overwritten.  Either pair may be NULL (skipped).  With the in-kernel weights of
+ * spaco_chunk_attn_bwd the rows already carry the factor and scaler is 1.
+ */
+int kvgrad_readout(const seco_desc* desc, const float* gk, const float* gv, void* d_k_new, void* d_v_new,
+                   float scaler, void* hip_stream);
+
+/*
  * SpaCO chunk selection (Alg. 2: "randomly select t distinct indices"), host only.
  * Deterministic in (seed, step): SplitMix64 stream keyed by (seed, step), unbiased bounded
  * draws by rejection, first t steps of a Fisher-Yates shuffle of 0..k-1, result sorted in

@@ -7,7 +7,9 @@ PyTorch fallback: if the library has not been built, importing the binding raise
 """
 from .binding import (  # noqa: F401
     SecoError,
+    kv_append,
     kvgrad_accumulate,
+    kvgrad_readout,
     kvgrad_zero,
     library_path,
     load_library,

@@ -54,6 +54,9 @@ def load_library():
                                          C.POINTER(C.c_float), i32, i32, vp, sz, vp]
     lib.kvgrad_zero.argtypes = [dp, fp, fp, i64, i64, vp]
     lib.kvgrad_accumulate.argtypes = [dp, fp, fp, fp, fp, C.c_float, i64, i64, vp]
+    lib.kv_append.argtypes = [dp, vp, vp, vp, vp, vp]
+    lib.kvgrad_readout.argtypes = [dp, fp, fp, vp, vp, C.c_float, vp]
+    lib.kv_append.restype = lib.kvgrad_readout.restype = C.c_int
     lib.spaco_select_chunks.argtypes = [C.c_uint64, C.c_uint64, i32, i32, C.POINTER(i32)]
     lib.spaco_chunk_weights.argtypes = [C.POINTER(i32), i32, i32, C.c_float, C.POINTER(C.c_float)]
     lib.spaco_select_bernoulli.argtypes = [C.c_uint64, C.c_uint64, i32, C.c_double, C.POINTER(i32), C.POINTER(i32)]
@@ -225,6 +228,41 @@ def kvgrad_accumulate(dst_k, dst_v, src_k, src_v, scale, row_begin=0, row_end=No
     _check(load_library().kvgrad_accumulate(C.byref(d), _ptr(dst_k), _ptr(dst_v), _ptr(src_k), _ptr(src_v),
                                             float(scale), int(row_begin), int(row_end), _stream(stream)),
            "kvgrad_accumulate")
+
+
+def _rows_desc(new, cache_or_g, row_begin, is_g):
+    d = SecoDesc()
+    d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = new.shape[0], new.shape[1], new.shape[1], new.shape[3]
+    d.chunk_len, d.q_start, d.dtype, d.softmax_scale = new.shape[2], int(row_begin), _dtype_code(new), 1.0
+    d.q_stride = d.o_stride = _strides3(new)
+    d.kv_stride = _strides3(new) if is_g else _strides3(cache_or_g)
+    d.g_stride = _strides3(cache_or_g) if is_g else _strides3(new)
+    return d
+
+
+def kv_append(k_new, v_new, k_cache, v_cache, row_begin, stream=None):
+    """Write the chunk's keys / values ([B, Hkv, C, D]) into cache rows [row_begin, row_begin + C)."""
+    d = _rows_desc(k_new, k_cache, row_begin, False)
+    if v_new.stride() != k_new.stride() or v_cache.stride() != k_cache.stride():
+        raise ValueError("k/v must share strides")
+    _check(load_library().kv_append(C.byref(d), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _stream(stream)),
+           "kv_append")
+
+
+def kvgrad_readout(gk, gv, row_begin, n_rows, dtype, scaler=1.0, d_k=None, d_v=None, stream=None):
+    """(d_k, d_v) = scaler * (gk, gv)[rows row_begin .. row_begin + n_rows) in the storage dtype."""
+    import torch
+    B, H, _, D = gk.shape
+    if d_k is None:
+        d_k = torch.empty(B, H, n_rows, D, dtype=dtype, device=gk.device)
+    if d_v is None:
+        d_v = torch.empty_strided(d_k.size(), d_k.stride(), dtype=dtype, device=gk.device)
+    if gv.stride() != gk.stride() or d_v.stride() != d_k.stride():
+        raise ValueError("gk/gv and d_k/d_v must share strides")
+    d = _rows_desc(d_k, gk, row_begin, True)
+    _check(load_library().kvgrad_readout(C.byref(d), _ptr(gk), _ptr(gv), _ptr(d_k), _ptr(d_v), float(scaler),
+                                         _stream(stream)), "kvgrad_readout")
+    return d_k, d_v
 
 
 def spaco_select_chunks(seed, step, k, t):

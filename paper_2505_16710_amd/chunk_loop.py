@@ -6,7 +6,7 @@ forward of a chunk is `seco_chunk_attn_fwd` against the cache, its backward is `
 `spaco_chunk_attn_bwd`, which deposits the chunk's dK/dV on every visible cache row, and the gradient
 handed to the chunk's own recomputed K/V is simply the chunk's rows of those buffers (they hold what
 the later chunks deposited plus the chunk's own diagonal block: the relay of Alg. 1, `m_i.grad <-
-m'_i.grad`, with no copy).  Under SpaCO the deposits on earlier selected chunks carry the compensation
+m'_i.grad`), read out by `kvgrad_readout`; new keys / values enter the cache through `kv_append`.  Under SpaCO the deposits on earlier selected chunks carry the compensation
 factor, so a chain through p caches is scaled by factor^p (Sec. 5).
 
 The projections, norms, MLP and loss around the attention are ordinary PyTorch GPU ops with autograd
@@ -40,9 +40,7 @@ class ChunkAttention(torch.autograd.Function):
 
     @staticmethod
     def forward(ctx, q, k_new, v_new, state, q_start, scale, weights, weight_chunk_len):
-        C = q.shape[2]
-        state.k[:, :, q_start:q_start + C].copy_(k_new)
-        state.v[:, :, q_start:q_start + C].copy_(v_new)
+        _b.kv_append(k_new, v_new, state.k, state.v, q_start)
         o, lse = _b.seco_chunk_attn_fwd(q, state.k, state.v, q_start, scale,
                                         o=torch.empty(q.shape, dtype=q.dtype, device=q.device))
         ctx.save_for_backward(q, o, lse)
@@ -59,8 +57,7 @@ class ChunkAttention(torch.autograd.Function):
         else:
             d_q = _b.spaco_chunk_attn_bwd(q, st.k, st.v, o, lse, d_o, st.gk, st.gv, s0, ctx.scale,
                                           ctx.weights, ctx.wlen)
-        d_k = st.gk[:, :, s0:s0 + C].to(q.dtype, copy=True)
-        d_v = st.gv[:, :, s0:s0 + C].to(q.dtype, copy=True)
+        d_k, d_v = _b.kvgrad_readout(st.gk, st.gv, s0, C, q.dtype)
         return d_q, d_k, d_v, None, None, None, None, None
 
 

@@ -145,6 +145,49 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(AttnParams p) {
   *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.d_q) + b * p.qs[0] + h * p.qs[1] + (int64_t)row * p.qs[2] + 4 * d4) = v;
 }
 
+// Row-range copy into the cache: work item = 16 bytes; consecutive threads walk along a row.
+__global__ __launch_bounds__(256) void rows_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, int H, int C,
+                                                        int v16, int64_t ds0, int64_t ds1, int64_t ds2, int64_t ss0,
+                                                        int64_t ss1, int64_t ss2, int64_t r0, int64_t total) {
+  // strides arrive in units of 16 bytes
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t dd = i % v16;
+    int64_t t = i / v16;
+    const int64_t row = t % C;
+    t /= C;
+    const int64_t h = t % H, b = t / H;
+    dst[b * ds0 + h * ds1 + (r0 + row) * ds2 + dd] = src[b * ss0 + h * ss1 + row * ss2 + dd];
+  }
+}
+
+// Read-out of KV-gradient rows: work item = 8 consecutive floats of a row (32 bytes in, 16 or 32 bytes out).
+template <bool kBf16>
+__global__ __launch_bounds__(256) void readout_kernel(void* __restrict__ out, const float* __restrict__ g, float scaler, int H,
+                                                      int C, int d8, int64_t os0, int64_t os1, int64_t os2, int64_t gs0,
+                                                      int64_t gs1, int64_t gs2, int64_t r0, int64_t total) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t dd = i % d8;
+    int64_t t = i / d8;
+    const int64_t row = t % C;
+    t /= C;
+    const int64_t h = t % H, b = t / H;
+    const float4* src = reinterpret_cast<const float4*>(g + b * gs0 + h * gs1 + (r0 + row) * gs2 + dd * 8);
+    float4 a = src[0], c = src[1];
+    a.x *= scaler; a.y *= scaler; a.z *= scaler; a.w *= scaler;
+    c.x *= scaler; c.y *= scaler; c.z *= scaler; c.w *= scaler;
+    const int64_t off = b * os0 + h * os1 + row * os2 + dd * 8;
+    if (kBf16) {
+      typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+      const bf16x8 v = {(__bf16)a.x, (__bf16)a.y, (__bf16)a.z, (__bf16)a.w, (__bf16)c.x, (__bf16)c.y, (__bf16)c.z, (__bf16)c.w};
+      *reinterpret_cast<bf16x8*>(static_cast<__bf16*>(out) + off) = v;
+    } else {
+      float4* d = reinterpret_cast<float4*>(static_cast<float*>(out) + off);
+      d[0] = a;
+      d[1] = c;
+    }
+  }
+}
+
 int grid_for(int64_t total) {
   const int64_t blocks = (total + 255) / 256;
   return (int)(blocks < 65536 ? blocks : 65536);  // grid-stride loop covers the rest
@@ -171,6 +214,37 @@ int launch_kvgrad_axpy(float* dst, const float* src, float scale, int B, int H, 
     ProfScope prof(kKernelKvgrad, s);
     hipLaunchKernelGGL(kvgrad_kernel<true>, dim3(grid_for(total)), dim3(256), 0, s, dst, src, scale, H, D / 4, gs[0],
                      gs[1], gs[2], r0, r1 - r0, total);
+  }
+  return launch_status();
+}
+
+int launch_rows_copy(void* dst, const void* src, int eb, int B, int H, int C, int D, const int64_t dst_s[3],
+                     const int64_t src_s[3], int64_t r0, hipStream_t s) {
+  const int per16 = 16 / eb;                  // elements per 16-byte word; strides and D are multiples of it
+  const int v16 = D / per16;
+  const int64_t total = (int64_t)B * H * C * v16;
+  if (total == 0) return SECO_OK;
+  {
+    ProfScope prof(kKernelKvgrad, s);
+    hipLaunchKernelGGL(rows_copy_kernel, dim3(grid_for(total)), dim3(256), 0, s, static_cast<uint4*>(dst),
+                       static_cast<const uint4*>(src), H, C, v16, dst_s[0] / per16, dst_s[1] / per16, dst_s[2] / per16,
+                       src_s[0] / per16, src_s[1] / per16, src_s[2] / per16, r0, total);
+  }
+  return launch_status();
+}
+
+int launch_readout(void* out, const float* g, float scaler, bool bf16, int B, int H, int C, int D,
+                   const int64_t out_s[3], const int64_t gs[3], int64_t r0, hipStream_t s) {
+  const int64_t total = (int64_t)B * H * C * (D / 8);
+  if (total == 0) return SECO_OK;
+  {
+    ProfScope prof(kKernelKvgrad, s);
+    if (bf16)
+      hipLaunchKernelGGL(readout_kernel<true>, dim3(grid_for(total)), dim3(256), 0, s, out, g, scaler, H, C, D / 8,
+                         out_s[0], out_s[1], out_s[2], gs[0], gs[1], gs[2], r0, total);
+    else
+      hipLaunchKernelGGL(readout_kernel<false>, dim3(grid_for(total)), dim3(256), 0, s, out, g, scaler, H, C, D / 8,
+                         out_s[0], out_s[1], out_s[2], gs[0], gs[1], gs[2], r0, total);
   }
   return launch_status();
 }

@@ -304,3 +304,57 @@ extern "C" int kvgrad_accumulate(const seco_desc* desc, float* dst_k, float* dst
     return rc;
   return SECO_OK;
 }
+
+// ---- cache append and gradient hand-over (appendix listing) ---------------------------------------------------------
+namespace {
+int check_append_like(const seco_desc* d, bool with_g) {
+  int rc = check_desc(d);
+  if (rc) return rc;
+  const int eb = d->dtype == SECO_BF16 ? 2 : 4;
+  if ((rc = check_strides(d->q_stride, eb, d->head_dim))) return rc;
+  if (with_g) {
+    if ((rc = check_strides(d->g_stride, 4, d->head_dim))) return rc;
+    if (d->head_dim % 8 != 0) return SECO_ERR_HEAD_DIM;
+  } else if ((rc = check_strides(d->kv_stride, eb, d->head_dim))) {
+    return rc;
+  }
+  return SECO_OK;
+}
+}  // namespace
+
+extern "C" int kv_append(const seco_desc* desc, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                         void* hip_stream) {
+  int rc = check_append_like(desc, false);
+  if (rc) return rc;
+  if ((k_new == nullptr) != (k_cache == nullptr) || (v_new == nullptr) != (v_cache == nullptr)) return SECO_ERR_NULL;
+  for (const void* ptr : {k_new, v_new, (const void*)k_cache, (const void*)v_cache})
+    if (ptr && !aligned16(ptr)) return SECO_ERR_ALIGN;
+  const int eb = desc->dtype == SECO_BF16 ? 2 : 4;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (k_new && (rc = launch_rows_copy(k_cache, k_new, eb, desc->batch, desc->n_kv_heads, desc->chunk_len, desc->head_dim,
+                                      desc->kv_stride, desc->q_stride, desc->q_start, s)))
+    return rc;
+  if (v_new && (rc = launch_rows_copy(v_cache, v_new, eb, desc->batch, desc->n_kv_heads, desc->chunk_len, desc->head_dim,
+                                      desc->kv_stride, desc->q_stride, desc->q_start, s)))
+    return rc;
+  return SECO_OK;
+}
+
+extern "C" int kvgrad_readout(const seco_desc* desc, const float* gk, const float* gv, void* d_k_new, void* d_v_new,
+                              float scaler, void* hip_stream) {
+  int rc = check_append_like(desc, true);
+  if (rc) return rc;
+  if ((gk == nullptr) != (d_k_new == nullptr) || (gv == nullptr) != (d_v_new == nullptr)) return SECO_ERR_NULL;
+  if (!std::isfinite(scaler)) return SECO_ERR_RANGE;
+  for (const void* ptr : {(const void*)gk, (const void*)gv, (const void*)d_k_new, (const void*)d_v_new})
+    if (ptr && !aligned16(ptr)) return SECO_ERR_ALIGN;
+  const bool bf16 = desc->dtype == SECO_BF16;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (gk && (rc = launch_readout(d_k_new, gk, scaler, bf16, desc->batch, desc->n_kv_heads, desc->chunk_len, desc->head_dim,
+                                 desc->q_stride, desc->g_stride, desc->q_start, s)))
+    return rc;
+  if (gv && (rc = launch_readout(d_v_new, gv, scaler, bf16, desc->batch, desc->n_kv_heads, desc->chunk_len, desc->head_dim,
+                                 desc->q_stride, desc->g_stride, desc->q_start, s)))
+    return rc;
+  return SECO_OK;
+}

@@ -87,6 +87,13 @@ int launch_kvgrad_zero(float* g, int B, int H, int D, const int64_t gs[3], int64
 int launch_kvgrad_axpy(float* dst, const float* src, float scale, int B, int H, int D, const int64_t gs[3],
                        int64_t r0, int64_t r1, hipStream_t s);
 
+// rows [r0, r0 + C) of a [B, H, *, D] array <- a [B, H, C, D] array (same element type, eb bytes per element)
+int launch_rows_copy(void* dst, const void* src, int eb, int B, int H, int C, int D, const int64_t dst_s[3],
+                     const int64_t src_s[3], int64_t r0, hipStream_t s);
+// out[B, H, C, D] (bf16 or fp32) = scaler * g[rows r0 .. r0 + C) (fp32)
+int launch_readout(void* out, const float* g, float scaler, bool bf16, int B, int H, int C, int D,
+                   const int64_t out_s[3], const int64_t gs[3], int64_t r0, hipStream_t s);
+
 // Optional per-kernel timing (seco_profile_enable): a scope brackets one launch with HIP events
 // on the launch stream.  Disabled by default; then a scope costs one branch.
 enum KernelKind { kKernelFwd = 0, kKernelDelta, kKernelDq, kKernelDkdv, kKernelKvgrad, kKernelMerge, kKernelKinds };

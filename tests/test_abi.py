@@ -177,3 +177,15 @@ def test_compensation_factor_with_cap():
     assert abs(seco.spaco_compensation_factor(7, 3) - 7 / 3) < 1e-6
     with pytest.raises(seco.SecoError):
         seco.spaco_compensation_factor(4, 5)
+
+
+def test_append_and_readout_validation():
+    lib = seco.load_library()
+    d = desc()
+    assert lib.kv_append(C.byref(d), FAKE, FAKE, None, FAKE, None) == -1
+    assert lib.kv_append(C.byref(d), C.c_void_p(0x1008), FAKE, FAKE, FAKE, None) == -5
+    assert lib.kv_append(C.byref(desc(head_dim=96)), FAKE, FAKE, FAKE, FAKE, None) == -3
+    assert lib.kvgrad_readout(C.byref(d), FAKE, None, None, None, 1.0, None) == -1
+    assert lib.kvgrad_readout(C.byref(d), FAKE, FAKE, FAKE, FAKE, float("inf"), None) == -8
+    assert lib.kvgrad_readout(C.byref(desc(dtype=B.SECO_F32, head_dim=12)), FAKE, FAKE, FAKE, FAKE, 1.0, None) == -3
+    assert lib.kvgrad_readout(C.byref(d), None, None, None, None, 1.0, None) == 0           # nothing to do

@@ -442,3 +442,35 @@ def test_more_weight_runs_than_one_segment_table_holds():
     assert max_rel(to_host(gv), wrow * rdv) <= 2e-2
     zero_rows = np.repeat(w == 0.0, C)
     assert not to_host(gk)[:, :, zero_rows].any() and not to_host(gv)[:, :, zero_rows].any()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_append_and_readout_bit_exact(dtype):
+    """kv_append / kvgrad_readout (appendix listing) against oracle/relay.py, strided chunk tensors, bit for bit."""
+    from oracle import relay as R
+    B, H, N, D, C, r0 = 2, 3, 160, 128 if dtype == "bf16" else 40, 48, 64
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    rng = np.random.default_rng(70)
+    from workloads import round_to
+    k_new = round_to(rng.standard_normal((B, H, C, D)).astype(np.float32), dtype)
+    v_new = round_to(rng.standard_normal((B, H, C, D)).astype(np.float32), dtype)
+    kc = round_to(rng.standard_normal((B, H, N, D)).astype(np.float32), dtype)
+    vc = round_to(rng.standard_normal((B, H, N, D)).astype(np.float32), dtype)
+    # chunk tensors as a projection would produce them: [B, C, H, D] storage viewed as [B, H, C, D]
+    kn_dev = to_dev(k_new.transpose(0, 2, 1, 3).copy(), dtype).transpose(1, 2)
+    vn_dev = to_dev(v_new.transpose(0, 2, 1, 3).copy(), dtype).transpose(1, 2)
+    kc_dev, vc_dev = to_dev(kc, dtype), to_dev(vc, dtype)
+    seco.kv_append(kn_dev, vn_dev, kc_dev, vc_dev, r0)
+    rk, rv = R.kv_append(kc, vc, k_new, v_new, r0)
+    np.testing.assert_array_equal(to_host(kc_dev), rk.astype(np.float64))
+    np.testing.assert_array_equal(to_host(vc_dev), rv.astype(np.float64))
+
+    gk = (rng.standard_normal((B, H, N, D)) * 3).astype(np.float32)
+    gv = (rng.standard_normal((B, H, N, D)) * 3).astype(np.float32)
+    gk_dev, gv_dev = torch.from_numpy(gk).to(DEV), torch.from_numpy(gv).to(DEV)
+    for scaler in (1.0, 16 / 3):
+        d_k = torch.empty(B, C, H, D, dtype=tdt, device=DEV).transpose(1, 2)      # strided output
+        d_k, d_v = seco.kvgrad_readout(gk_dev, gv_dev, r0, C, tdt, scaler=scaler, d_k=d_k)
+        np.testing.assert_array_equal(to_host(d_k), R.kvgrad_readout(gk, r0, r0 + C, scaler, dtype).astype(np.float64))
+        np.testing.assert_array_equal(to_host(d_v), R.kvgrad_readout(gv, r0, r0 + C, scaler, dtype).astype(np.float64))
+    assert torch.equal(gk_dev.cpu(), torch.from_numpy(gk))            # the buffers themselves are only read
