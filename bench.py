@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--calls", default="",
                     help="comma-separated chunk indices: instead of whole steps, time the forward + backward call pair "
                          "of just these chunks (per-kernel event times; used for counter collection)")
+    ap.add_argument("--hbm-kernels", action="store_true",
+                    help="also time the HBM-bound helpers (kvgrad_zero / accumulate, kv_append, kvgrad_readout) and "
+                         "report their GB/s against the 8 TB/s HBM peak")
     ap.add_argument("--schedules", action="store_true",
                     help="also time a whole layer of --config under Alg. 1 and Alg. 2 (needs a config with spaco_t)")
     ap.add_argument("--graph", action="store_true",
@@ -305,6 +308,44 @@ def main():
                                "sample": f"fp64 NumPy oracle, fwd+bwd of the last {done} chunk calls of one (batch, KV head) "
                                          f"unit of {cfg.name} ({Hq // Hkv} query heads), {el:.1f} s",
                                "host_cores_available": len(os.sched_getaffinity(0))}
+
+    if args.hbm_kernels:
+        # the HBM-bound helpers on this configuration's buffers: bytes moved / time against the 8 TB/s of HBM3E
+        Lh = Layer(N, C)
+        j = k_chunks - 1
+        knew = torch.randn(B, C, Hkv, D, device=dev).to(tdt).transpose(1, 2)
+        dk = torch.empty(B, C, Hkv, D, device=dev, dtype=tdt).transpose(1, 2)
+        dv = torch.empty_strided(dk.size(), dk.stride(), device=dev, dtype=tdt)
+        g2 = torch.zeros_like(Lh.gk)
+        eb = 2 if cfg.dtype == "bf16" else 4
+        gbytes = Lh.gk.numel() * 4
+        cases = {
+            "kvgrad_zero": (lambda: seco.kvgrad_zero(Lh.gk, Lh.gv), 2 * gbytes),
+            "kvgrad_accumulate": (lambda: seco.kvgrad_accumulate(Lh.gk, Lh.gv, g2, g2, 2.0), 2 * 3 * gbytes),
+            "kv_append": (lambda: seco.kv_append(knew, knew, Lh.kc, Lh.vc, j * C), 2 * 2 * knew.numel() * eb),
+            "kvgrad_readout": (lambda: seco.kvgrad_readout(Lh.gk, Lh.gv, j * C, C, tdt, d_k=dk, d_v=dv),
+                               2 * knew.numel() * (4 + eb)),
+        }
+        n_rows = (1 << 30) // (Hkv * D * 4)
+        big_dst = torch.zeros(1, Hkv, n_rows, D, device=dev, dtype=torch.float32)
+        big_src = torch.ones_like(big_dst)
+        cases["kvgrad_accumulate_1GiB"] = (lambda: seco.kvgrad_accumulate(big_dst, None, big_src, None, 0.5), 3 << 30)
+        res = {"note": "only the 1 GiB case exceeds the 256 MB memory-side cache, i.e. streams from HBM; the others run "
+                       "on this configuration's buffers and are partly cache-resident or launch-bound"}
+        for name, (fn, nbytes) in cases.items():
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 20
+            res[name] = {"bytes": nbytes, "avg_us": round(us, 2), "GB_per_s": round(nbytes / us / 1e3, 1),
+                         "frac_of_8TBps": round(nbytes / us / 1e3 / 8000.0, 3)}
+        out["hbm_kernels"] = res
+        del Lh
 
     if args.calibrate_copy:
         n_rows = (1 << 30) // (Hkv * D * 4)
