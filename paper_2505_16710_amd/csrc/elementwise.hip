@@ -8,10 +8,14 @@ namespace {
 
 // Rows [r0, r1) of a [B, H, N, D] fp32 buffer, one float4 per thread-iteration.
 // Work item index -> (b, h, row, d4); consecutive threads touch consecutive 16-byte words of a row.
+// blockIdx.y selects the tensor (gK or gV): both are handled by one launch.
 template <bool kAxpy>
-__global__ __launch_bounds__(256) void kvgrad_kernel(float* __restrict__ dst, const float* __restrict__ src, float scale,
-                                                     int H, int d4, int64_t gs0, int64_t gs1, int64_t gs2, int64_t r0,
-                                                     int64_t nrows, int64_t total) {
+__global__ __launch_bounds__(256) void kvgrad_kernel(float* __restrict__ dst_a, float* __restrict__ dst_b,
+                                                     const float* __restrict__ src_a, const float* __restrict__ src_b,
+                                                     float scale, int H, int d4, int64_t gs0, int64_t gs1, int64_t gs2,
+                                                     int64_t r0, int64_t nrows, int64_t total) {
+  float* __restrict__ dst = blockIdx.y ? dst_b : dst_a;
+  const float* __restrict__ src = blockIdx.y ? src_b : src_a;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
     const int64_t dd = i % d4;
     int64_t t = i / d4;
@@ -146,10 +150,13 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(AttnParams p) {
 }
 
 // Row-range copy into the cache: work item = 16 bytes; consecutive threads walk along a row.
-__global__ __launch_bounds__(256) void rows_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, int H, int C,
-                                                        int v16, int64_t ds0, int64_t ds1, int64_t ds2, int64_t ss0,
-                                                        int64_t ss1, int64_t ss2, int64_t r0, int64_t total) {
-  // strides arrive in units of 16 bytes
+__global__ __launch_bounds__(256) void rows_copy_kernel(uint4* __restrict__ dst_a, uint4* __restrict__ dst_b,
+                                                        const uint4* __restrict__ src_a, const uint4* __restrict__ src_b,
+                                                        int H, int C, int v16, int64_t ds0, int64_t ds1, int64_t ds2,
+                                                        int64_t ss0, int64_t ss1, int64_t ss2, int64_t r0, int64_t total) {
+  // strides arrive in units of 16 bytes; blockIdx.y selects the tensor (keys or values)
+  uint4* __restrict__ dst = blockIdx.y ? dst_b : dst_a;
+  const uint4* __restrict__ src = blockIdx.y ? src_b : src_a;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
     const int64_t dd = i % v16;
     int64_t t = i / v16;
@@ -162,9 +169,13 @@ __global__ __launch_bounds__(256) void rows_copy_kernel(uint4* __restrict__ dst,
 
 // Read-out of KV-gradient rows: work item = 8 consecutive floats of a row (32 bytes in, 16 or 32 bytes out).
 template <bool kBf16>
-__global__ __launch_bounds__(256) void readout_kernel(void* __restrict__ out, const float* __restrict__ g, float scaler, int H,
-                                                      int C, int d8, int64_t os0, int64_t os1, int64_t os2, int64_t gs0,
-                                                      int64_t gs1, int64_t gs2, int64_t r0, int64_t total) {
+__global__ __launch_bounds__(256) void readout_kernel(void* __restrict__ out_a, void* __restrict__ out_b,
+                                                      const float* __restrict__ g_a, const float* __restrict__ g_b,
+                                                      float scaler, int H, int C, int d8, int64_t os0, int64_t os1,
+                                                      int64_t os2, int64_t gs0, int64_t gs1, int64_t gs2, int64_t r0,
+                                                      int64_t total) {
+  void* __restrict__ out = blockIdx.y ? out_b : out_a;
+  const float* __restrict__ g = blockIdx.y ? g_b : g_a;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
     const int64_t dd = i % d8;
     int64_t t = i / d8;
@@ -195,56 +206,64 @@ int grid_for(int64_t total) {
 
 }  // namespace
 
-int launch_kvgrad_zero(float* g, int B, int H, int D, const int64_t gs[3], int64_t r0, int64_t r1, hipStream_t s) {
+// The launchers take a pair of tensors (gK and gV, keys and values); a NULL member is skipped.
+int launch_kvgrad_zero(float* ga, float* gb, int B, int H, int D, const int64_t gs[3], int64_t r0, int64_t r1,
+                       hipStream_t s) {
   const int64_t total = (int64_t)B * H * (r1 - r0) * (D / 4);
-  if (total == 0) return SECO_OK;
+  if (!ga) { ga = gb; gb = nullptr; }
+  if (total == 0 || !ga) return SECO_OK;
   {
     ProfScope prof(kKernelKvgrad, s);
-    hipLaunchKernelGGL(kvgrad_kernel<false>, dim3(grid_for(total)), dim3(256), 0, s, g, nullptr, 0.f, H, D / 4, gs[0],
-                     gs[1], gs[2], r0, r1 - r0, total);
+    hipLaunchKernelGGL(kvgrad_kernel<false>, dim3(grid_for(total), gb ? 2 : 1), dim3(256), 0, s, ga, gb, nullptr, nullptr,
+                       0.f, H, D / 4, gs[0], gs[1], gs[2], r0, r1 - r0, total);
   }
   return launch_status();
 }
 
-int launch_kvgrad_axpy(float* dst, const float* src, float scale, int B, int H, int D, const int64_t gs[3], int64_t r0,
-                       int64_t r1, hipStream_t s) {
+int launch_kvgrad_axpy(float* da, float* db, const float* sa, const float* sb, float scale, int B, int H, int D,
+                       const int64_t gs[3], int64_t r0, int64_t r1, hipStream_t s) {
   const int64_t total = (int64_t)B * H * (r1 - r0) * (D / 4);
-  if (total == 0) return SECO_OK;
+  if (!da) { da = db; sa = sb; db = nullptr; sb = nullptr; }
+  if (total == 0 || !da) return SECO_OK;
   {
     ProfScope prof(kKernelKvgrad, s);
-    hipLaunchKernelGGL(kvgrad_kernel<true>, dim3(grid_for(total)), dim3(256), 0, s, dst, src, scale, H, D / 4, gs[0],
-                     gs[1], gs[2], r0, r1 - r0, total);
+    hipLaunchKernelGGL(kvgrad_kernel<true>, dim3(grid_for(total), db ? 2 : 1), dim3(256), 0, s, da, db, sa, sb, scale, H,
+                       D / 4, gs[0], gs[1], gs[2], r0, r1 - r0, total);
   }
   return launch_status();
 }
 
-int launch_rows_copy(void* dst, const void* src, int eb, int B, int H, int C, int D, const int64_t dst_s[3],
-                     const int64_t src_s[3], int64_t r0, hipStream_t s) {
+int launch_rows_copy(void* da, void* db, const void* sa, const void* sb, int eb, int B, int H, int C, int D,
+                     const int64_t dst_s[3], const int64_t src_s[3], int64_t r0, hipStream_t s) {
   const int per16 = 16 / eb;                  // elements per 16-byte word; strides and D are multiples of it
   const int v16 = D / per16;
   const int64_t total = (int64_t)B * H * C * v16;
-  if (total == 0) return SECO_OK;
+  if (!da) { da = db; sa = sb; db = nullptr; sb = nullptr; }
+  if (total == 0 || !da) return SECO_OK;
   {
     ProfScope prof(kKernelKvgrad, s);
-    hipLaunchKernelGGL(rows_copy_kernel, dim3(grid_for(total)), dim3(256), 0, s, static_cast<uint4*>(dst),
-                       static_cast<const uint4*>(src), H, C, v16, dst_s[0] / per16, dst_s[1] / per16, dst_s[2] / per16,
-                       src_s[0] / per16, src_s[1] / per16, src_s[2] / per16, r0, total);
+    hipLaunchKernelGGL(rows_copy_kernel, dim3(grid_for(total), db ? 2 : 1), dim3(256), 0, s, static_cast<uint4*>(da),
+                       static_cast<uint4*>(db), static_cast<const uint4*>(sa), static_cast<const uint4*>(sb), H, C, v16,
+                       dst_s[0] / per16, dst_s[1] / per16, dst_s[2] / per16, src_s[0] / per16, src_s[1] / per16,
+                       src_s[2] / per16, r0, total);
   }
   return launch_status();
 }
 
-int launch_readout(void* out, const float* g, float scaler, bool bf16, int B, int H, int C, int D,
-                   const int64_t out_s[3], const int64_t gs[3], int64_t r0, hipStream_t s) {
+int launch_readout(void* oa, void* ob, const float* ga, const float* gb, float scaler, bool bf16, int B, int H, int C,
+                   int D, const int64_t out_s[3], const int64_t gs[3], int64_t r0, hipStream_t s) {
   const int64_t total = (int64_t)B * H * C * (D / 8);
-  if (total == 0) return SECO_OK;
+  if (!oa) { oa = ob; ga = gb; ob = nullptr; gb = nullptr; }
+  if (total == 0 || !oa) return SECO_OK;
   {
     ProfScope prof(kKernelKvgrad, s);
+    const dim3 grid(grid_for(total), ob ? 2 : 1);
     if (bf16)
-      hipLaunchKernelGGL(readout_kernel<true>, dim3(grid_for(total)), dim3(256), 0, s, out, g, scaler, H, C, D / 8,
-                         out_s[0], out_s[1], out_s[2], gs[0], gs[1], gs[2], r0, total);
+      hipLaunchKernelGGL(readout_kernel<true>, grid, dim3(256), 0, s, oa, ob, ga, gb, scaler, H, C, D / 8, out_s[0],
+                         out_s[1], out_s[2], gs[0], gs[1], gs[2], r0, total);
     else
-      hipLaunchKernelGGL(readout_kernel<false>, dim3(grid_for(total)), dim3(256), 0, s, out, g, scaler, H, C, D / 8,
-                         out_s[0], out_s[1], out_s[2], gs[0], gs[1], gs[2], r0, total);
+      hipLaunchKernelGGL(readout_kernel<false>, grid, dim3(256), 0, s, oa, ob, ga, gb, scaler, H, C, D / 8, out_s[0],
+                         out_s[1], out_s[2], gs[0], gs[1], gs[2], r0, total);
   }
   return launch_status();
 }

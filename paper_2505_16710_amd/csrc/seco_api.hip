@@ -279,12 +279,7 @@ extern "C" int kvgrad_zero(const seco_desc* desc, float* gk, float* gv, int64_t 
   if (rc) return rc;
   if ((gk && !aligned16(gk)) || (gv && !aligned16(gv))) return SECO_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  for (float* g : {gk, gv}) {
-    if (!g) continue;
-    if ((rc = launch_kvgrad_zero(g, desc->batch, desc->n_kv_heads, desc->head_dim, desc->g_stride, row_begin, row_end, s)))
-      return rc;
-  }
-  return SECO_OK;
+  return launch_kvgrad_zero(gk, gv, desc->batch, desc->n_kv_heads, desc->head_dim, desc->g_stride, row_begin, row_end, s);
 }
 
 extern "C" int kvgrad_accumulate(const seco_desc* desc, float* dst_k, float* dst_v, const float* src_k,
@@ -296,13 +291,8 @@ extern "C" int kvgrad_accumulate(const seco_desc* desc, float* dst_k, float* dst
   for (const void* ptr : {(const void*)dst_k, (const void*)dst_v, (const void*)src_k, (const void*)src_v})
     if (ptr && !aligned16(ptr)) return SECO_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (dst_k && (rc = launch_kvgrad_axpy(dst_k, src_k, scale, desc->batch, desc->n_kv_heads, desc->head_dim,
-                                        desc->g_stride, row_begin, row_end, s)))
-    return rc;
-  if (dst_v && (rc = launch_kvgrad_axpy(dst_v, src_v, scale, desc->batch, desc->n_kv_heads, desc->head_dim,
-                                        desc->g_stride, row_begin, row_end, s)))
-    return rc;
-  return SECO_OK;
+  return launch_kvgrad_axpy(dst_k, dst_v, src_k, src_v, scale, desc->batch, desc->n_kv_heads, desc->head_dim,
+                            desc->g_stride, row_begin, row_end, s);
 }
 
 // ---- cache append and gradient hand-over (appendix listing) ---------------------------------------------------------
@@ -331,13 +321,8 @@ extern "C" int kv_append(const seco_desc* desc, const void* k_new, const void* v
     if (ptr && !aligned16(ptr)) return SECO_ERR_ALIGN;
   const int eb = desc->dtype == SECO_BF16 ? 2 : 4;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (k_new && (rc = launch_rows_copy(k_cache, k_new, eb, desc->batch, desc->n_kv_heads, desc->chunk_len, desc->head_dim,
-                                      desc->kv_stride, desc->q_stride, desc->q_start, s)))
-    return rc;
-  if (v_new && (rc = launch_rows_copy(v_cache, v_new, eb, desc->batch, desc->n_kv_heads, desc->chunk_len, desc->head_dim,
-                                      desc->kv_stride, desc->q_stride, desc->q_start, s)))
-    return rc;
-  return SECO_OK;
+  return launch_rows_copy(k_cache, v_cache, k_new, v_new, eb, desc->batch, desc->n_kv_heads, desc->chunk_len,
+                          desc->head_dim, desc->kv_stride, desc->q_stride, desc->q_start, s);
 }
 
 extern "C" int kvgrad_readout(const seco_desc* desc, const float* gk, const float* gv, void* d_k_new, void* d_v_new,
@@ -350,11 +335,6 @@ extern "C" int kvgrad_readout(const seco_desc* desc, const float* gk, const floa
     if (ptr && !aligned16(ptr)) return SECO_ERR_ALIGN;
   const bool bf16 = desc->dtype == SECO_BF16;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (gk && (rc = launch_readout(d_k_new, gk, scaler, bf16, desc->batch, desc->n_kv_heads, desc->chunk_len, desc->head_dim,
-                                 desc->q_stride, desc->g_stride, desc->q_start, s)))
-    return rc;
-  if (gv && (rc = launch_readout(d_v_new, gv, scaler, bf16, desc->batch, desc->n_kv_heads, desc->chunk_len, desc->head_dim,
-                                 desc->q_stride, desc->g_stride, desc->q_start, s)))
-    return rc;
-  return SECO_OK;
+  return launch_readout(d_k_new, d_v_new, gk, gv, scaler, bf16, desc->batch, desc->n_kv_heads, desc->chunk_len,
+                        desc->head_dim, desc->q_stride, desc->g_stride, desc->q_start, s);
 }

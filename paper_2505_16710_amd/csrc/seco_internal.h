@@ -83,16 +83,19 @@ constexpr int kColTileBf16 = SECO_DKDV_COLS;  // columns per workgroup in launch
 // delta[r] = sum_d dO[r,d] * O[r,d]
 int launch_delta(const AttnParams& p, int dtype, hipStream_t s);
 
-int launch_kvgrad_zero(float* g, int B, int H, int D, const int64_t gs[3], int64_t r0, int64_t r1, hipStream_t s);
-int launch_kvgrad_axpy(float* dst, const float* src, float scale, int B, int H, int D, const int64_t gs[3],
-                       int64_t r0, int64_t r1, hipStream_t s);
+// Bandwidth-bound helpers; each takes a pair of tensors (gK and gV, keys and values) handled by one launch,
+// a NULL member of the pair is skipped.
+int launch_kvgrad_zero(float* ga, float* gb, int B, int H, int D, const int64_t gs[3], int64_t r0, int64_t r1,
+                       hipStream_t s);
+int launch_kvgrad_axpy(float* da, float* db, const float* sa, const float* sb, float scale, int B, int H, int D,
+                       const int64_t gs[3], int64_t r0, int64_t r1, hipStream_t s);
 
 // rows [r0, r0 + C) of a [B, H, *, D] array <- a [B, H, C, D] array (same element type, eb bytes per element)
-int launch_rows_copy(void* dst, const void* src, int eb, int B, int H, int C, int D, const int64_t dst_s[3],
-                     const int64_t src_s[3], int64_t r0, hipStream_t s);
+int launch_rows_copy(void* da, void* db, const void* sa, const void* sb, int eb, int B, int H, int C, int D,
+                     const int64_t dst_s[3], const int64_t src_s[3], int64_t r0, hipStream_t s);
 // out[B, H, C, D] (bf16 or fp32) = scaler * g[rows r0 .. r0 + C) (fp32)
-int launch_readout(void* out, const float* g, float scaler, bool bf16, int B, int H, int C, int D,
-                   const int64_t out_s[3], const int64_t gs[3], int64_t r0, hipStream_t s);
+int launch_readout(void* oa, void* ob, const float* ga, const float* gb, float scaler, bool bf16, int B, int H, int C,
+                   int D, const int64_t out_s[3], const int64_t gs[3], int64_t r0, hipStream_t s);
 
 // Optional per-kernel timing (seco_profile_enable): a scope brackets one launch with HIP events
 // on the launch stream.  Disabled by default; then a scope costs one branch.
