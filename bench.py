@@ -85,7 +85,7 @@ def main():
             self.N, self.C, self.k = N, C, N // C
             self.q, self.kc, self.vc, self.do = make_inputs(N)
             self.o = torch.empty_like(self.q)
-            self.lse = torch.empty(B, Hq, C, device=dev, dtype=torch.float32)
+            self.lse = torch.empty(self.k, B, Hq, C, device=dev, dtype=torch.float32)   # kept per chunk
             self.dq = torch.empty_like(self.q)
             self.gk = torch.empty(B, Hkv, N, D, device=dev, dtype=torch.float32)
             self.gv = torch.empty_like(self.gk)
@@ -101,10 +101,10 @@ def main():
 
         def fwd(self, j):
             seco.seco_chunk_attn_fwd(self.rows(self.q, j), self.kc, self.vc, j * self.C, scale,
-                                     o=self.rows(self.o, j), lse=self.lse, ws=self.ws_fwd)
+                                     o=self.rows(self.o, j), lse=self.lse[j], ws=self.ws_fwd)
 
         def bwd(self, j, weights=None):
-            args = (self.rows(self.q, j), self.kc, self.vc, self.rows(self.o, j), self.lse, self.rows(self.do, j),
+            args = (self.rows(self.q, j), self.kc, self.vc, self.rows(self.o, j), self.lse[j], self.rows(self.do, j),
                     self.gk, self.gv, j * self.C, scale)
             if weights is None:
                 seco.seco_chunk_attn_bwd(*args, d_q=self.rows(self.dq, j), ws=self.ws)
@@ -252,8 +252,23 @@ def main():
                 Lx.fwd(j)
                 Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam))
 
+        def seco_layer_kept():          # stage 2 takes O and LSE from stage 1 (kept per chunk) instead of recomputing
+            for j in range(kx):
+                Lx.fwd(j)
+            seco.kvgrad_zero(Lx.gk, Lx.gv)
+            for j in range(kx - 1, -1, -1):
+                Lx.bwd(j)
+
+        def spaco_layer_kept():
+            for j in range(kx):
+                Lx.fwd(j)
+            seco.kvgrad_zero(Lx.gk, Lx.gv)
+            for j in sel:
+                Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam))
+
         res = {}
-        for name, fn in (("seco", seco_layer), (f"spaco_t{tx}", spaco_layer)):
+        for name, fn in (("seco", seco_layer), (f"spaco_t{tx}", spaco_layer), ("seco_kept_outputs", seco_layer_kept),
+                         (f"spaco_t{tx}_kept_outputs", spaco_layer_kept)):
             fn()
             torch.cuda.synchronize()
             best = 1e9

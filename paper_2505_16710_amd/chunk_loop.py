@@ -33,16 +33,25 @@ class LayerState:
         self.v = torch.zeros_like(self.k)
         self.gk = torch.empty(B, Hkv, N, D, dtype=torch.float32, device=device)
         self.gv = torch.empty_like(self.gk)
+        self.kept = {}      # q_start -> (O, LSE) of stage 1, when attention outputs are kept for stage 2
 
 
 class ChunkAttention(torch.autograd.Function):
     """Attention of one chunk against a layer's cache; backward deposits into the layer's KV-gradient buffers."""
 
     @staticmethod
-    def forward(ctx, q, k_new, v_new, state, q_start, scale, weights, weight_chunk_len):
-        _b.kv_append(k_new, v_new, state.k, state.v, q_start)
-        o, lse = _b.seco_chunk_attn_fwd(q, state.k, state.v, q_start, scale,
-                                        o=torch.empty(q.shape, dtype=q.dtype, device=q.device))
+    def forward(ctx, q, k_new, v_new, state, q_start, scale, weights, weight_chunk_len, keep):
+        # keep: None = always compute; "store" = stage 1, remember (O, LSE); "reuse" = stage 2, take them back
+        # (the rebuilt chunk has the same inputs and the kernels are deterministic, so the values are identical and
+        # the cache rows already hold this chunk's K/V)
+        if keep == "reuse":
+            o, lse = state.kept[q_start]
+        else:
+            _b.kv_append(k_new, v_new, state.k, state.v, q_start)
+            o, lse = _b.seco_chunk_attn_fwd(q, state.k, state.v, q_start, scale,
+                                            o=torch.empty(q.shape, dtype=q.dtype, device=q.device))
+            if keep == "store":
+                state.kept[q_start] = (o, lse)
         ctx.save_for_backward(q, o, lse)
         ctx.state, ctx.q_start, ctx.scale, ctx.weights, ctx.wlen = state, q_start, scale, weights, weight_chunk_len
         return o
@@ -58,7 +67,7 @@ class ChunkAttention(torch.autograd.Function):
             d_q = _b.spaco_chunk_attn_bwd(q, st.k, st.v, o, lse, d_o, st.gk, st.gv, s0, ctx.scale,
                                           ctx.weights, ctx.wlen)
         d_k, d_v = _b.kvgrad_readout(st.gk, st.gv, s0, C, q.dtype)
-        return d_q, d_k, d_v, None, None, None, None, None
+        return d_q, d_k, d_v, None, None, None, None, None, None
 
 
 def _rmsnorm(x, g):
@@ -75,7 +84,7 @@ class ChunkedDecoder:
         self.scale = float(head_dim) ** -0.5
         _b.load_library()          # fail here, loudly, if the HIP library has not been built
 
-    def _chunk(self, tokens, targets, q_start, states, weights, wlen):
+    def _chunk(self, tokens, targets, q_start, states, weights, wlen, keep=None):
         p, B, C = self.p, tokens.shape[0], tokens.shape[1]
         x = p["emb"][tokens]
         for l in range(self.n_layers):
@@ -83,16 +92,20 @@ class ChunkedDecoder:
             q = (h @ p[f"l{l}.wq"]).view(B, C, self.Hq, self.D).transpose(1, 2)
             k = (h @ p[f"l{l}.wk"]).view(B, C, self.Hkv, self.D).transpose(1, 2)
             v = (h @ p[f"l{l}.wv"]).view(B, C, self.Hkv, self.D).transpose(1, 2)
-            o = ChunkAttention.apply(q, k, v, states[l], q_start, self.scale, weights, wlen)
+            o = ChunkAttention.apply(q, k, v, states[l], q_start, self.scale, weights, wlen, keep)
             x = x + o.transpose(1, 2).reshape(B, C, self.Hq * self.D) @ p[f"l{l}.wo"]
             h = _rmsnorm(x, p[f"l{l}.norm2"])
             x = x + F.silu(h @ p[f"l{l}.w1"]) @ p[f"l{l}.w2"]
         logits = _rmsnorm(x, p["norm_f"]) @ p["head"]
         return F.cross_entropy(logits.reshape(B * C, -1).float(), targets.reshape(B * C), reduction="sum")
 
-    def step(self, tokens, targets, chunk_len, selected=None, factor=1.0):
+    def step(self, tokens, targets, chunk_len, selected=None, factor=1.0, keep_attention_outputs=False):
         """One SeCO step (selected is None: Alg. 1) or SpaCO step (Alg. 2, `selected` chunk indices,
-        relay factor `factor`).  Returns (sum of the chunk losses from stage 1, {name: gradient})."""
+        relay factor `factor`).  Returns (sum of the chunk losses from stage 1, {name: gradient}).
+
+        keep_attention_outputs: stage 1 keeps every layer's O and LSE (2 + 4/D bytes per query element: with 288 GB
+        of HBM that is cheap), and the rebuilt chunks of stage 2 take them back instead of running the attention
+        forward again; the gradients are bit-identical to the recomputing schedule."""
         p = self.p
         B, N = tokens.shape
         dtype, dev = p["emb"].dtype, p["emb"].device
@@ -103,7 +116,8 @@ class ChunkedDecoder:
         total = torch.zeros((), dtype=torch.float32, device=dev)
         with torch.no_grad():                                           # stage 1: inference over all chunks
             for s0 in starts:
-                total += self._chunk(tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, states, None, 0)
+                total += self._chunk(tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, states, None, 0,
+                                     "store" if keep_attention_outputs else None)
         for st in states:
             _b.kvgrad_zero(st.gk, st.gv)
         if selected is None:
@@ -113,7 +127,8 @@ class ChunkedDecoder:
         for j in order:                                                 # stage 2: rebuild + back-propagate
             w = None if selected is None else _b.spaco_chunk_weights(order, j, factor)
             s0 = starts[j]
-            loss = self._chunk(tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, states, w, chunk_len)
+            loss = self._chunk(tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, states, w, chunk_len,
+                               "reuse" if keep_attention_outputs else None)
             loss.backward()
         grads = {n: (t.grad if t.grad is not None else torch.zeros_like(t)) for n, t in p.items()}
         return float(total), grads

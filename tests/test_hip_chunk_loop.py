@@ -76,3 +76,17 @@ def test_spaco_step_bf16_matmul_kernels():
     _, g_ref = om.spaco_grads(BF16_CFG, p64, tok, tgt, C, sel, f)
     _, g = dec.step(tok.to(DEV), tgt.to(DEV), C, selected=sel, factor=f)
     _compare(g_ref, g, 6e-2)
+
+
+@pytest.mark.parametrize("dtype,cfg", [(torch.float32, F32_CFG), (torch.bfloat16, BF16_CFG)])
+def test_keeping_attention_outputs_gives_identical_gradients(dtype, cfg):
+    """Stage 2 may take O and LSE from stage 1 instead of running the attention forward again: same values
+    (deterministic kernels, same inputs), hence bit-identical gradients, for SeCO and SpaCO."""
+    p64, dec, tok, tgt = _setup(cfg, 13, 1, 256, dtype)
+    tok, tgt = tok.to(DEV), tgt.to(DEV)
+    for kw in ({}, {"selected": [3, 1, 0], "factor": 4 / 3}):
+        _, g_a = dec.step(tok, tgt, 64, **kw)
+        g_a = {n: t.clone() for n, t in g_a.items()}
+        _, g_b = dec.step(tok, tgt, 64, keep_attention_outputs=True, **kw)
+        for n in g_a:
+            assert torch.equal(g_a[n], g_b[n]), n
