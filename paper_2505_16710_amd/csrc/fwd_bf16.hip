@@ -34,7 +34,7 @@ namespace {
 
 constexpr int BM = 128;  // query rows per workgroup
 constexpr int BNW = 64;  // cache rows per wavefront and tile
-constexpr float kLazy = 8.f;   // threshold of the lazy O rescale, in log2 units
+constexpr float kBig = 1099511627776.f;   // 2^40: a tile's exponentials may sum to this before the reference moves
 
 template <int KH, bool SPLIT>
 __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
@@ -187,39 +187,59 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
             if (kv > qpos) s[kvb][r] = -INFINITY;
           }
       }
-      float mx = s[0][0];
+      // Reference value of the row's exponentials.  A max subtraction only guards against overflow, so the
+      // reference m_run is kept as it is as long as the exponentials stay representable: the (costly) row maximum
+      // is computed only on a row's first visible tile and when the tile's sum of exponentials exceeds kBig = 2^40,
+      // which for a whole kernel is a handful of times.  Exponentials may thus reach 2^40; bf16 and fp32 have
+      // the exponent range for that, and O and the sum are rescaled together when the reference moves.
+      auto tile_max = [&]() {
+        float mx = s[0][0];
 #pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      // Lazy rescaling: the reference maximum of a row moves only when the tile maximum exceeds it by more
-      // than kLazy (log2 units), so exponentials stay below 2^kLazy and the rescale of the O^T accumulator
-      // runs a handful of times per kernel instead of once per tile.
-      const float m_blk = mx * c;
-      const bool bump = m_blk > m_run + kLazy;
-      if (__builtin_amdgcn_ballot_w64(bump) != 0) {
-        const float m_new = bump ? m_blk : m_run;
-        const float alpha = bump ? fast_exp2(m_run - m_new) : 1.f;   // exp2(-inf) = 0 on a row's first visible tile
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
+        return fmaxf(mx, __shfl_xor(mx, 32)) * c;
+      };
+      auto move_reference = [&](float m_new) {          // m_new >= m_run; exp2(-inf - x) = 0 on the first tile
+        const float alpha = fast_exp2(m_run - m_new);
         l_run *= alpha;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
         m_run = m_new;
+      };
+      if (__builtin_amdgcn_ballot_w64(m_run == -INFINITY) != 0) {      // some row has seen nothing yet
+        const float m_blk = tile_max();
+        if (m_run == -INFINITY && m_blk != -INFINITY) m_run = m_blk;    // (o and l_run are still zero)
       }
       // a part of a tile can be fully masked for a row (only when kh > 0 or q_start is unaligned): such a row
       // has seen nothing yet and keeps m_run = -inf; use 0 so that exp2(-inf - (-inf)) never appears
-      const float m_use = m_run == -INFINITY ? 0.f : m_run;
+      float m_use = m_run == -INFINITY ? 0.f : m_run;
       float sum = 0.f;
+      f32x16 e[2];
 #pragma unroll
       for (int kvb = 0; kvb < 2; ++kvb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float e = fast_exp2(__builtin_fmaf(s[kvb][r], c, -m_use));
-          s[kvb][r] = e;
-          sum += e;
+          e[kvb][r] = fast_exp2(__builtin_fmaf(s[kvb][r], c, -m_use));
+          sum += e[kvb][r];
         }
+      if (__builtin_amdgcn_ballot_w64(!(sum <= kBig)) != 0) {           // reference too low for this tile (rare)
+        const float m_blk = tile_max();
+        if (m_blk > m_run) move_reference(m_blk);
+        m_use = m_run == -INFINITY ? 0.f : m_run;
+        sum = 0.f;
+#pragma unroll
+        for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            e[kvb][r] = fast_exp2(__builtin_fmaf(s[kvb][r], c, -m_use));
+            sum += e[kvb][r];
+          }
+      }
+#pragma unroll
+      for (int kvb = 0; kvb < 2; ++kvb) s[kvb] = e[kvb];
       l_run += sum;
 #pragma unroll
       for (int kvb = 0; kvb < 2; ++kvb)

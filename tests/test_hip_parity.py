@@ -474,3 +474,32 @@ def test_append_and_readout_bit_exact(dtype):
         np.testing.assert_array_equal(to_host(d_k), R.kvgrad_readout(gk, r0, r0 + C, scaler, dtype).astype(np.float64))
         np.testing.assert_array_equal(to_host(d_v), R.kvgrad_readout(gv, r0, r0 + C, scaler, dtype).astype(np.float64))
     assert torch.equal(gk_dev.cpu(), torch.from_numpy(gk))            # the buffers themselves are only read
+
+
+def test_forward_reference_moves_when_later_scores_are_much_larger():
+    """The forward keeps a row's exponent reference as long as the exponentials stay representable and moves it when a
+    tile's sum exceeds 2^40 (or overflows).  Inputs built so that every later 64-column tile has scores far above
+    all earlier ones (by 65 and by more than 128 in log2 units), and one with far smaller ones."""
+    B, Hq, Hkv, N, C = 1, 2, 1, 512, 128
+    s = 1 / np.sqrt(128)
+    rng = np.random.default_rng(80)
+    q = np.full((B, Hq, N, 128), 2.0, dtype=np.float32)
+    q[:, 1] = -2.0                                           # second head: scores fall instead of rise
+    k = np.zeros((B, Hkv, N, 128), dtype=np.float32)
+    k[:, :, 64:128] = 2.0                                    # dot 512  -> +65 in log2 units
+    k[:, :, 128:192] = 2.0
+    k[:, :, 128:192, :64] = 7.0                              # dot 1152 -> +147: exp2 overflows before the move
+    k[:, :, 192:] = 8.0                                      # dot 2048
+    k += 0.01 * rng.standard_normal(k.shape).astype(np.float32)
+    v = rng.standard_normal((B, Hkv, N, 128)).astype(np.float32)
+    from workloads import round_to
+    q, k, v = (round_to(t, "bf16") for t in (q, k, v))
+    qd, kd, vd = (to_dev(t, "bf16") for t in (q, k, v))
+    for j in range(N // C):
+        sl = slice(j * C, (j + 1) * C)
+        o, lse = seco.seco_chunk_attn_fwd(qd[:, :, sl], kd, vd, j * C, s)
+        ro, rl = A.chunk_attn_fwd(q[:, :, sl], k, v, j * C, s)
+        oh, lh = to_host(o), to_host(lse)
+        assert np.isfinite(oh).all() and np.isfinite(lh).all()
+        assert max_rel(oh, ro) <= 1e-2, j
+        assert max_rel(lh, rl) <= 1e-2, j
