@@ -266,9 +266,23 @@ def main():
             for j in sel:
                 Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam))
 
+        def spaco_percall_layer():      # every chunk back-propagated, each call with its own draw of t earlier chunks
+            for j in range(kx):
+                Lx.fwd(j)
+            seco.kvgrad_zero(Lx.gk, Lx.gv)
+            for j in range(kx - 1, -1, -1):
+                Lx.fwd(j)
+                Lx.bwd(j, seco.spaco_percall_weights(cx.seed, 0, j, tx))
+
+        def spaco_last_call():          # the single call of the last chunk with t sampled earlier chunks + itself
+            j = kx - 1
+            Lx.fwd(j)
+            Lx.bwd(j, seco.spaco_percall_weights(cx.seed, 0, j, tx))
+
         res = {}
         for name, fn in (("seco", seco_layer), (f"spaco_t{tx}", spaco_layer), ("seco_kept_outputs", seco_layer_kept),
-                         (f"spaco_t{tx}_kept_outputs", spaco_layer_kept)):
+                         (f"spaco_t{tx}_kept_outputs", spaco_layer_kept), (f"spaco_percall_t{tx}", spaco_percall_layer),
+                         (f"spaco_last_call_t{tx}", spaco_last_call)):
             fn()
             torch.cuda.synchronize()
             best = 1e9

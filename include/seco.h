@@ -176,6 +176,16 @@ int kvgrad_readout(const seco_desc* desc, const float* gk, const float* gv, void
 int spaco_select_chunks(uint64_t seed, uint64_t step, int32_t k, int32_t t, int32_t* out_host);
 
 /*
+ * Weight vector of the policy "every chunk back-propagated, each call with its own draw", host only: call j draws
+ * m = min(t, j) of its j earlier chunks (spaco_select_chunks with step * 2^20 + j as the step) and weights them
+ * j / m, its own rows 1.  Each earlier chunk then has expected weight 1 (unbiased dK/dV for the layer) and dQ is
+ * exact, because every chunk is back-propagated: one reading of "a few uniformly sampled earlier chunks plus the
+ * current chunk"; Alg. 2 itself draws once per iteration (spaco_select_chunks + spaco_chunk_weights).
+ * w_host: HOST array of j+1 floats.
+ */
+int spaco_percall_weights(uint64_t seed, uint64_t step, int32_t j, int32_t t, float* w_host);
+
+/*
  * Selection by independent inclusion, host only: every chunk 0..k-1 is selected with probability q, independently
  * (the sampling law under which the survival argument of Sec. 5, "Compensation Factor", holds exactly: a chain
  * through p+1 chunks survives with probability q^(p+1); with relay factor 1/q and an overall 1/q the gradient

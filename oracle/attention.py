@@ -49,6 +49,7 @@ __all__ = [
     "chunk_attn_bwd",
     "seco_layer",
     "spaco_layer",
+    "weighted_layer",
 ]
 
 
@@ -269,3 +270,28 @@ def spaco_layer(Q, K, V, dO, chunk_len, scale, selected, factor, tier="matmul"):
                 gK[:, :, t0:t0 + ci] += factor * dk[:, :, t0:t0 + ci]
                 gV[:, :, t0:t0 + ci] += factor * dv[:, :, t0:t0 + ci]
     return O, LSE, dQ, gK, gV
+
+
+def weighted_layer(Q, K, V, dO, chunk_len, scale, calls, tier="matmul"):
+    """A layer's backward under an arbitrary host policy: `calls` is a list of (j, w) with j the chunk that is
+    back-propagated and w the weight vector w[0..j] its call uses (w[i] multiplies what the call deposits on the
+    rows of chunk i; see the library's spaco_chunk_attn_bwd).  Calls are processed in the given order.
+
+    Alg. 2 with its single draw is one such policy; so are the two other readings of "a few sampled earlier
+    chunks plus the current chunk": one call for the last chunk only, or every chunk back-propagated with its own
+    draw of earlier chunks.  returns dQ, gK, gV.
+    """
+    Q, K, V, dO = _as64(Q), _as64(K), _as64(V), _as64(dO)
+    chunks = _chunks(Q.shape[2], chunk_len)
+    dQ, gK, gV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
+    for j, w in calls:
+        s0, c = chunks[j]
+        o_j, lse_j = chunk_attn_fwd(Q[:, :, s0:s0 + c], K, V, s0, scale, tier)
+        dq, dk, dv = chunk_attn_bwd(Q[:, :, s0:s0 + c], K, V, o_j, lse_j, dO[:, :, s0:s0 + c], s0, scale, tier)
+        dQ[:, :, s0:s0 + c] = dq
+        for i in range(j + 1):
+            if w[i] != 0:
+                t0, ci = chunks[i]
+                gK[:, :, t0:t0 + ci] += float(w[i]) * dk[:, :, t0:t0 + ci]
+                gV[:, :, t0:t0 + ci] += float(w[i]) * dv[:, :, t0:t0 + ci]
+    return dQ, gK, gV

@@ -114,3 +114,18 @@ def path_ratio(k, t, p):
         num *= k - i
         den *= t - i
     return num / den
+
+
+def percall_weights(seed, step, j, t):
+    """Policy "every chunk back-propagated, each call with its own draw": call j draws m = min(t, j) of its j
+    earlier chunks uniformly (stream keyed by (seed, step * 2^20 + j)) and weights them j / m, its own rows 1.
+    Every earlier chunk is included with probability m / j, so the expected weight of each is 1: the layer's dK/dV
+    are unbiased, and dQ is exact because every chunk is back-propagated (one reading of "a few uniformly sampled
+    earlier chunks plus the current chunk").  Returns w[0..j] (fp32)."""
+    w = np.zeros(j + 1, dtype=np.float32)
+    w[j] = 1.0
+    m = min(t, j)
+    if m > 0:
+        for i in select_chunks(seed, step * (1 << 20) + j, j, m):
+            w[int(i)] = np.float32(j / m)
+    return w

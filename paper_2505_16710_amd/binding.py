@@ -59,6 +59,8 @@ def load_library():
     lib.kv_append.restype = lib.kvgrad_readout.restype = C.c_int
     lib.spaco_select_chunks.argtypes = [C.c_uint64, C.c_uint64, i32, i32, C.POINTER(i32)]
     lib.spaco_chunk_weights.argtypes = [C.POINTER(i32), i32, i32, C.c_float, C.POINTER(C.c_float)]
+    lib.spaco_percall_weights.argtypes = [C.c_uint64, C.c_uint64, i32, i32, C.POINTER(C.c_float)]
+    lib.spaco_percall_weights.restype = C.c_int
     lib.spaco_select_bernoulli.argtypes = [C.c_uint64, C.c_uint64, i32, C.c_double, C.POINTER(i32), C.POINTER(i32)]
     lib.spaco_select_bernoulli.restype = C.c_int
     lib.spaco_compensation_factor.argtypes = [i32, i32, C.c_float]
@@ -270,6 +272,13 @@ def spaco_select_chunks(seed, step, k, t):
     out = (C.c_int32 * max(int(t), 1))()
     _check(load_library().spaco_select_chunks(int(seed), int(step), int(k), int(t), out), "spaco_select_chunks")
     return list(out[:t])
+
+
+def spaco_percall_weights(seed, step, j, t):
+    """Weight vector w[0..j] of call j when every call draws min(t, j) of its earlier chunks itself (list of float)."""
+    w = (C.c_float * (int(j) + 1))()
+    _check(load_library().spaco_percall_weights(int(seed), int(step), int(j), int(t), w), "spaco_percall_weights")
+    return list(w)
 
 
 def spaco_select_bernoulli(seed, step, k, q):

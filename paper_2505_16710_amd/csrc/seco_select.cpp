@@ -52,6 +52,22 @@ extern "C" int spaco_select_chunks(uint64_t seed, uint64_t step, int32_t k, int3
   return SECO_OK;
 }
 
+extern "C" int spaco_percall_weights(uint64_t seed, uint64_t step, int32_t j, int32_t t, float* w_host) {
+  if (!w_host) return SECO_ERR_NULL;
+  if (j < 0 || t < 0) return SECO_ERR_RANGE;
+  std::fill(w_host, w_host + j + 1, 0.f);
+  w_host[j] = 1.f;
+  const int32_t m = std::min(t, j);
+  if (m > 0) {
+    std::vector<int32_t> sel(m);
+    const int rc = spaco_select_chunks(seed, step * (1ull << 20) + (uint64_t)j, j, m, sel.data());
+    if (rc) return rc;
+    const float w = (float)((double)j / (double)m);
+    for (int32_t i : sel) w_host[i] = w;
+  }
+  return SECO_OK;
+}
+
 extern "C" int spaco_select_bernoulli(uint64_t seed, uint64_t step, int32_t k, double q, int32_t* out_host,
                                       int32_t* n_selected_host) {
   if (!out_host || !n_selected_host) return SECO_ERR_NULL;

@@ -189,3 +189,14 @@ def test_append_and_readout_validation():
     assert lib.kvgrad_readout(C.byref(d), FAKE, FAKE, FAKE, FAKE, float("inf"), None) == -8
     assert lib.kvgrad_readout(C.byref(desc(dtype=B.SECO_F32, head_dim=12)), FAKE, FAKE, FAKE, FAKE, 1.0, None) == -3
     assert lib.kvgrad_readout(C.byref(d), None, None, None, None, 1.0, None) == 0           # nothing to do
+
+
+def test_percall_weights_match_oracle_bit_exactly():
+    for seed in (0, 5, 2 ** 64 - 1):
+        for step in (0, 1, 4095):
+            for j, t in [(0, 4), (1, 4), (2, 1), (7, 4), (15, 4), (31, 8), (127, 8)]:
+                got = np.array(seco.spaco_percall_weights(seed, step, j, t), dtype=np.float32)
+                np.testing.assert_array_equal(got, S.percall_weights(seed, step, j, t))
+    lib = seco.load_library()
+    assert lib.spaco_percall_weights(0, 0, -1, 4, (C.c_float * 1)()) == -8
+    assert lib.spaco_percall_weights(0, 0, 3, 4, None) == -1

@@ -503,3 +503,17 @@ def test_forward_reference_moves_when_later_scores_are_much_larger():
         assert np.isfinite(oh).all() and np.isfinite(lh).all()
         assert max_rel(oh, ro) <= 1e-2, j
         assert max_rel(lh, rl) <= 1e-2, j
+
+
+def test_per_call_draw_policy_parity():
+    """Every chunk back-propagated, each call with its own draw of earlier chunks (weights from the library's host
+    policy call, which the CPU tests compare bit for bit with the oracle's)."""
+    N, C, t, seed = 1024, 128, 3, 17
+    k = N // C
+    x = small_layer(90, 1, 4, 2, N, 128, "bf16")
+    s = 1 / np.sqrt(128)
+    got = run_layer(x, C, s, "bf16", selected=list(range(k)), weights_fn=lambda j: seco.spaco_percall_weights(seed, 0, j, t))
+    calls = [(j, S.percall_weights(seed, 0, j, t)) for j in range(k - 1, -1, -1)]
+    dq, gk, gv = A.weighted_layer(x["q"], x["k"], x["v"], x["do"], C, s, calls)
+    for n, r in (("dq", dq), ("gk", gk), ("gv", gv)):
+        assert max_rel(got[n], r) <= TOL["bf16"][n], n

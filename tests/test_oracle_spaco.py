@@ -155,3 +155,45 @@ def test_ragged_last_chunk():
     sp = A.spaco_layer(x["q"], x["k"], x["v"], x["do"], 4, 0.5, [0, 1, 2, 3], 1.0)
     for a, b in zip(sp, chunked):
         assert np.array_equal(a, b)
+
+
+def test_per_call_draw_policy_is_exactly_unbiased_by_enumeration():
+    """Every chunk back-propagated; call j keeps m = min(t, j) of its j earlier chunks with weight j / m.
+    Averaged over all draws of every call the layer's gK/gV equal SeCO's, and dQ is SeCO's for every draw."""
+    import itertools
+    from oracle import attention as A
+    rng = np.random.default_rng(5)
+    B, Hq, Hkv, N, D, C, t = 1, 2, 1, 16, 4, 4, 2
+    Q, dO = rng.standard_normal((2, B, Hq, N, D))
+    K, V = rng.standard_normal((2, B, Hkv, N, D))
+    s = 0.5
+    _, _, dq_ref, gk_ref, gv_ref = A.seco_layer(Q, K, V, dO, C, s)
+    k = N // C
+    per_call = []
+    for j in range(k):
+        m = min(t, j)
+        subsets = list(itertools.combinations(range(j), m)) if m else [()]
+        per_call.append([(j, np.array([(j / m if i in sub else 0.0) for i in range(j)] + [1.0])) for sub in subsets])
+    gk_mean, gv_mean, n = 0.0, 0.0, 0
+    for combo in itertools.product(*per_call):
+        dq, gk, gv = A.weighted_layer(Q, K, V, dO, C, s, sorted(combo, key=lambda cw: -cw[0]))
+        np.testing.assert_allclose(dq, dq_ref, rtol=0, atol=1e-13)
+        gk_mean, gv_mean, n = gk_mean + gk, gv_mean + gv, n + 1
+    assert n == 1 * 1 * 1 * 3            # draws: j=0: 1, j=1: 1 (m=1 of 1), j=2: C(2,2)=1, j=3: C(3,2)=3
+    np.testing.assert_allclose(gk_mean / n, gk_ref, rtol=0, atol=1e-12 * np.abs(gk_ref).max())
+    np.testing.assert_allclose(gv_mean / n, gv_ref, rtol=0, atol=1e-12 * np.abs(gv_ref).max())
+
+
+def test_percall_weights_follow_the_policy():
+    from oracle.selection import percall_weights
+    for j, t in [(0, 4), (1, 4), (3, 4), (9, 4), (31, 8)]:
+        w = percall_weights(7, 3, j, t)
+        m = min(t, j)
+        assert w.shape == (j + 1,) and w[j] == 1.0
+        assert int((w[:j] != 0).sum()) == m
+        if m:
+            assert np.all(w[:j][w[:j] != 0] == np.float32(j / m))
+    # inclusion frequency of an earlier chunk over many steps ~ m / j
+    j, t, n = 8, 2, 4000
+    hits = sum(percall_weights(1, step, j, t)[3] != 0 for step in range(n))
+    assert abs(hits - n * t / j) < 6 * np.sqrt(n * (t / j) * (1 - t / j))
