@@ -182,11 +182,15 @@ def main():
             seco.seco_profile_enable(kinds=[dom])
         else:
             seco.seco_profile_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         run_step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     prof = None
     if not args.no_profile:
         prof = seco.seco_profile_read()
@@ -203,6 +207,7 @@ def main():
                    "n_chunks": k_chunks, "flops_per_step": flops_step},
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "launch_mode": "hip_graph_replay" if args.graph else "eager",
+        "step_ms_min": round(per_step[0], 4), "step_ms_median": round(per_step[len(per_step) // 2], 4),
     }
 
     if prof is not None:
