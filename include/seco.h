@@ -18,7 +18,8 @@
  *   - All tensor pointers are DEVICE pointers unless a name ends in _host.
  *   - Layout: [batch, head, row, head_dim]; head_dim is contiguous; the three
  *     outer strides are given explicitly, in ELEMENTS.  Every row must start on
- *     a 16-byte boundary (base pointer and strides).
+ *     a 16-byte boundary (base pointer and strides); a row stride may not exceed 2^22 elements
+ *     (SECO_ERR_TOO_LARGE).
  *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
  *   - The caller owns every buffer and the stream.  Entry points validate,
  *     enqueue kernels on `hip_stream` (a hipStream_t, may be NULL for the

@@ -36,6 +36,8 @@ int check_strides(const int64_t s[3], int elem_bytes, int D) {
   for (int i = 0; i < 3; ++i)
     if (s[i] < 0 || s[i] % per16 != 0) return SECO_ERR_ALIGN;
   if (s[2] < D) return SECO_ERR_ALIGN;
+  // the kernels address the rows of a tile with 32-bit byte offsets from the tile's first row
+  if (s[2] > ((int64_t)1 << 22)) return SECO_ERR_TOO_LARGE;
   return SECO_OK;
 }
 

@@ -62,6 +62,7 @@ def test_validation_status_codes():
     assert fwd(desc(), q=None) == -1
     assert fwd(desc(), k=C.c_void_p(0x1004)) == -5
     assert fwd(desc(q_start=1 << 30)) == -10
+    assert fwd(desc(kv_stride=(C.c_int64 * 3)(1 << 40, 1 << 32, (1 << 22) + 8))) == -10   # row stride beyond the 32-bit tile offsets
     assert seco.load_library().seco_chunk_attn_fwd(None, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None) == -1
     assert bwd(desc(), ws=None) == -6
     assert bwd(desc(), ws_bytes=16) == -6
