@@ -30,6 +30,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions from scalar code.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # machine scheduler strategy that keeps memory (LDS) instructions in clauses: measured 3 % faster on the
+         # forward kernel and about 0.5 % on the whole benchmark step than the default
+         "-mllvm", "-amdgpu-sched-strategy=max-memory-clause",
          "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 
 
