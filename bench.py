@@ -261,6 +261,28 @@ def main():
                 Lx.fwd(j)
                 Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam))
 
+        lse_full = torch.empty(B, Hq, cx.seq_len, device=dev, dtype=torch.float32)
+        d_full = seco.binding.make_desc(Lx.q, Lx.kc, 0, scale, o=Lx.o)
+        n_full = seco.seco_workspace_bytes(d_full, seco.binding.SECO_OP_FWD)
+        ws_full = torch.empty(n_full, device=dev, dtype=torch.uint8) if n_full else False
+
+        def prefill_stage1():           # stage 1 as ONE forward call over the whole sequence; LSE handed out per chunk
+            seco.seco_chunk_attn_fwd(Lx.q, Lx.kc, Lx.vc, 0, scale, o=Lx.o, lse=lse_full, ws=ws_full)
+            for j in range(kx):
+                Lx.lse[j].copy_(lse_full[:, :, j * Lx.C:(j + 1) * Lx.C])
+
+        def seco_layer_prefill_kept():  # whole-sequence stage 1 + kept outputs: stage 2 is backward calls only
+            prefill_stage1()
+            seco.kvgrad_zero(Lx.gk, Lx.gv)
+            for j in range(kx - 1, -1, -1):
+                Lx.bwd(j)
+
+        def spaco_layer_prefill_kept():
+            prefill_stage1()
+            seco.kvgrad_zero(Lx.gk, Lx.gv)
+            for j in sel:
+                Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam))
+
         def seco_layer_kept():          # stage 2 takes O and LSE from stage 1 (kept per chunk) instead of recomputing
             for j in range(kx):
                 Lx.fwd(j)
@@ -290,7 +312,10 @@ def main():
 
         res = {}
         for name, fn in (("seco", seco_layer), (f"spaco_t{tx}", spaco_layer), ("seco_kept_outputs", seco_layer_kept),
-                         (f"spaco_t{tx}_kept_outputs", spaco_layer_kept), (f"spaco_percall_t{tx}", spaco_percall_layer),
+                         (f"spaco_t{tx}_kept_outputs", spaco_layer_kept),
+                         ("seco_prefill_kept_outputs", seco_layer_prefill_kept),
+                         (f"spaco_t{tx}_prefill_kept_outputs", spaco_layer_prefill_kept),
+                         (f"spaco_percall_t{tx}", spaco_percall_layer),
                          (f"spaco_last_call_t{tx}", spaco_last_call)):
             fn()
             torch.cuda.synchronize()

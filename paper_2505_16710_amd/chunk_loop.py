@@ -45,7 +45,13 @@ class ChunkAttention(torch.autograd.Function):
         # (the rebuilt chunk has the same inputs and the kernels are deterministic, so the values are identical and
         # the cache rows already hold this chunk's K/V)
         if keep == "reuse":
-            o, lse = state.kept[q_start]
+            # the span of stage 1 that holds this chunk's rows (the chunk itself, or a longer span to cut from)
+            s0, (o_all, lse_all) = max((kv for kv in state.kept.items() if kv[0] <= q_start), key=lambda kv: kv[0])
+            a, b = q_start - s0, q_start - s0 + q.shape[2]
+            if a == 0 and b == o_all.shape[2]:
+                o, lse = o_all, lse_all
+            else:
+                o, lse = o_all[:, :, a:b].contiguous(), lse_all[:, :, a:b].contiguous()
         else:
             _b.kv_append(k_new, v_new, state.k, state.v, q_start)
             o, lse = _b.seco_chunk_attn_fwd(q, state.k, state.v, q_start, scale,
@@ -99,13 +105,19 @@ class ChunkedDecoder:
         logits = _rmsnorm(x, p["norm_f"]) @ p["head"]
         return F.cross_entropy(logits.reshape(B * C, -1).float(), targets.reshape(B * C), reduction="sum")
 
-    def step(self, tokens, targets, chunk_len, selected=None, factor=1.0, keep_attention_outputs=False):
+    def step(self, tokens, targets, chunk_len, selected=None, factor=1.0, keep_attention_outputs=False,
+             stage1_chunk_len=None):
         """One SeCO step (selected is None: Alg. 1) or SpaCO step (Alg. 2, `selected` chunk indices,
         relay factor `factor`).  Returns (sum of the chunk losses from stage 1, {name: gradient}).
 
         keep_attention_outputs: stage 1 keeps every layer's O and LSE (2 + 4/D bytes per query element: with 288 GB
         of HBM that is cheap), and the rebuilt chunks of stage 2 take them back instead of running the attention
-        forward again; the gradients are bit-identical to the recomputing schedule."""
+        forward again; the gradients are bit-identical to the recomputing schedule.
+        stage1_chunk_len: chunk length of the inference pass only (default chunk_len).  Stage 1 holds no graph, so on a
+        GPU with room for one layer's activations of the whole sequence it can run as a single chunk (a plain
+        prefill); together with keep_attention_outputs, stage 2 then launches backward kernels only.  The caches
+        and kept outputs are then produced by differently shaped launches, so gradients agree with the chunked
+        stage 1 to rounding, not bit for bit."""
         p = self.p
         B, N = tokens.shape
         dtype, dev = p["emb"].dtype, p["emb"].device
@@ -114,9 +126,10 @@ class ChunkedDecoder:
         for t in p.values():
             t.grad = None
         total = torch.zeros((), dtype=torch.float32, device=dev)
+        c1 = stage1_chunk_len or chunk_len
         with torch.no_grad():                                           # stage 1: inference over all chunks
-            for s0 in starts:
-                total += self._chunk(tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, states, None, 0,
+            for s0 in range(0, N, c1):
+                total += self._chunk(tokens[:, s0:s0 + c1], targets[:, s0:s0 + c1], s0, states, None, 0,
                                      "store" if keep_attention_outputs else None)
         for st in states:
             _b.kvgrad_zero(st.gk, st.gv)

@@ -90,3 +90,22 @@ def test_keeping_attention_outputs_gives_identical_gradients(dtype, cfg):
         _, g_b = dec.step(tok, tgt, 64, keep_attention_outputs=True, **kw)
         for n in g_a:
             assert torch.equal(g_a[n], g_b[n]), n
+
+
+def test_whole_sequence_stage1_with_kept_outputs_matches_oracle():
+    """Stage 1 as one plain forward over the whole sequence, stage 2 from its kept O / LSE: same gradients as the
+    oracle's Alg. 1 / Alg. 2 (to the usual tolerance; the launches differ in shape from the chunked stage 1)."""
+    N, C = 192, 32
+    p64, dec, tok, tgt = _setup(F32_CFG, 15, 2, N, torch.float32)
+    _, g_ref = om.monolithic_grads(F32_CFG, p64, tok, tgt)
+    _, g = dec.step(tok.to(DEV), tgt.to(DEV), C, keep_attention_outputs=True, stage1_chunk_len=N)
+    _compare(g_ref, g, 5e-4)
+    sel, f = [5, 3, 0], 2.0
+    _, g_ref = om.spaco_grads(F32_CFG, p64, tok, tgt, C, sel, f)
+    _, g = dec.step(tok.to(DEV), tgt.to(DEV), C, selected=sel, factor=f, keep_attention_outputs=True, stage1_chunk_len=N)
+    _compare(g_ref, g, 5e-4)
+    # bf16 matrix-core kernels
+    p64, dec, tok, tgt = _setup(BF16_CFG, 16, 1, 256, torch.bfloat16)
+    _, g_ref = om.monolithic_grads(BF16_CFG, p64, tok, tgt)
+    _, g = dec.step(tok.to(DEV), tgt.to(DEV), 64, keep_attention_outputs=True, stage1_chunk_len=256)
+    _compare(g_ref, g, 6e-2)
