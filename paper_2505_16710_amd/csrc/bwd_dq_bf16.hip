@@ -177,14 +177,17 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
         for (int t = 0; t < 8; ++t) s = mfma(lds_row8(kt, kvb * 32 + l32, 2 * t + g), qf[t], s);
 #pragma unroll
         for (int t = 0; t < 8; ++t) dp = mfma(lds_row8(vt, kvb * 32 + l32, 2 * t + g), dof[t], dp);
-        const bool diag = col0 + 31 > p.q_start + m0;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kv = col0 + 8 * (r >> 2) + 4 * g + (r & 3);
-          float pr = fast_exp2(__builtin_fmaf(s[r], c, -lse_c));
-          if (diag && kv > qpos) pr = 0.f;
-          s[r] = pr * (dp[r] - delta);
+        for (int r = 0; r < 16; ++r) s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_c));
+        if (col0 + 31 > p.q_start + m0) {   // block reaches past this wavefront's first row: zero what lies above the diagonal
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kv = col0 + 8 * (r >> 2) + 4 * g + (r & 3);
+            if (kv > qpos) s[r] = 0.f;
+          }
         }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] *= dp[r] - delta;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const bf16x8 dsb = pack8(s, t);
