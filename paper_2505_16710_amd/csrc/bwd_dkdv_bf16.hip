@@ -156,6 +156,14 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     if (tid < 2 * BQ) *reinterpret_cast<SECO_LDS float*>(smem + slot * kStageBytes + 2 * kTileBytes + tid * 4) = stat;
   };
 
+  // lane-dependent parts of the LDS operand addresses (constant for the whole kernel)
+  int r_off[8];
+  TrOff t_off[4];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) r_off[t] = row8_lane_off(l32, 2 * t + g);
+#pragma unroll
+  for (int db = 0; db < 4; ++db) t_off[db] = tr8_lane_off(db, lane);
+
   f32x16 acc[4];   // role A: dV, role B: dK  (32 cache rows x 128)
 #pragma unroll
   for (int db = 0; db < 4; ++db)
@@ -240,7 +248,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
         lds_char* qt1 = smem + slot1 * kStageBytes;
         SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt1 + 2 * kTileBytes);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) x[t] = lds_row8(qt1, l32, 2 * t + g);
+        for (int t = 0; t < 8; ++t) x[t] = lds_row8_at(qt1 + r_off[t], 0);
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = lse_s[8 * (r >> 2) + 4 * g + (r & 3)];
@@ -248,7 +256,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
           s = mfma(x[t], frag[t], s);
-          x[t] = lds_row8(qt1, 32 + l32, 2 * t + g);
+          x[t] = lds_row8_at(qt1 + r_off[t], 32);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r]);
@@ -264,7 +272,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
           s = mfma(x[t], frag[t], s);
-          x[t] = lds_tr8(dot, 16 * (t >> 2), t & 3, lane);
+          x[t] = lds_tr8_at(dot, t_off[t & 3], 16 * (t >> 2));
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r]);
@@ -278,14 +286,14 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           acc[i & 3] = mfma(pa0[i >> 2], x[i], acc[i & 3]);
-          x[i] = lds_tr8(dot, 32 + 16 * (i >> 2), i & 3, lane);
+          x[i] = lds_tr8_at(dot, t_off[i & 3], 32 + 16 * (i >> 2));
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i & 3] = mfma(pa1[i >> 2], x[i], acc[i & 3]);
       } else {
         SECO_LDS float* delta_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + BQ;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) x[t] = lds_row8(dot, l32, 2 * t + g);
+        for (int t = 0; t < 8; ++t) x[t] = lds_row8_at(dot + r_off[t], 0);
         lds_char* pb0 = pslot(it & 1, 0);
         const bf16x8 ph0[2] = {p_half(pb0, 0), p_half(pb0, 1)};
         f32x16 d;
@@ -295,7 +303,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
           d = mfma(x[t], frag[t], d);
-          x[t] = lds_row8(dot, 32 + l32, 2 * t + g);
+          x[t] = lds_row8_at(dot + r_off[t], 32);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) d[r] *= (float)ph0[r >> 3][r & 7];
@@ -308,7 +316,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
           d = mfma(x[t], frag[t], d);
-          x[t] = lds_tr8(qt, 16 * (t >> 2), t & 3, lane);
+          x[t] = lds_tr8_at(qt, t_off[t & 3], 16 * (t >> 2));
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) d[r] *= (float)ph1[r >> 3][r & 7];
@@ -317,7 +325,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           acc[i & 3] = mfma(ds0[i >> 2], x[i], acc[i & 3]);
-          x[i] = lds_tr8(qt, 32 + 16 * (i >> 2), i & 3, lane);
+          x[i] = lds_tr8_at(qt, t_off[i & 3], 32 + 16 * (i >> 2));
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i & 3] = mfma(ds1[i >> 2], x[i], acc[i & 3]);

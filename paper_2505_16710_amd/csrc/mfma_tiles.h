@@ -64,6 +64,30 @@ __device__ __forceinline__ bf16x8 lds_tr8(lds_char* tile, int row0, int db, int 
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// The same two reads with the lane-dependent part of the address taken out of the loop.  tile_off(row0 + r, chunk)
+// = row0 * kRowBytes + tile_off(r, chunk) whenever row0 is a multiple of 16 (the swizzle looks at the low four row
+// bits only), so a kernel can compute these offsets once; an access in its main loop is then
+// tile base + per-lane offset (one add per tile and offset) + a compile-time constant folded into the instruction.
+struct TrOff { int lo, hi; };     // rows r and r + 8 of lds_tr8
+__device__ __forceinline__ int row8_lane_off(int l32, int chunk) { return tile_off(l32, chunk); }
+__device__ __forceinline__ TrOff tr8_lane_off(int db, int lane) {
+  const int ii = lane & 15, half = (lane >> 4) & 1, g = lane >> 5;
+  const int row = 4 * g + (ii >> 2);
+  const int chunk = 4 * db + 2 * half + ((ii & 3) >> 1);
+  const int sub = (ii & 1) << 3;
+  return {tile_off(row, chunk) + sub, tile_off(row + 8, chunk) + sub};
+}
+__device__ __forceinline__ bf16x8 lds_row8_at(lds_char* tile_plus_off, int row0) {   // row0: multiple of 32
+  return *reinterpret_cast<SECO_LDS bf16x8*>(tile_plus_off + row0 * kRowBytes);
+}
+__device__ __forceinline__ bf16x8 lds_tr8_at(lds_char* tile, TrOff off, int row0) {   // row0: multiple of 16
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<SECO_LDS s16x4*>(tile + off.lo + row0 * kRowBytes));
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<SECO_LDS s16x4*>(tile + off.hi + row0 * kRowBytes));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
