@@ -146,6 +146,14 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
     }
   };
 
+  // lane-dependent parts of the LDS operand addresses (constant for the whole kernel)
+  int r_off[8];
+  TrOff t_off[4];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) r_off[t] = row8_lane_off(l32, 2 * t + g);
+#pragma unroll
+  for (int db = 0; db < 4; ++db) t_off[db] = tr8_lane_off(db, lane);
+
   f32x16 dq[4];
 #pragma unroll
   for (int db = 0; db < 4; ++db)
@@ -174,9 +182,9 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) s = mfma(lds_row8(kt, kvb * 32 + l32, 2 * t + g), qf[t], s);
+        for (int t = 0; t < 8; ++t) s = mfma(lds_row8_at(kt + r_off[t], kvb * 32), qf[t], s);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) dp = mfma(lds_row8(vt, kvb * 32 + l32, 2 * t + g), dof[t], dp);
+        for (int t = 0; t < 8; ++t) dp = mfma(lds_row8_at(vt + r_off[t], kvb * 32), dof[t], dp);
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_c));
         if (col0 + 31 > p.q_start + m0) {   // block reaches past this wavefront's first row: zero what lies above the diagonal
@@ -192,7 +200,7 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
         for (int t = 0; t < 2; ++t) {
           const bf16x8 dsb = pack8(s, t);
 #pragma unroll
-          for (int db = 0; db < 4; ++db) dq[db] = mfma(lds_tr8(kt, kvb * 32 + 16 * t, db, lane), dsb, dq[db]);
+          for (int db = 0; db < 4; ++db) dq[db] = mfma(lds_tr8_at(kt, t_off[db], kvb * 32 + 16 * t), dsb, dq[db]);
         }
       }
     }
