@@ -26,6 +26,12 @@
 //
 // Column tiles are enumerated from a by-value segment table (runs of cache rows that share
 // one non-zero weight); SpaCO's unselected chunks simply have no tiles.
+//
+// A workgroup occupies a whole CU, so a launch runs in rounds of 256 column tiles and a last round with few
+// tiles costs as much as a full one.  When the last round would hold at most 128 tiles, the last column tiles
+// of every (batch, KV head) are therefore divided among 2 or 4 workgroups by query head: each writes its
+// fp32 sums to the workspace and dkdv_tail_merge_kernel adds them to gK/gV in head order (still one writer
+// per element and a fixed summation order, so results stay reproducible).
 #include "mfma_tiles.h"
 #include "seco_internal.h"
 
@@ -50,9 +56,18 @@ struct DkdvCfg {
   static constexpr int kCols = NCB * 32;                                // cache rows per workgroup
 };
 
+// The last n_tiles column tiles of every (batch, KV head) are each divided among hs workgroups by query head;
+// their sums go to part[split tile][head share][dV, dK][cache row of the tile][128] instead of gK/gV.
+struct TailSplit {
+  int n_tiles;
+  int hs;
+  float* part;
+};
+
 // (RB is fixed to 2 by the hand-pipelined main loop.)
 template <int NCB, int RB>
-__global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, SegTable seg, int total_items) {
+__global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, SegTable seg, TailSplit ts,
+                                                                  int total_items) {
   using Cfg = DkdvCfg<NCB, RB>;
   constexpr int BQ = Cfg::kBQ, kTileBytes = Cfg::kTileBytes, kStageBytes = Cfg::kStageBytes;
   constexpr int NW = 2 * NCB;                 // wavefronts
@@ -67,10 +82,17 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int role = wave / NCB, cb = wave % NCB;
-  // item -> (batch, kv head, column tile)
+  // item -> (batch, kv head, column tile, share of the query heads); the divided tiles come last in a unit
   const int n_ctiles = seg.tile_begin[seg.n];
-  const int tile = item % n_ctiles;
-  const int kvh = (item / n_ctiles) % p.Hkv, b = item / (n_ctiles * p.Hkv);
+  const int n_whole = n_ctiles - ts.n_tiles;
+  const int per_unit = n_whole + ts.n_tiles * ts.hs;
+  const int unit = item / per_unit, in_unit = item % per_unit;
+  const bool divided = in_unit >= n_whole;
+  const int tile = divided ? n_whole + (in_unit - n_whole) / ts.hs : in_unit;
+  const int share = divided ? (in_unit - n_whole) % ts.hs : 0;
+  const int n_heads = divided ? p.G / ts.hs : p.G;   // query heads of the group handled here, from head0 on
+  const int head0 = share * n_heads;
+  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
   int si = 0;
   while (si + 1 < seg.n && tile >= seg.tile_begin[si + 1]) ++si;
   const int c0 = seg.col_begin[si] + (tile - seg.tile_begin[si]) * Cfg::kCols;
@@ -99,7 +121,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   // query-row stages that see at least one cache row of this workgroup; iteration = (head of the group, stage)
   const int rt0 = max(0, c0 - p.q_start) / BQ;
   const int n_rt = (p.C + BQ - 1) / BQ - rt0;
-  const int n_iter = n_rt * p.G;
+  const int n_iter = n_rt * n_heads;
   struct Pos { int hg, r0; };   // head within the group, first chunk-local row of the stage
   auto advance = [&](Pos x) {
     x.r0 += BQ;
@@ -204,7 +226,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 + lane * 16) = pack8(s, 1);
   };
 
-  Pos cur{0, rt0 * BQ};
+  Pos cur{head0, rt0 * BQ};
   Pos nxt = advance(cur);
   copy_stage(cur, 0);
   fetch_stat(cur);
@@ -340,6 +362,18 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     slot = slot1;
   }
 
+  if (divided) {
+    // a share of the heads: plain stores of the unweighted sums, all 32 rows (the merge drops rows past the tile's end)
+    float* pb = ts.part + ((((int64_t)unit * ts.n_tiles + (tile - n_whole)) * ts.hs + share) * 2 + role) *
+                              (int64_t)(Cfg::kCols * 128) + (cb * 32) * 128 + l32;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float* pr = pb + (8 * (r >> 2) + 4 * g + (r & 3)) * 128;
+#pragma unroll
+      for (int db = 0; db < 4; ++db) pr[32 * db] = acc[db][r];
+    }
+    return;
+  }
   // exclusive read-modify-write of this workgroup's gK/gV rows: role A adds dV, role B adds s * dK
   float* gbase = (role == 0 ? p.gv : p.gk) + b * p.gs[0] + kvh * p.gs[1];
   const float wf = role == 0 ? weight : weight * p.scale;
@@ -364,19 +398,63 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   }
 }
 
+// gK/gV of the divided column tiles: g += w * (sum of the head shares, in head order).  One thread per four
+// consecutive elements of a (tile, dV or dK) pair.
+template <int COLS>
+__global__ __launch_bounds__(256) void dkdv_tail_merge_kernel(AttnParams p, SegTable seg, TailSplit ts, int n_units) {
+  constexpr int kQuads = COLS * 128 / 4;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int quad = (int)(gid % kQuads);
+  const int64_t pair = gid / kQuads;
+  const int role = (int)(pair & 1);
+  const int64_t st = pair >> 1;                       // divided tile, counted over all units
+  if (st >= (int64_t)n_units * ts.n_tiles) return;
+  const int unit = (int)(st / ts.n_tiles);
+  const int n_ctiles = seg.tile_begin[seg.n];
+  const int tile = n_ctiles - ts.n_tiles + (int)(st % ts.n_tiles);
+  int si = 0;
+  while (si + 1 < seg.n && tile >= seg.tile_begin[si + 1]) ++si;
+  const int row = seg.col_begin[si] + (tile - seg.tile_begin[si]) * COLS + quad / 32;
+  if (row >= seg.col_end[si]) return;
+  const float wf = role == 0 ? seg.weight[si] : seg.weight[si] * p.scale;
+  const float* src = ts.part + (st * ts.hs * 2 + role) * (int64_t)(COLS * 128) + (int64_t)quad * 4;
+  float4 sum = *reinterpret_cast<const float4*>(src);
+  for (int h = 1; h < ts.hs; ++h) {
+    const float4 x = *reinterpret_cast<const float4*>(src + (int64_t)h * 2 * COLS * 128);
+    sum.x += x.x; sum.y += x.y; sum.z += x.z; sum.w += x.w;
+  }
+  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+  float* g = (role == 0 ? p.gv : p.gk) + b * p.gs[0] + kvh * p.gs[1] + (int64_t)row * p.gs[2] + (quad % 32) * 4;
+  float4 old = *reinterpret_cast<float4*>(g);
+  old.x += wf * sum.x; old.y += wf * sum.y; old.z += wf * sum.z; old.w += wf * sum.w;
+  *reinterpret_cast<float4*>(g) = old;
+}
+
 }  // namespace
 
 template <int NCB, int RB>
 int launch_cfg(const AttnParams& p, const SegTable& seg, hipStream_t s) {
   using Cfg = DkdvCfg<NCB, RB>;
-  const int total = seg.tile_begin[seg.n] * p.Hkv * p.B;
+  const int n_units = p.Hkv * p.B, n_ctiles = seg.tile_begin[seg.n];
+  TailSplit ts{0, 1, p.tail_part};
+  const TailPlan tp = tail_plan(n_units, n_ctiles, p.G, p.C);
+  if (p.tail_part && tp.hs > 1) {
+    ts.n_tiles = tp.n_tiles;
+    ts.hs = tp.hs;
+  }
+  const int total = n_units * (n_ctiles - ts.n_tiles + ts.n_tiles * ts.hs);
   auto kern = dkdv_bf16_kernel<NCB, RB>;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                           Cfg::kSmemBytes) != hipSuccess)
     return SECO_ERR_LAUNCH;
   {
-    ProfScope prof(kKernelDkdv, s);
-    hipLaunchKernelGGL(kern, dim3(xcd_grid(total)), dim3(Cfg::kThreads), Cfg::kSmemBytes, s, p, seg, total);
+    ProfScope prof(kKernelDkdv, s);   // the merge of the divided tiles counts as part of the dK/dV pass
+    hipLaunchKernelGGL(kern, dim3(xcd_grid(total)), dim3(Cfg::kThreads), Cfg::kSmemBytes, s, p, seg, ts, total);
+    if (ts.n_tiles > 0) {
+      const int64_t threads = (int64_t)n_units * ts.n_tiles * 2 * (Cfg::kCols * 128 / 4);
+      hipLaunchKernelGGL(dkdv_tail_merge_kernel<Cfg::kCols>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p,
+                         seg, ts, n_units);
+    }
   }
   return launch_status();
 }

@@ -87,6 +87,14 @@ int splits_for(const seco_desc* d) {
   return split_count(pl, d->q_start + d->chunk_len);
 }
 
+// workspace of the dK/dV pass for the column tiles it divides by query head (bf16, grouped heads only)
+size_t tail_part_bytes(const seco_desc* d) {
+  if (d->dtype != SECO_BF16 || d->n_q_heads / d->n_kv_heads < 2) return 0;
+  return (size_t)kTailMaxShares * 2 * kColTileBf16 * 128 * sizeof(float);
+}
+// the partial dQ of the split path and the divided dK/dV tiles are never live together: they share one region
+size_t bwd_part_bytes(const seco_desc* d) { return std::max(split_part_bytes(d), tail_part_bytes(d)); }
+
 int check_fwd_like(const seco_desc* d) {
   int rc = check_desc(d);
   if (rc) return rc;
@@ -130,7 +138,7 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
     }
   }
 
-  if (!ws || ws_bytes < delta_bytes(d) + split_part_bytes(d) || (reinterpret_cast<uintptr_t>(ws) & 255u))
+  if (!ws || ws_bytes < delta_bytes(d) + bwd_part_bytes(d) || (reinterpret_cast<uintptr_t>(ws) & 255u))
     return SECO_ERR_WORKSPACE;
 
   AttnParams p = make_params(d);
@@ -141,6 +149,7 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
   p.n_splits = splits_for(d);
   p.Cpad = (d->chunk_len + 31) / 32 * 32;
   p.part = reinterpret_cast<float*>(static_cast<char*>(ws) + delta_bytes(d));
+  p.tail_part = tail_part_bytes(d) ? p.part : nullptr;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool bf16 = d->dtype == SECO_BF16;
   // delta = rowsum(dO * O): the bf16 dQ kernel computes it in its prologue (and stores it for the dK/dV kernel)
@@ -225,7 +234,7 @@ extern "C" int seco_profile_read(double* total_ms, int64_t* launches) {
 extern "C" size_t seco_workspace_bytes(const seco_desc* desc, int op) {
   if (check_desc(desc) != SECO_OK) return (size_t)-1;
   if (op == SECO_OP_FWD) return split_part_bytes(desc) + split_ml_bytes(desc);
-  if (op == SECO_OP_BWD) return delta_bytes(desc) + split_part_bytes(desc);
+  if (op == SECO_OP_BWD) return delta_bytes(desc) + bwd_part_bytes(desc);
   return (size_t)-1;
 }
 

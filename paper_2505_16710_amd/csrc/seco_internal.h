@@ -21,6 +21,7 @@ struct AttnParams {
   float* gv;
   float* part;       // split path: partial O (forward) or partial dQ (backward), fp32 [n_splits, B, Hq, C, D]
   float* part_ml;    // split path, forward: (reference max in log2 units, sum) per partial row, [n_splits, B, Hq, C, 2]
+  float* tail_part;  // dK/dV pass: sums of the column tiles divided by query head (workspace), or NULL
   int n_splits;      // > 1 selects the split path
   int Cpad;          // C rounded up to 32: rows per head in the packed row space of the split path
   int B, Hq, Hkv, D, C, q_start, G;
@@ -64,6 +65,32 @@ inline int split_count(const SplitPlan& pl, int kv_len) {
 }
 int launch_fwd_merge(const AttnParams& p, hipStream_t s);   // O, LSE from the partials
 int launch_dq_merge(const AttnParams& p, hipStream_t s);    // dQ = scale * sum of the partials, in split order
+
+// Last round of the bf16 dK/dV pass.  One workgroup fills a CU, so n_units * n_ctiles column tiles run in rounds of
+// 256 (the CUs); when the last round would hold at most half of that, the last n_tiles column tiles of every
+// (batch, KV head) are divided among hs workgroups by query head (hs = 1: nothing is divided).  A share keeps
+// at least 512 query rows, and all shares together fit one round.
+constexpr int kTailRound = 256;          // workgroups of one round: the CUs of an MI355X
+constexpr int kTailMaxShares = kTailRound;   // upper bound of n_units * n_tiles * hs
+struct TailPlan {
+  int n_tiles;
+  int hs;
+};
+inline TailPlan tail_plan(int n_units, int n_ctiles, int G, int C) {
+  TailPlan tp{0, 1};
+  const int64_t items = (int64_t)n_units * n_ctiles;
+  const int tail = (int)(items % kTailRound);
+  if (tail == 0 || tail > kTailRound / 2) return tp;
+  const int n_tiles = (tail + n_units - 1) / n_units;
+  for (int hs = 4; hs >= 2; hs >>= 1) {
+    if (G % hs != 0 || (int64_t)n_units * n_tiles * hs > kTailMaxShares) continue;
+    if ((int64_t)C * (G / hs) < 512) continue;
+    tp.n_tiles = n_tiles;
+    tp.hs = hs;
+    break;
+  }
+  return tp;
+}
 
 // fp32 reference-grade kernels (any head_dim that is a multiple of 4, up to 256)
 int launch_fwd_f32(const AttnParams& p, hipStream_t s);

@@ -84,6 +84,27 @@ def test_spaco_parity(dtype, D, N, C, sel, lam):
             assert not got["gk"][:, :, i * C:(i + 1) * C].any() and not got["dq"][:, :, i * C:(i + 1) * C].any()
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,N,C,sel", [
+    (5, 16, 8, 1024, 512, None),         # 40 units: the second call has 320 column tiles, the last 2 of a unit go to 2 workgroups each
+    (1, 8, 2, 2080, 520, None),          # G = 4: every tile divided among 4 workgroups; ragged column tiles
+    (1, 8, 2, 2080, 520, [3, 2, 0]),     # the same with weights (applied when the shares are merged)
+])
+def test_bf16_last_round_divided_by_query_head(B, Hq, Hkv, N, C, sel):
+    """dK/dV pass with a short last round: column tiles shared out by query head and merged in head order."""
+    x = small_layer(21, B, Hq, Hkv, N, 128, "bf16")
+    s = 1 / np.sqrt(128)
+    lam = float(np.float32(4 / 3))
+    kw = {} if sel is None else {"selected": sel, "factor": lam}
+    got = run_layer(x, C, s, "bf16", **kw)
+    if sel is None:
+        ref = A.seco_layer(x["q"], x["k"], x["v"], x["do"], C, s)
+    else:
+        ref = A.spaco_layer(x["q"], x["k"], x["v"], x["do"], C, s, sel, lam)
+    check(got, ref, "bf16", f"divided last round {B,Hq,Hkv,N,C,sel}")
+    again = run_layer(x, C, s, "bf16", **kw)
+    assert np.array_equal(got["gk"], again["gk"]) and np.array_equal(got["gv"], again["gv"])
+
+
 def _one_call(dtype, D, N, C, j, weights=None, seed=40):
     x = small_layer(seed, 1, 4, 2, N, D, dtype)
     q, k, v, do = (to_dev(x[n], dtype) for n in ("q", "k", "v", "do"))
