@@ -24,7 +24,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak (published)
 # HBM bytes per launch (mean over the 16 calls of cfg2) from rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0; the
 # factors come from a streaming kernel of known size in the same runs (profiles/cfg2_hbm_traffic_pmc.txt).
-HBM_TRAFFIC_PER_LAUNCH = {("cfg2", "dkdv"): 221.1e6}
+HBM_TRAFFIC_PER_LAUNCH = {("cfg2", "dkdv"): 254.7e6}
 
 
 def pairs(j, C):
