@@ -31,6 +31,15 @@ Grouped-query attention: query head h reads KV head h // G, G = Hq // Hkv.
 SeCO (Alg. 1, second loop): chunks are back-propagated in reverse order and
 each call adds its dK/dV contribution, for every visible column, into a
 persistent gradient buffer over the whole cache (the paper's m'_i.grad).
+Column-weighted dQ (an extension the paper does not have; Alg. 2 keeps dQ exact):
+dQ is a sum over cache columns of terms that need only that column's K and V rows
+and the row's LSE and delta, so a call may visit a subset of the column chunks and
+weight each visited chunk by the reciprocal of its inclusion probability:
+
+    dQ_w[r,:] = scale * sum_c w[c] dS[r,c] K[c,:]
+
+which is exact for w = 1 and an unbiased estimate of dQ whenever E[w[c]] = 1.
+
 SpaCO (Alg. 2): only the selected chunks are back-propagated; what a call
 deposits on an *earlier* selected chunk is multiplied by the compensation
 factor, what it deposits on its own rows is not, and unselected chunks receive
@@ -47,6 +56,7 @@ import numpy as np
 __all__ = [
     "chunk_attn_fwd",
     "chunk_attn_bwd",
+    "chunk_attn_dq_weighted",
     "seco_layer",
     "spaco_layer",
     "weighted_layer",
@@ -196,6 +206,46 @@ def chunk_attn_bwd(q, k_cache, v_cache, o, lse, d_o, q_start, scale, tier="matmu
                       _as64(d_o), int(q_start), float(scale))
 
 
+def chunk_attn_dq_weighted(q, k_cache, v_cache, o, lse, d_o, q_start, scale, col_weight, tier="matmul"):
+    """dQ of one chunk with a weight per cache column: scale * sum_c col_weight[c] * dS[r,c] * K[c,:]
+    (dS as in chunk_attn_bwd: the exact P, from the exact LSE, and the exact delta).
+
+    col_weight  [q_start + C] non-negative weights, one per visible cache column
+    returns     dQ_w [B, Hq, C, D]
+    """
+    q, k_cache, v_cache, o, lse, d_o = (_as64(x) for x in (q, k_cache, v_cache, o, lse, d_o))
+    q_start, scale = int(q_start), float(scale)
+    B, Hq, Hkv, C, D, G = _check(q, k_cache, v_cache, q_start)
+    L = q_start + C
+    w = _as64(col_weight)
+    if w.shape != (L,):
+        raise ValueError("one weight per visible cache column is needed")
+    dq = np.zeros((B, Hq, C, D))
+    if tier == "loops":
+        for b in range(B):
+            for h in range(Hq):
+                g = h // G
+                for r in range(C):
+                    delta = sum(d_o[b, h, r, d] * o[b, h, r, d] for d in range(D))
+                    for c in range(q_start + r + 1):
+                        s = scale * sum(q[b, h, r, d] * k_cache[b, g, c, d] for d in range(D))
+                        dp = sum(d_o[b, h, r, d] * v_cache[b, g, c, d] for d in range(D))
+                        ds = math.exp(s - lse[b, h, r]) * (dp - delta)
+                        for d in range(D):
+                            dq[b, h, r, d] += scale * w[c] * ds * k_cache[b, g, c, d]
+        return dq
+    vis = _visible(q_start, C, L)
+    for b in range(B):
+        for h in range(Hq):
+            kk = k_cache[b, h // G, :L]
+            vv = v_cache[b, h // G, :L]
+            prob = np.where(vis, np.exp(scale * (q[b, h] @ kk.T) - lse[b, h][:, None]), 0.0)
+            delta = (d_o[b, h] * o[b, h]).sum(axis=1, keepdims=True)
+            ds = prob * (d_o[b, h] @ vv.T - delta)
+            dq[b, h] = scale * ((ds * w[None, :]) @ kk)
+    return dq
+
+
 def _chunks(N, chunk_len):
     """(q_start, length) of every chunk; the last one may be short."""
     return [(s, min(chunk_len, N - s)) for s in range(0, N, chunk_len)]
@@ -279,15 +329,21 @@ def weighted_layer(Q, K, V, dO, chunk_len, scale, calls, tier="matmul"):
 
     Alg. 2 with its single draw is one such policy; so are the two other readings of "a few sampled earlier
     chunks plus the current chunk": one call for the last chunk only, or every chunk back-propagated with its own
-    draw of earlier chunks.  returns dQ, gK, gV.
+    draw of earlier chunks.  A call may carry a third element wq[0..j]: its dQ is then the column-weighted one
+    (chunk_attn_dq_weighted with weight wq[i] on the columns of chunk i).  returns dQ, gK, gV.
     """
     Q, K, V, dO = _as64(Q), _as64(K), _as64(V), _as64(dO)
     chunks = _chunks(Q.shape[2], chunk_len)
     dQ, gK, gV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
-    for j, w in calls:
+    for call in calls:
+        j, w = call[0], call[1]
         s0, c = chunks[j]
         o_j, lse_j = chunk_attn_fwd(Q[:, :, s0:s0 + c], K, V, s0, scale, tier)
         dq, dk, dv = chunk_attn_bwd(Q[:, :, s0:s0 + c], K, V, o_j, lse_j, dO[:, :, s0:s0 + c], s0, scale, tier)
+        if len(call) > 2 and call[2] is not None:      # per-chunk weights of the dQ columns
+            col_w = np.concatenate([np.full(chunks[i][1], float(call[2][i])) for i in range(j + 1)])
+            dq = chunk_attn_dq_weighted(Q[:, :, s0:s0 + c], K, V, o_j, lse_j, dO[:, :, s0:s0 + c], s0, scale,
+                                        col_w, tier)
         dQ[:, :, s0:s0 + c] = dq
         for i in range(j + 1):
             if w[i] != 0:
