@@ -54,7 +54,7 @@ typedef enum seco_status {
   SECO_ERR_DTYPE = -4,       /* dtype is not a seco_dtype */
   SECO_ERR_ALIGN = -5,       /* pointer or stride breaks the 16-byte row alignment */
   SECO_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than seco_workspace_bytes() */
-  SECO_ERR_WEIGHTS = -7,     /* chunk weights: n_chunks/weight_chunk_len do not cover [0, q_start + chunk_len), or a weight is not finite */
+  SECO_ERR_WEIGHTS = -7,     /* chunk weights: n_chunks/weight_chunk_len do not cover [0, q_start + chunk_len), a weight is not finite, or a dQ weight is negative */
   SECO_ERR_RANGE = -8,       /* row range or selection arguments out of range */
   SECO_ERR_LAUNCH = -9,      /* the HIP runtime refused a launch (hipGetLastError) */
   SECO_ERR_TOO_LARGE = -10   /* a size exceeds what the 32-bit tile indexing supports */
@@ -62,7 +62,7 @@ typedef enum seco_status {
 
 typedef enum seco_op {
   SECO_OP_FWD = 0,
-  SECO_OP_BWD = 1            /* seco_chunk_attn_bwd and spaco_chunk_attn_bwd */
+  SECO_OP_BWD = 1            /* seco_chunk_attn_bwd, spaco_chunk_attn_bwd, spaco_chunk_attn_bwd_sparse_dq */
 } seco_op;
 
 /* One chunk call.  kv_len = q_start + chunk_len cache rows are visible. */
@@ -135,6 +135,27 @@ int spaco_chunk_attn_bwd(const seco_desc* desc, const void* q, const void* k_cac
                          void* d_q, float* gk, float* gv,
                          const float* chunk_weight_host, int32_t n_chunks, int32_t weight_chunk_len,
                          void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * spaco_chunk_attn_bwd with a dQ that visits only some cache rows as well.  Not in the paper, whose Alg. 2 keeps
+ * dQ exact over every earlier cache, so that a selected chunk's backward still grows with the context; the
+ * sampling argument of its Sec. 5 (an expected weight of 1 on every term keeps the sum unbiased) applies to the
+ * column sum of dQ too, because the term of a cache row needs only that row of K and V and the query row's LSE
+ * and delta, both exact here:
+ *     dQ = s * sum_i dq_weight_host[i] * sum_{c in chunk i} dS[:, c] K[c, :]
+ * with chunk i = rows [i * weight_chunk_len, (i+1) * weight_chunk_len) as for chunk_weight_host.  Rows of chunks
+ * with dq weight 0 are not read; all weights 1 give the exact dQ (bit-identical to spaco_chunk_attn_bwd).
+ *   dq_weight_host  HOST array of n_chunks finite, non-negative floats, read before the call returns;
+ *                   SECO_ERR_WEIGHTS otherwise.  Its non-zero weights may form at most 48 runs of consecutive
+ *                   chunks with equal weight (SECO_ERR_TOO_LARGE beyond that).
+ * gk/gv, chunk_weight_host and every other argument: as spaco_chunk_attn_bwd.
+ */
+int spaco_chunk_attn_bwd_sparse_dq(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                   const void* o, const float* lse, const void* d_o,
+                                   void* d_q, float* gk, float* gv,
+                                   const float* chunk_weight_host, const float* dq_weight_host,
+                                   int32_t n_chunks, int32_t weight_chunk_len,
+                                   void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
  * Zero rows [row_begin, row_end) of the KV gradient buffers (start of a training iteration;

@@ -52,6 +52,9 @@ def load_library():
     lib.seco_chunk_attn_bwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp, fp, fp, vp, sz, vp]
     lib.spaco_chunk_attn_bwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp, fp, fp,
                                          C.POINTER(C.c_float), i32, i32, vp, sz, vp]
+    lib.spaco_chunk_attn_bwd_sparse_dq.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp, fp, fp, C.POINTER(C.c_float),
+                                                   C.POINTER(C.c_float), i32, i32, vp, sz, vp]
+    lib.spaco_chunk_attn_bwd_sparse_dq.restype = C.c_int
     lib.kvgrad_zero.argtypes = [dp, fp, fp, i64, i64, vp]
     lib.kvgrad_accumulate.argtypes = [dp, fp, fp, fp, fp, C.c_float, i64, i64, vp]
     lib.kv_append.argtypes = [dp, vp, vp, vp, vp, vp]
@@ -181,8 +184,10 @@ def seco_chunk_attn_bwd(q, k_cache, v_cache, o, lse, d_o, gk, gv, q_start, scale
 
 
 def spaco_chunk_attn_bwd(q, k_cache, v_cache, o, lse, d_o, gk, gv, q_start, scale, chunk_weight, weight_chunk_len,
-                         d_q=None, ws=None, stream=None):
-    """As seco_chunk_attn_bwd with per-chunk weights (host sequence of floats) on the dK/dV contributions."""
+                         d_q=None, ws=None, stream=None, dq_weight=None):
+    """As seco_chunk_attn_bwd with per-chunk weights (host sequence of floats) on the dK/dV contributions.
+    With dq_weight (one non-negative float per chunk) the call is spaco_chunk_attn_bwd_sparse_dq: dQ visits only
+    the chunks with a non-zero dq weight and scales their terms by it."""
     import torch
     lib = load_library()
     if d_q is None:
@@ -194,6 +199,15 @@ def spaco_chunk_attn_bwd(q, k_cache, v_cache, o, lse, d_o, gk, gv, q_start, scal
         ws, _ = _workspace(d, SECO_OP_BWD, q)
     n = len(chunk_weight)
     w = (C.c_float * n)(*[float(x) for x in chunk_weight])
+    if dq_weight is not None:
+        if len(dq_weight) != n:
+            raise ValueError("dq_weight and chunk_weight must have one entry per chunk")
+        wq = (C.c_float * n)(*[float(x) for x in dq_weight])
+        _check(lib.spaco_chunk_attn_bwd_sparse_dq(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(o), _ptr(lse),
+                                                  _ptr(d_o), _ptr(d_q), _ptr(gk), _ptr(gv), w, wq, n,
+                                                  int(weight_chunk_len), _ptr(ws), ws.numel() * ws.element_size(),
+                                                  _stream(stream)), "spaco_chunk_attn_bwd_sparse_dq")
+        return d_q
     _check(lib.spaco_chunk_attn_bwd(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(o), _ptr(lse), _ptr(d_o),
                                     _ptr(d_q), _ptr(gk), _ptr(gv), w, n, int(weight_chunk_len), _ptr(ws),
                                     ws.numel() * ws.element_size(), _stream(stream)), "spaco_chunk_attn_bwd")

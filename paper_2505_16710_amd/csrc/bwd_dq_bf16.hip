@@ -10,6 +10,13 @@
 // so that LSE and delta are per-lane scalars and dS^T feeds dQ^T += K^T dS^T from registers;
 // K^T comes from the same K tile through the LDS transpose read.
 //
+// Column-weighted dQ (SPARSE = true): the tiles are taken from a by-value table of runs of cache rows, each with
+// one positive weight w, instead of from all visible rows: dQ = s * sum over the runs of w * dS K.  A tile starts
+// where its run starts (not on a multiple of the tile height), rows past the run's end are masked like rows above
+// the diagonal, and the weight costs nothing per element: P * w = exp2(S - (LSE - log2 w)), one logarithm per
+// tile.  With every chunk sampled with probability pi and weighted 1 / pi this is an unbiased estimate of dQ
+// whose cost does not grow with the number of unvisited rows.
+//
 // Short chunks (SPLIT = true): as in the forward, the rows of the G heads of a KV head are packed into one row
 // space and the visible cache rows of a row tile are divided among n_splits workgroups; each writes its partial
 // dQ (fp32, unscaled) to the workspace and dq_merge_kernel adds the partials in split order.
@@ -22,8 +29,10 @@ namespace {
 constexpr int BM = 128;
 constexpr int BNW = 64;   // cache rows per wavefront and tile
 
-template <int KH, bool SPLIT>
-__global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
+// seg (SPARSE only): runs of cache rows in ascending order, each with a positive weight
+template <int KH, bool SPLIT, bool SPARSE>
+__global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, SegTable seg, int n_mtiles,
+                                                              int total_items) {
   static_assert(!SPLIT || KH == 1, "the split variant uses the 4-wavefront shape");
   constexpr int BN = BNW * KH;
   constexpr int kTileBytes = BN * kRowBytes;
@@ -107,7 +116,23 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
   } else {
     wg_kv_end = p.q_start + min((mt + 1) * BM, p.C);
   }
-  const int n_tiles = (wg_kv_end + BN - 1) / BN;
+  // SPARSE: position in the run table = (run, first cache row of the tile, end of the run clipped to the rows
+  // this workgroup sees); runs that start at or past that limit have no tiles
+  struct Cur { int si, col, end; };
+  auto run_at = [&](int si) { return Cur{si, seg.col_begin[si], min(seg.col_end[si], wg_kv_end)}; };
+  auto advance = [&](Cur x) {
+    x.col += BN;
+    if (x.col >= x.end && x.si + 1 < seg.n) x = run_at(x.si + 1);
+    return x;
+  };
+  int n_tiles = (wg_kv_end + BN - 1) / BN;
+  if constexpr (SPARSE) {
+    n_tiles = 0;
+    for (int si = 0; si < seg.n; ++si) {
+      const int len = min(seg.col_end[si], wg_kv_end) - seg.col_begin[si];
+      if (len > 0) n_tiles += (len + BN - 1) / BN;
+    }
+  }
   const int wave_kv_end = m0 < p.C ? p.q_start + min(m0 + 32, p.C) : 0;
   int n_begin = 0, n_end = n_tiles;            // tiles of this workgroup
   if constexpr (SPLIT) {
@@ -123,10 +148,10 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
 #pragma unroll
   for (int i = 0; i < 4; ++i) lane_off[i] = dma_lane_offset(4 * (wave + 4 * KH * i), p.kvs[2] * 2, lane);
   const uint32_t lds_wave = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + wave * 4 * kRowBytes);
-  auto copy_tile = [&](int n, int buf) {
-    if ((n + 1) * BN <= kv_len) {
-      const __bf16* kt_src = kbase + (int64_t)n * BN * p.kvs[2];
-      const __bf16* vt_src = vbase + (int64_t)n * BN * p.kvs[2];
+  auto copy_tile = [&](int col, int buf) {      // col: first cache row of the tile
+    if (col + BN <= kv_len) {
+      const __bf16* kt_src = kbase + (int64_t)col * p.kvs[2];
+      const __bf16* vt_src = vbase + (int64_t)col * p.kvs[2];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const uint32_t dst = lds_wave + buf * 2 * kTileBytes + i * (16 * KH * kRowBytes);
@@ -139,7 +164,7 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int r = 4 * (wave + 4 * KH * i);
-        const int64_t off = (int64_t)min(n * BN + r + (lane >> 4), kv_len - 1) * p.kvs[2];
+        const int64_t off = (int64_t)min(col + r + (lane >> 4), kv_len - 1) * p.kvs[2];
         dma4rows(kt, r, kbase + off, lane);
         dma4rows(vt, r, vbase + off, lane);
       }
@@ -160,7 +185,13 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
 
-  if (n_begin < n_end) copy_tile(n_begin, 0);
+  Cur cur{0, n_begin * BN, 0};
+  if constexpr (SPARSE) {
+    cur = run_at(0);
+    for (int i = 0; i < n_begin && i < n_tiles; ++i) cur = advance(cur);
+  }
+  Cur nxt = cur;
+  if (n_begin < n_end) copy_tile(cur.col, 0);
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
     settle(qf[t]);
@@ -171,13 +202,19 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
 
   for (int n = n_begin; n < n_end; ++n) {
     const int buf = (n - n_begin) & 1;
-    if (n + 1 < n_end) copy_tile(n + 1, buf ^ 1);
+    if constexpr (SPARSE) {
+      nxt = advance(cur);
+    } else {
+      nxt.col = cur.col + BN;
+    }
+    if (n + 1 < n_end) copy_tile(nxt.col, buf ^ 1);
     lds_char* kt = smem + buf * 2 * kTileBytes + kh * BNW * kRowBytes;
     lds_char* vt = kt + kTileBytes;
+    const float lse_t = SPARSE ? lse_c - __builtin_amdgcn_logf(seg.weight[cur.si]) : lse_c;   // v_log_f32: log2
 #pragma unroll
     for (int kvb = 0; kvb < 2; ++kvb) {
-      const int col0 = n * BN + kh * BNW + kvb * 32;
-      if (col0 < wave_kv_end) {
+      const int col0 = cur.col + kh * BNW + kvb * 32;
+      if (col0 < wave_kv_end && (!SPARSE || col0 < cur.end)) {
         f32x16 s, dp;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
@@ -186,12 +223,14 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
 #pragma unroll
         for (int t = 0; t < 8; ++t) dp = mfma(lds_row8_at(vt + r_off[t], kvb * 32), dof[t], dp);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_c));
-        if (col0 + 31 > p.q_start + m0) {   // block reaches past this wavefront's first row: zero what lies above the diagonal
+        for (int r = 0; r < 16; ++r) s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_t));
+        // block reaches past this wavefront's first row (or past the end of its run): zero what lies above the
+        // diagonal (or belongs to rows outside the run)
+        if (col0 + 31 > p.q_start + m0 || (SPARSE && col0 + 32 > cur.end)) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int kv = col0 + 8 * (r >> 2) + 4 * g + (r & 3);
-            if (kv > qpos) s[r] = 0.f;
+            if (kv > qpos || (SPARSE && kv >= cur.end)) s[r] = 0.f;
           }
         }
 #pragma unroll
@@ -206,6 +245,7 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
     }
     dma_wait_all();
     __syncthreads();
+    cur = nxt;
   }
 
   if (KH == 2) {
@@ -262,31 +302,38 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, int 
   }
 }
 
-template <int KH, bool SPLIT>
-int launch_kh(const AttnParams& p, int n_mtiles, int total, hipStream_t s) {
+template <int KH, bool SPLIT, bool SPARSE>
+int launch_kh(const AttnParams& p, const SegTable& seg, int n_mtiles, int total, hipStream_t s) {
   constexpr int smem = 4 * BNW * KH * kRowBytes;
-  auto kern = dq_bf16_kernel<KH, SPLIT>;
+  auto kern = dq_bf16_kernel<KH, SPLIT, SPARSE>;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
       hipSuccess)
     return SECO_ERR_LAUNCH;
   {
     ProfScope prof(kKernelDq, s);
-    hipLaunchKernelGGL(kern, dim3(xcd_grid(total)), dim3(256 * KH), smem, s, p, n_mtiles, total);
+    hipLaunchKernelGGL(kern, dim3(xcd_grid(total)), dim3(256 * KH), smem, s, p, seg, n_mtiles, total);
   }
   return launch_status();
 }
 
 }  // namespace
 
-int launch_dq_bf16(const AttnParams& p, hipStream_t s) {
+// runs == nullptr: all visible cache rows, weight 1
+int launch_dq_bf16(const AttnParams& p, const SegTable* runs, hipStream_t s) {
+  SegTable none = {};
+  const SegTable& seg = runs ? *runs : none;
   if (p.n_splits > 1) {
     const SplitPlan plan = split_plan(p.B, p.Hkv, p.G, p.C);
-    int rc = launch_kh<1, true>(p, plan.n_mtiles, plan.items * p.n_splits, s);
+    const int total = plan.items * p.n_splits;
+    int rc = runs ? launch_kh<1, true, true>(p, seg, plan.n_mtiles, total, s)
+                  : launch_kh<1, true, false>(p, seg, plan.n_mtiles, total, s);
     return rc ? rc : launch_dq_merge(p, s);
   }
   const int n_mtiles = (p.C + BM - 1) / BM;
   const int total = p.B * p.Hq * n_mtiles;
-  return total < 2 * kNumCUs ? launch_kh<2, false>(p, n_mtiles, total, s) : launch_kh<1, false>(p, n_mtiles, total, s);
+  if (total < 2 * kNumCUs)
+    return runs ? launch_kh<2, false, true>(p, seg, n_mtiles, total, s) : launch_kh<2, false, false>(p, seg, n_mtiles, total, s);
+  return runs ? launch_kh<1, false, true>(p, seg, n_mtiles, total, s) : launch_kh<1, false, false>(p, seg, n_mtiles, total, s);
 }
 
 }  // namespace seco

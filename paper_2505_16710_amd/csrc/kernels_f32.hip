@@ -86,8 +86,9 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_f32_kernel(AttnParams p) {
   if (lane == 0) p.lse[((int64_t)b * p.Hq + h) * p.C + r] = m + __logf(l);
 }
 
-// dQ = s * dS K over all visible columns; wave per query row.
-__global__ __launch_bounds__(kWaves * 64) void dq_f32_kernel(AttnParams p) {
+// dQ = s * sum over the runs of cache rows in `seg` of w * dS K (one run with weight 1 over all visible rows: the
+// exact dQ); wave per query row.
+__global__ __launch_bounds__(kWaves * 64) void dq_f32_kernel(AttnParams p, SegTable seg) {
   __shared__ float qsh[kWaves][kMaxD];
   __shared__ float dosh[kWaves][kMaxD];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -111,22 +112,26 @@ __global__ __launch_bounds__(kWaves * 64) void dq_f32_kernel(AttnParams p) {
   const float lse = p.lse[row], delta = p.delta[row];
   const int last = p.q_start + r;
   float acc[kRegs] = {0.f, 0.f, 0.f, 0.f};
-  for (int c0 = 0; c0 <= last; c0 += 64) {
-    const int c = c0 + lane;
-    float ds = 0.f;
-    if (c <= last) {
-      const float s = p.scale * dot_row(K + (int64_t)c * p.kvs[2], qsh[w], D);
-      const float dp = dot_row(V + (int64_t)c * p.kvs[2], dosh[w], D);
-      ds = __expf(s - lse) * (dp - delta);
-    }
-    const int nc = min(64, last - c0 + 1);
-    for (int cc = 0; cc < nc; ++cc) {
-      const float dsc = __shfl(ds, cc);
-      const float* krow = K + (int64_t)(c0 + cc) * p.kvs[2];
+  for (int si = 0; si < seg.n; ++si) {
+    const int run_last = min(last, seg.col_end[si] - 1);   // last column of the run this row sees
+    const float wt = seg.weight[si];
+    for (int c0 = seg.col_begin[si]; c0 <= run_last; c0 += 64) {
+      const int c = c0 + lane;
+      float ds = 0.f;
+      if (c <= run_last) {
+        const float s = p.scale * dot_row(K + (int64_t)c * p.kvs[2], qsh[w], D);
+        const float dp = dot_row(V + (int64_t)c * p.kvs[2], dosh[w], D);
+        ds = wt * (__expf(s - lse) * (dp - delta));
+      }
+      const int nc = min(64, run_last - c0 + 1);
+      for (int cc = 0; cc < nc; ++cc) {
+        const float dsc = __shfl(ds, cc);
+        const float* krow = K + (int64_t)(c0 + cc) * p.kvs[2];
 #pragma unroll
-      for (int i = 0; i < kRegs; ++i) {
-        const int d = lane + 64 * i;
-        if (d < D) acc[i] += dsc * krow[d];
+        for (int i = 0; i < kRegs; ++i) {
+          const int d = lane + 64 * i;
+          if (d < D) acc[i] += dsc * krow[d];
+        }
       }
     }
   }
@@ -215,11 +220,15 @@ int launch_fwd_f32(const AttnParams& p, hipStream_t s) {
   return launch_status();
 }
 
-int launch_dq_f32(const AttnParams& p, hipStream_t s) {
+int launch_dq_f32(const AttnParams& p, const SegTable* dq_runs, hipStream_t s) {
+  SegTable all = {};
+  all.n = 1;
+  all.col_end[0] = p.q_start + p.C;
+  all.weight[0] = 1.f;
   dim3 grid((p.C + kWaves - 1) / kWaves, p.Hq, p.B);
   {
     ProfScope prof(kKernelDq, s);
-    hipLaunchKernelGGL(dq_f32_kernel, grid, dim3(kWaves * 64), 0, s, p);
+    hipLaunchKernelGGL(dq_f32_kernel, grid, dim3(kWaves * 64), 0, s, p, dq_runs ? *dq_runs : all);
   }
   return launch_status();
 }

@@ -106,8 +106,8 @@ int check_fwd_like(const seco_desc* d) {
 }
 
 int backward(const seco_desc* d, const void* q, const void* k, const void* v, const void* o, const float* lse,
-             const void* d_o, void* d_q, float* gk, float* gv, const float* w, int32_t n_chunks, int32_t wlen, void* ws,
-             size_t ws_bytes, void* stream) {
+             const void* d_o, void* d_q, float* gk, float* gv, const float* w, const float* wq, int32_t n_chunks,
+             int32_t wlen, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_fwd_like(d);
   if (rc) return rc;
   if ((rc = check_strides(d->g_stride, 4, d->head_dim))) return rc;
@@ -138,6 +138,32 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
     }
   }
 
+  // Runs of the column-weighted dQ: the same construction over wq, which must be non-negative.  A single run
+  // of weight 1 over every visible row is the exact dQ and takes the dense kernel.
+  SegTable dq_runs;
+  std::memset(&dq_runs, 0, sizeof(dq_runs));
+  bool sparse_dq = false;
+  if (wq) {
+    for (int i = 0; i < n_chunks; ++i)
+      if (!std::isfinite(wq[i]) || wq[i] < 0.f) return SECO_ERR_WEIGHTS;
+    int n = 0;
+    for (int i = 0; i < n_chunks; ++i) {
+      if (wq[i] == 0.f) continue;
+      const int b = (int)((int64_t)i * wlen), e = (int)std::min<int64_t>((int64_t)(i + 1) * wlen, kv_len);
+      if (n > 0 && dq_runs.col_end[n - 1] == b && dq_runs.weight[n - 1] == wq[i]) {
+        dq_runs.col_end[n - 1] = e;
+      } else {
+        if (n == kMaxSegments) return SECO_ERR_TOO_LARGE;
+        dq_runs.col_begin[n] = b;
+        dq_runs.col_end[n] = e;
+        dq_runs.weight[n] = wq[i];
+        ++n;
+      }
+    }
+    dq_runs.n = n;
+    sparse_dq = !(n == 1 && dq_runs.col_begin[0] == 0 && dq_runs.col_end[0] == kv_len && dq_runs.weight[0] == 1.f);
+  }
+
   if (!ws || ws_bytes < delta_bytes(d) + bwd_part_bytes(d) || (reinterpret_cast<uintptr_t>(ws) & 255u))
     return SECO_ERR_WORKSPACE;
 
@@ -154,7 +180,8 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
   const bool bf16 = d->dtype == SECO_BF16;
   // delta = rowsum(dO * O): the bf16 dQ kernel computes it in its prologue (and stores it for the dK/dV kernel)
   if (!bf16 && (rc = launch_delta(p, d->dtype, s))) return rc;
-  if ((rc = bf16 ? launch_dq_bf16(p, s) : launch_dq_f32(p, s))) return rc;
+  const SegTable* runs_arg = sparse_dq ? &dq_runs : nullptr;
+  if ((rc = bf16 ? launch_dq_bf16(p, runs_arg, s) : launch_dq_f32(p, runs_arg, s))) return rc;
   for (size_t first = 0; first < runs.size(); first += kMaxSegments) {
     SegTable seg;
     std::memset(&seg, 0, sizeof(seg));
@@ -262,7 +289,7 @@ extern "C" int seco_chunk_attn_fwd(const seco_desc* desc, const void* q, const v
 extern "C" int seco_chunk_attn_bwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
                                    const void* o, const float* lse, const void* d_o, void* d_q, float* gk, float* gv,
                                    void* ws, size_t ws_bytes, void* hip_stream) {
-  return backward(desc, q, k_cache, v_cache, o, lse, d_o, d_q, gk, gv, nullptr, 0, 0, ws, ws_bytes, hip_stream);
+  return backward(desc, q, k_cache, v_cache, o, lse, d_o, d_q, gk, gv, nullptr, nullptr, 0, 0, ws, ws_bytes, hip_stream);
 }
 
 extern "C" int spaco_chunk_attn_bwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
@@ -270,8 +297,18 @@ extern "C" int spaco_chunk_attn_bwd(const seco_desc* desc, const void* q, const 
                                     const float* chunk_weight_host, int32_t n_chunks, int32_t weight_chunk_len, void* ws,
                                     size_t ws_bytes, void* hip_stream) {
   if (!chunk_weight_host) return SECO_ERR_NULL;
-  return backward(desc, q, k_cache, v_cache, o, lse, d_o, d_q, gk, gv, chunk_weight_host, n_chunks, weight_chunk_len, ws,
-                  ws_bytes, hip_stream);
+  return backward(desc, q, k_cache, v_cache, o, lse, d_o, d_q, gk, gv, chunk_weight_host, nullptr, n_chunks,
+                  weight_chunk_len, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int spaco_chunk_attn_bwd_sparse_dq(const seco_desc* desc, const void* q, const void* k_cache,
+                                              const void* v_cache, const void* o, const float* lse, const void* d_o,
+                                              void* d_q, float* gk, float* gv, const float* chunk_weight_host,
+                                              const float* dq_weight_host, int32_t n_chunks, int32_t weight_chunk_len,
+                                              void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!chunk_weight_host || !dq_weight_host) return SECO_ERR_NULL;
+  return backward(desc, q, k_cache, v_cache, o, lse, d_o, d_q, gk, gv, chunk_weight_host, dq_weight_host, n_chunks,
+                  weight_chunk_len, ws, ws_bytes, hip_stream);
 }
 
 namespace {

@@ -94,13 +94,15 @@ inline TailPlan tail_plan(int n_units, int n_ctiles, int G, int C) {
 
 // fp32 reference-grade kernels (any head_dim that is a multiple of 4, up to 256)
 int launch_fwd_f32(const AttnParams& p, hipStream_t s);
-int launch_dq_f32(const AttnParams& p, hipStream_t s);
+int launch_dq_f32(const AttnParams& p, const SegTable* dq_runs, hipStream_t s);   // dq_runs as in launch_dq_bf16
 int launch_dkdv_f32(const AttnParams& p, const SegTable& seg, hipStream_t s);
 constexpr int kColTileF32 = 4;     // columns per workgroup in launch_dkdv_f32
 
 // bf16 matrix-core kernels (head_dim 128)
 int launch_fwd_bf16(const AttnParams& p, hipStream_t s);
-int launch_dq_bf16(const AttnParams& p, hipStream_t s);
+// dq_runs: NULL for all visible cache rows with weight 1; else runs of cache rows (ascending, disjoint), each with
+// a positive weight (tile_begin is not used)
+int launch_dq_bf16(const AttnParams& p, const SegTable* dq_runs, hipStream_t s);
 int launch_dkdv_bf16(const AttnParams& p, const SegTable& seg, hipStream_t s);
 #ifndef SECO_DKDV_COLS
 #define SECO_DKDV_COLS 128

@@ -87,6 +87,21 @@ def test_spaco_weight_validation():
     assert lib.spaco_chunk_attn_bwd(C.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
                                     None, 2, 256, C.c_void_p(0x1000), 1 << 30, None) == -1
 
+    # weights of the dQ columns: finite and non-negative, at most 48 runs of equal non-zero weights
+    def sparse(w, wq, n, wlen, dd=d):
+        arr = (C.c_float * n)(*w)
+        arq = (C.c_float * n)(*wq) if wq is not None else None
+        return lib.spaco_chunk_attn_bwd_sparse_dq(C.byref(dd), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                                  arr, arq, n, wlen, None, 0, None)
+    assert sparse([1.0, 1.0], None, 2, 256) == -1
+    assert sparse([1.0, 1.0], [-1.0, 1.0], 2, 256) == -7
+    assert sparse([1.0, 1.0], [float("nan"), 1.0], 2, 256) == -7
+    assert sparse([1.0, 1.0], [1.0, 1.0], 3, 256) == -7              # coverage is checked as for the dK/dV weights
+    assert sparse([1.0, 1.0], [2.0, 1.0], 2, 256) == -6              # valid weights: the next check is the workspace
+    assert sparse([1.0] * 128, [1.0 + (i % 2) for i in range(128)], 128, 4) == -10   # 128 runs
+    assert sparse([1.0] * 128, [float(i % 2) for i in range(128)], 128, 4) == -10    # 64 runs
+    assert sparse([1.0] * 128, [float(i % 4 == 0) for i in range(128)], 128, 4) == -6   # 32 runs fit
+
 
 def test_kvgrad_validation_and_workspace_size():
     lib = seco.load_library()

@@ -538,3 +538,68 @@ def test_per_call_draw_policy_parity():
     dq, gk, gv = A.weighted_layer(x["q"], x["k"], x["v"], x["do"], C, s, calls)
     for n, r in (("dq", dq), ("gk", gk), ("gv", gv)):
         assert max_rel(got[n], r) <= TOL["bf16"][n], n
+
+
+# ---- column-weighted (sparse) dQ ----------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,D,Hq,Hkv,N,C,j,wq", [
+    ("f32", 64, 4, 2, 512, 128, 3, [2.0, 0.0, 1.5, 1.0]),
+    ("bf16", 128, 4, 2, 1024, 256, 3, [2.0, 0.0, 1.5, 1.0]),                       # short-chunk (split) kernel
+    ("bf16", 128, 4, 2, 1280, 160, 7, [0.0, 3.0, 3.0, 0.0, 0.0, 1.25, 0.0, 1.0]),  # runs that start and end inside tiles
+    ("bf16", 128, 4, 2, 1280, 160, 7, [0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 1.0]),   # own chunk only
+    ("bf16", 128, 32, 8, 4096, 1024, 3, [4.0, 0.0, 0.5, 1.0]),                     # 8-wavefront kernel (128-row tiles)
+    ("bf16", 128, 32, 8, 4096, 2048, 1, [0.75, 1.0]),                              # 4-wavefront kernel, 512 workgroups
+    ("bf16", 128, 8, 2, 3000, 1000, 2, [2.0, 0.0, 1.0]),                           # ragged everything, G = 4
+])
+def test_sparse_dq_parity(dtype, D, Hq, Hkv, N, C, j, wq):
+    """spaco_chunk_attn_bwd_sparse_dq against the oracle's column-weighted dQ; gK/gV do not depend on the dQ weights."""
+    x = small_layer(50, 1, Hq, Hkv, N, D, dtype)
+    q, k, v, do = (to_dev(x[n], dtype) for n in ("q", "k", "v", "do"))
+    s = 1 / np.sqrt(D)
+    s0 = j * C
+    c = min(C, N - s0)
+    qc, doc = q[:, :, s0:s0 + c], do[:, :, s0:s0 + c].contiguous()
+    o, lse = seco.seco_chunk_attn_fwd(qc, k, v, s0, s)
+    w = [1.0] * (j + 1)
+    gk, gv = (torch.zeros(k.shape, dtype=torch.float32, device=DEV) for _ in range(2))
+    dq = seco.spaco_chunk_attn_bwd(qc, k, v, o, lse, doc, gk, gv, s0, s, w, C, dq_weight=wq)
+    gk0, gv0 = (torch.zeros(k.shape, dtype=torch.float32, device=DEV) for _ in range(2))
+    dq_dense = seco.spaco_chunk_attn_bwd(qc, k, v, o, lse, doc, gk0, gv0, s0, s, w, C)
+    torch.cuda.synchronize()
+    assert torch.equal(gk, gk0) and torch.equal(gv, gv0)
+    q64, k64, v64, do64 = (x[n].astype(np.float64) for n in ("q", "k", "v", "do"))
+    o_ref, lse_ref = A.chunk_attn_fwd(q64[:, :, s0:s0 + c], k64, v64, s0, s)
+    col_w = np.concatenate([np.full(min(C, s0 + c - i * C), wq[i]) for i in range(j + 1)])
+    ref = A.chunk_attn_dq_weighted(q64[:, :, s0:s0 + c], k64, v64, o_ref, lse_ref, do64[:, :, s0:s0 + c], s0, s, col_w)
+    exact, _, _ = A.chunk_attn_bwd(q64[:, :, s0:s0 + c], k64, v64, o_ref, lse_ref, do64[:, :, s0:s0 + c], s0, s)
+    err = max_rel(to_host(dq), ref)
+    print(f"sparse dq {dtype} {Hq,Hkv,N,C,j}: {err:.2e}; dense {max_rel(to_host(dq_dense), exact):.2e}", flush=True)
+    assert err <= TOL[dtype]["dq"]
+    assert max_rel(ref, exact) > 0.05          # the weights matter in this example
+
+
+@pytest.mark.parametrize("dtype,D,C", [("f32", 64, 128), ("bf16", 128, 256), ("bf16", 128, 1024)])
+def test_sparse_dq_special_cases(dtype, D, C):
+    """All dQ weights 1: bit-identical to the dense call.  All 0: dQ = 0 (and gK/gV as usual).  Two reruns agree bitwise."""
+    Hq, Hkv, j = (32, 8, 2) if C == 1024 else (4, 2, 3)
+    N = (j + 1) * C
+    x = small_layer(51, 1, Hq, Hkv, N, D, dtype)
+    q, k, v, do = (to_dev(x[n], dtype) for n in ("q", "k", "v", "do"))
+    s = 1 / np.sqrt(D)
+    qc, doc = q[:, :, j * C:], do[:, :, j * C:].contiguous()
+    o, lse = seco.seco_chunk_attn_fwd(qc, k, v, j * C, s)
+    w = [2.0] * j + [1.0]
+
+    def call(wq):
+        gk, gv = (torch.zeros(k.shape, dtype=torch.float32, device=DEV) for _ in range(2))
+        dq = seco.spaco_chunk_attn_bwd(qc, k, v, o, lse, doc, gk, gv, j * C, s, w, C, dq_weight=wq)
+        torch.cuda.synchronize()
+        return dq, gk, gv
+    dense = call(None)
+    ones = call([1.0] * (j + 1))
+    zeros = call([0.0] * (j + 1))
+    some = call([0.0, 3.0] + [1.0] * (j - 1))
+    again = call([0.0, 3.0] + [1.0] * (j - 1))
+    assert all(torch.equal(a, b) for a, b in zip(dense, ones))
+    assert not zeros[0].any() and torch.equal(zeros[1], dense[1]) and torch.equal(zeros[2], dense[2])
+    assert all(torch.equal(a, b) for a, b in zip(some, again))
+    assert not torch.equal(some[0], dense[0])
