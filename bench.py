@@ -103,13 +103,14 @@ def main():
             seco.seco_chunk_attn_fwd(self.rows(self.q, j), self.kc, self.vc, j * self.C, scale,
                                      o=self.rows(self.o, j), lse=self.lse[j], ws=self.ws_fwd)
 
-        def bwd(self, j, weights=None):
+        def bwd(self, j, weights=None, dq_weights=None):
             args = (self.rows(self.q, j), self.kc, self.vc, self.rows(self.o, j), self.lse[j], self.rows(self.do, j),
                     self.gk, self.gv, j * self.C, scale)
             if weights is None:
                 seco.seco_chunk_attn_bwd(*args, d_q=self.rows(self.dq, j), ws=self.ws)
             else:
-                seco.spaco_chunk_attn_bwd(*args, weights, self.C, d_q=self.rows(self.dq, j), ws=self.ws)
+                seco.spaco_chunk_attn_bwd(*args, weights, self.C, d_q=self.rows(self.dq, j), ws=self.ws,
+                                          dq_weight=dq_weights)
 
     L = Layer(N, C)
 
@@ -297,6 +298,16 @@ def main():
             for j in sel:
                 Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam))
 
+        # dQ visits the selected chunks only as well (given chunk j is drawn, an earlier chunk is drawn with probability
+        # (t-1)/(k-1): weight (k-1)/(t-1) keeps the estimate of dQ unbiased); whole-sequence stage 1, kept outputs
+        lam_q = (kx - 1) / (tx - 1) if tx > 1 else 0.0
+
+        def spaco_layer_sparse_dq():
+            prefill_stage1()
+            seco.kvgrad_zero(Lx.gk, Lx.gv)
+            for j in sel:
+                Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam), seco.spaco_chunk_weights(sel, j, lam_q))
+
         def spaco_percall_layer():      # every chunk back-propagated, each call with its own draw of t earlier chunks
             for j in range(kx):
                 Lx.fwd(j)
@@ -315,6 +326,7 @@ def main():
                          (f"spaco_t{tx}_kept_outputs", spaco_layer_kept),
                          ("seco_prefill_kept_outputs", seco_layer_prefill_kept),
                          (f"spaco_t{tx}_prefill_kept_outputs", spaco_layer_prefill_kept),
+                         (f"spaco_t{tx}_prefill_kept_outputs_sparse_dq", spaco_layer_sparse_dq),
                          (f"spaco_percall_t{tx}", spaco_percall_layer),
                          (f"spaco_last_call_t{tx}", spaco_last_call)):
             fn()
