@@ -149,6 +149,8 @@ int spaco_chunk_attn_bwd(const seco_desc* desc, const void* q, const void* k_cac
  *                   SECO_ERR_WEIGHTS otherwise.  Its non-zero weights may form at most 48 runs of consecutive
  *                   chunks with equal weight (SECO_ERR_TOO_LARGE beyond that).
  * gk/gv, chunk_weight_host and every other argument: as spaco_chunk_attn_bwd.
+ * In a model with several attention layers the dQ weights of a chunk's call must be drawn independently per layer
+ * for the estimate to stay unbiased (a path that stays inside the chunk meets the same cache rows in every layer).
  */
 int spaco_chunk_attn_bwd_sparse_dq(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
                                    const void* o, const float* lse, const void* d_o,
