@@ -107,7 +107,8 @@ int seco_chunk_attn_fwd(const seco_desc* desc, const void* q, const void* k_cach
  * for every visible cache row c.  gk/gv are accumulated into, never overwritten; rows at or
  * beyond q_start + C are not touched.  o, lse are the outputs of seco_chunk_attn_fwd for the
  * same desc; d_o has o's layout.
- * ws: seco_workspace_bytes(desc, SECO_OP_BWD) bytes, 256-byte aligned: delta, plus one region shared by the
+ * ws: seco_workspace_bytes(desc, SECO_OP_BWD) bytes, 256-byte aligned: one fp32 value per query row (delta; bf16:
+ *     two, delta and the log-sum-exp in the form the dK/dV kernel consumes), plus one region shared by the
  *     partial dQ of the short-chunk path described at seco_chunk_attn_fwd and, for bf16 with grouped heads, the
  *     sums of the cache-row tiles whose query heads the dK/dV pass shares out among several workgroups when its
  *     last round of workgroups would be less than half full (at most 32 MiB; merged in head order, so gk/gv

@@ -16,7 +16,7 @@
 // wavefronts share a SIMD.  Role A runs one row tile ahead of role B, so the P hand-over
 // costs no extra barrier: one barrier per 32-row tile.
 //
-// Q, dO, LSE and delta of one stage of query rows stream through a three-deep ring of swizzled LDS
+// Q, dO, -LSE and -delta of one stage of query rows stream through a three-deep ring of swizzled LDS
 // stages (A reads Q of stage i+1 while B reads Q and dO of stage i and stage i+2 is landing);
 // Q and dO are copied global -> LDS directly (no staging registers), issued two stages ahead.
 // S and dP are computed in the "row = query" orientation, so P and dS sit in the C layout
@@ -163,19 +163,31 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       }
     }
   };
-  // -LSE (in log2 units) and -delta of the stage go through a register: threads 0 .. 2*BQ-1
-  float stat = 0.f;
-  auto fetch_stat = [&](Pos x) {
-    if (tid < 2 * BQ) {
-      const int rr = x.r0 + (tid % BQ);
-      const int64_t idx = stat_base + (int64_t)x.hg * p.C + min(rr, p.C - 1);
-      // stored negated (they start the MFMA chains); rows past the chunk get -LSE = -inf so that their probabilities vanish
-      if (tid < BQ) stat = rr < p.C ? -p.lse[idx] * kLog2e : -INFINITY;
-      else stat = -p.delta[idx];
+  // -LSE (in log2 units) and -delta of the stage's rows, as the dQ kernel left them in the workspace: one
+  // asynchronous 64-lane copy each (wavefronts 0 and 1), straight into the stage's slot.  The last, ragged stage
+  // of a head goes through registers instead: rows past the chunk get -LSE = -inf so that their probabilities vanish.
+  static_assert(BQ == 64, "one 64-lane copy per row statistic");
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const uint32_t lds_stat = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + 2 * kTileBytes + (wave & 1) * BQ * 4);
+  auto copy_stat = [&](Pos x, int slot) {
+    if (x.r0 + BQ <= p.C) {
+      if (wave_u < 2) {
+        const uint64_t a = (uint64_t)(uintptr_t)((wave_u == 0 ? p.nlse2 : p.delta) + stat_base + (int64_t)x.hg * p.C + x.r0);
+        // (wavefront-uniform by construction; the halves go through readfirstlane so that the compiler keeps them
+        // in scalar registers; each half is widened from an unsigned 32-bit value)
+        const uint64_t src = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(a >> 32)) << 32) |
+                             (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)a);
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1"
+                     :
+                     : "v"(lane * 4), "s"(src), "s"(lds_stat + slot * kStageBytes)
+                     : "memory", "m0");
+      }
+    } else if (wave_u < 2) {             // (wavefront-uniform control flow only: the copies above need scalar addresses)
+      const int rr = x.r0 + lane;
+      const float v = (wave_u == 0 ? p.nlse2 : p.delta)[stat_base + (int64_t)x.hg * p.C + min(rr, p.C - 1)];
+      const float stat = wave_u == 0 && rr >= p.C ? -INFINITY : v;
+      *reinterpret_cast<SECO_LDS float*>(smem + slot * kStageBytes + 2 * kTileBytes + (wave_u * BQ + lane) * 4) = stat;
     }
-  };
-  auto stash_stat = [&](int slot) {
-    if (tid < 2 * BQ) *reinterpret_cast<SECO_LDS float*>(smem + slot * kStageBytes + 2 * kTileBytes + tid * 4) = stat;
   };
 
   // lane-dependent parts of the LDS operand addresses (constant for the whole kernel)
@@ -229,12 +241,10 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   Pos cur{head0, rt0 * BQ};
   Pos nxt = advance(cur);
   copy_stage(cur, 0);
-  fetch_stat(cur);
-  stash_stat(0);
+  copy_stat(cur, 0);
   if (n_iter > 1) {
     copy_stage(nxt, 1);
-    fetch_stat(nxt);
-    stash_stat(1);
+    copy_stat(nxt, 1);
   }
 #pragma unroll
   for (int t = 0; t < 8; ++t) settle(frag[t]);
@@ -253,7 +263,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     const int slot2 = slot1 + 1 == kStages ? 0 : slot1 + 1;
     if (it + 2 < n_iter) {
       copy_stage(nxt2, slot2);
-      fetch_stat(nxt2);
+      copy_stat(nxt2, slot2);
     }
     lds_char* qt = smem + slot * kStageBytes;
     lds_char* dot = qt + kTileBytes;
@@ -353,7 +363,6 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
         for (int i = 0; i < 8; ++i) acc[i & 3] = mfma(ds1[i >> 2], x[i], acc[i & 3]);
       }
     }
-    if (it + 2 < n_iter) stash_stat(slot2);
     dma_wait_all();
     __syncthreads();
     cur = nxt;

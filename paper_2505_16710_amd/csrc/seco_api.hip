@@ -61,10 +61,12 @@ AttnParams make_params(const seco_desc* d) {
   return p;
 }
 
-size_t delta_bytes(const seco_desc* d) {
+// one fp32 value per query row: delta; the bf16 path keeps a second array (LSE in the form its dK/dV kernel uses)
+size_t row_stat_bytes(const seco_desc* d) {
   const size_t n = (size_t)d->batch * d->n_q_heads * d->chunk_len * sizeof(float);
   return (n + 255) & ~(size_t)255;
 }
+size_t delta_bytes(const seco_desc* d) { return (d->dtype == SECO_BF16 ? 2 : 1) * row_stat_bytes(d); }
 
 size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
 
@@ -171,6 +173,7 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
   p.q = q; p.k = k; p.v = v; p.o = o; p.d_o = d_o; p.d_q = d_q;
   p.lse = const_cast<float*>(lse);
   p.delta = static_cast<float*>(ws);
+  p.nlse2 = d->dtype == SECO_BF16 ? reinterpret_cast<float*>(static_cast<char*>(ws) + row_stat_bytes(d)) : nullptr;
   p.gk = gk; p.gv = gv;
   p.n_splits = splits_for(d);
   p.Cpad = (d->chunk_len + 31) / 32 * 32;

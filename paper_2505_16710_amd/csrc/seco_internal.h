@@ -16,7 +16,8 @@ struct AttnParams {
   void* o_out;
   void* d_q;
   float* lse;        // [B, Hq, C] contiguous
-  float* delta;      // [B, Hq, C] contiguous (workspace), backward only
+  float* delta;      // [B, Hq, C] contiguous (workspace), backward only: rowsum(dO * O); NEGATED on the bf16 path
+  float* nlse2;      // bf16 backward: -LSE * log2(e), [B, Hq, C] (workspace), written by the dQ kernel for the dK/dV kernel
   float* gk;
   float* gv;
   float* part;       // split path: partial O (forward) or partial dQ (backward), fp32 [n_splits, B, Hq, C, D]

@@ -112,20 +112,21 @@ def test_kvgrad_validation_and_workspace_size():
     assert lib.kvgrad_accumulate(C.byref(d), FAKE, None, None, None, 1.0, 0, 4, None) == -1
     assert lib.kvgrad_accumulate(C.byref(d), FAKE, None, FAKE, None, 1.0, 0, 4, None) == -8   # dst aliases src
     assert lib.kvgrad_zero(C.byref(d), None, None, 0, 4, None) == 0                           # nothing to do
-    # long chunks (enough row tiles to fill the GPU): no forward workspace; the backward takes delta plus the sums
+    # long chunks (enough row tiles to fill the GPU): no forward workspace; the backward takes two values per query
+    # row (delta and the log-sum-exp in the form the dK/dV kernel starts from; fp32: delta only) plus the sums
     # of the column tiles that the dK/dV pass divides by query head (at most 256 shares of 2 x 128 x 128 floats)
     big = desc(n_q_heads=32, n_kv_heads=8, chunk_len=1024)
     assert seco.seco_workspace_bytes(big, B.SECO_OP_FWD) == 0
-    assert seco.seco_workspace_bytes(big, B.SECO_OP_BWD) == 1 * 32 * 1024 * 4 + 256 * 2 * 128 * 128 * 4
+    assert seco.seco_workspace_bytes(big, B.SECO_OP_BWD) == 2 * 32 * 1024 * 4 + 256 * 2 * 128 * 128 * 4
     # without grouped heads nothing is divided: delta only
     mha = desc(n_q_heads=8, n_kv_heads=8, chunk_len=4096)
-    assert seco.seco_workspace_bytes(mha, B.SECO_OP_BWD) == 1 * 8 * 4096 * 4
+    assert seco.seco_workspace_bytes(mha, B.SECO_OP_BWD) == 2 * 8 * 4096 * 4
     # fp32 never uses the split path
     assert seco.seco_workspace_bytes(desc(dtype=B.SECO_F32), B.SECO_OP_FWD) == 0
     # short chunk: 2 KV heads x 4 packed row tiles = 8 work items -> up to 64 splits of fp32 partials
     rows = 1 * 4 * 256
     assert seco.seco_workspace_bytes(d, B.SECO_OP_FWD) == 64 * rows * 128 * 4 + 64 * rows * 2 * 4
-    assert seco.seco_workspace_bytes(d, B.SECO_OP_BWD) == rows * 4 + 64 * rows * 128 * 4
+    assert seco.seco_workspace_bytes(d, B.SECO_OP_BWD) == 2 * rows * 4 + 64 * rows * 128 * 4
     assert bwd(d, ws_bytes=rows * 4) == -6            # delta alone is no longer enough for this shape
     assert seco.seco_workspace_bytes(desc(dtype=B.SECO_F32, chunk_len=3), B.SECO_OP_BWD) == 256   # rounded up to 256
     assert "head_dim" in seco.seco_strerror(-3) and seco.seco_strerror(0) == "ok"
