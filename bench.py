@@ -163,9 +163,11 @@ def main():
             step()
         run_step = graph.replay
 
-    # Per-kernel event times come from the warm-up steps (every launch bracketed); in the timed steps only the
-    # launches of the dominant kernel are bracketed, because a pair of events costs a few microseconds per launch
-    # and would otherwise slow the very region that gives `value` by about 3 %.
+    # Per-kernel event times come from the warm-up steps (every launch bracketed).  In the timed steps only the
+    # launches of the dominant kernel are bracketed, and only in every PROF_EVERY-th step: an event costs a gap of
+    # about 5.6 us before the next kernel (rocprofv3 kernel trace), i.e. 11 us per bracketed launch; around every
+    # launch that would slow the very region that gives `value` by 3 %, around the dominant kernel in every step
+    # by 1.8 %, this way by 0.4 %.
     warm_prof = None
     for i in range(args.warmup):
         if not args.no_profile and i == args.warmup - 1:      # the last warm-up step is the profiled one
@@ -177,17 +179,25 @@ def main():
         warm_prof = seco.seco_profile_read()
         seco.seco_profile_enable(False)
     dom = None
+    prof_kinds = None
+    if not args.no_profile and warm_prof is not None:
+        dom = max(("fwd", "dq", "dkdv"), key=lambda kd: warm_prof[kd][0])
+        prof_kinds = [dom]
+    PROF_EVERY = 5
+    n_prof_steps = 0
     if not args.no_profile:
-        if warm_prof is not None:
-            dom = max(("fwd", "dq", "dkdv"), key=lambda kd: warm_prof[kd][0])
-            seco.seco_profile_enable(kinds=[dom])
-        else:
-            seco.seco_profile_enable(True)
+        seco.seco_profile_enable(False)             # also drops any earlier records
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
     marks[0].record()
     for i in range(args.steps):
+        bracket = not args.no_profile and i % PROF_EVERY == 0
+        if bracket:
+            seco.seco_profile_set(prof_kinds)       # host flag only: the records collected so far are kept
+            n_prof_steps += 1
         run_step()
+        if bracket:
+            seco.seco_profile_set([])
         marks[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -214,7 +224,7 @@ def main():
     if prof is not None:
         alg = {"fwd": flops_fwd, "dq": flops_dq, "dkdv": flops_dkdv}
         kern = {}
-        kprof, ksteps = (warm_prof, 1) if warm_prof is not None else (prof, args.steps)
+        kprof, ksteps = (warm_prof, 1) if warm_prof is not None else (prof, n_prof_steps)
         for kind, (ms, n) in kprof.items():
             if n:
                 kern[kind] = {"launches": int(n), "avg_ms": round(ms / n, 5), "total_ms_per_step": round(ms / ksteps, 4)}
@@ -224,7 +234,7 @@ def main():
         if dom is None:
             dom = max(alg, key=lambda kd: prof[kd][0])
         ms, n = prof[dom]
-        achieved = alg[dom] * args.steps / (ms * 1e-3) / 1e12
+        achieved = alg[dom] * n_prof_steps / (ms * 1e-3) / 1e12
         # bf16 kernels are dense MFMA contractions (2500 TFLOP/s); the fp32 parity kernels use the vector ALU only
         # (256 CUs x 128 lanes x 2 FLOP x 2.4 GHz = 157.3 TFLOP/s)
         bf16 = cfg.dtype == "bf16"
@@ -234,7 +244,8 @@ def main():
                            "frac": round(achieved / peak, 4),
                            "traffic": HBM_TRAFFIC_PER_LAUNCH.get((cfg.name, dom)),
                            "avg_launch_ms": round(ms / n, 5), "launches": int(n),
-                           "measured_in": "timed steps (HIP events around every launch of this kernel)"}
+                           "measured_in": f"timed steps (HIP events around every launch of this kernel in {n_prof_steps} "
+                                          f"of the {args.steps} timed steps)"}
         out["kernels"] = kern
 
     def layer_seconds(cx):

@@ -259,6 +259,8 @@ int seco_profile_enable(int on);                    /* all kinds on / off; forge
 int seco_profile_enable_kinds(uint32_t kind_mask);  /* bit k set: time kernels of kind k only (events cost a few
                                                        microseconds per launch, so a benchmark brackets only what
                                                        it reports) */
+int seco_profile_set_kinds(uint32_t kind_mask);     /* the same mask, but the events recorded so far are kept: lets a
+                                                       benchmark bracket only some of its steps */
 int seco_profile_read(double* total_ms_host, int64_t* launches_host);
 
 /* Workspace bytes an entry point needs for this desc (0 if none; (size_t)-1 on an invalid desc). */

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     seco_chunk_attn_fwd,
     seco_profile_enable,
     seco_profile_read,
+    seco_profile_set,
     seco_strerror,
     seco_workspace_bytes,
     spaco_chunk_attn_bwd,

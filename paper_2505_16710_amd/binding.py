@@ -75,6 +75,8 @@ def load_library():
     lib.seco_profile_enable.argtypes = [C.c_int]
     lib.seco_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.seco_profile_enable_kinds.argtypes = [C.c_uint32]
+    lib.seco_profile_set_kinds.argtypes = [C.c_uint32]
+    lib.seco_profile_set_kinds.restype = C.c_int
     lib.seco_profile_enable.restype = lib.seco_profile_read.restype = lib.seco_profile_enable_kinds.restype = C.c_int
     for name in ("seco_chunk_attn_fwd", "seco_chunk_attn_bwd", "spaco_chunk_attn_bwd", "kvgrad_zero",
                  "kvgrad_accumulate", "spaco_select_chunks", "spaco_chunk_weights"):
@@ -332,6 +334,14 @@ def seco_profile_enable(on=True, kinds=None):
         _check(load_library().seco_profile_enable_kinds(mask), "seco_profile_enable_kinds")
     else:
         _check(load_library().seco_profile_enable(1 if on else 0), "seco_profile_enable")
+
+
+def seco_profile_set(kinds=None):
+    """Change which kinds are timed (None: all, []: none) without dropping what has been recorded."""
+    mask = 0
+    for k in (PROFILE_KINDS if kinds is None else kinds):
+        mask |= 1 << PROFILE_KINDS.index(k)
+    _check(load_library().seco_profile_set_kinds(mask), "seco_profile_set_kinds")
 
 
 def seco_profile_read():

@@ -239,6 +239,11 @@ extern "C" int seco_profile_enable_kinds(uint32_t kind_mask) {
   return SECO_OK;
 }
 
+extern "C" int seco_profile_set_kinds(uint32_t kind_mask) {
+  g_prof_mask = kind_mask & ((1u << SECO_PROFILE_KINDS) - 1u);
+  return SECO_OK;
+}
+
 extern "C" int seco_profile_enable(int on) { return seco_profile_enable_kinds(on ? ~0u : 0u); }
 
 extern "C" int seco_profile_read(double* total_ms, int64_t* launches) {
