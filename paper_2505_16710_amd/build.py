@@ -22,6 +22,7 @@ SOURCES = [
     "elementwise.hip",
     "kernels_f32.hip",
     "fwd_bf16.hip",
+    "fwd4_bf16.hip",
     "bwd_dq_bf16.hip",
     "bwd_dkdv_bf16.hip",
 ]

@@ -4,28 +4,21 @@
 //
 // Decomposition.  A workgroup owns 128 query rows of one head; a wavefront owns 32 of them and
 // keeps Q^T fragments, the running max / sum and the O^T accumulator (128 x 32, fp32) in
-// registers.  K and V tiles stream through a double-buffered, swizzled LDS tile shared by the
-// workgroup; the next tile is copied global -> LDS directly while the current one is consumed.
-// Two shapes of workgroup (template parameter KH):
-//   KH = 1: 4 wavefronts, tiles of 64 cache rows, 64 KiB of LDS -> two workgroups per CU;
-//   KH = 2: 8 wavefronts, tiles of 128 cache rows; wavefront (rb, kh) handles row block rb and
-//           the kh-th 64-row half of every tile, and the two partial (max, sum, O) of a row
-//           block are merged through LDS at the end.  One such workgroup fills a CU with two
-//           wavefronts per SIMD, which is what short chunks need (a 1024-row chunk of a
-//           32-head layer has only 256 row tiles for 256 CUs).
+// registers.  K and V tiles stream through swizzled LDS tiles shared by the workgroup, copied
+// global -> LDS directly ahead of their use.  Two shapes of workgroup:
+//   4 wavefronts (fwd4_bf16.hip): tiles of 64 cache rows, 80 KiB of LDS -> two workgroups per CU; used when a
+//       call has at least two row tiles per CU, and by the split path of short chunks;
+//   8 wavefronts (this file): tiles of 128 cache rows in two buffers of a K and a V tile; wavefront (rb, kh)
+//       handles row block rb and the kh-th 64-row half of every tile, and the two partial (max, sum, O) of a
+//       row block are merged through LDS at the end.  One such workgroup fills a CU with two wavefronts per
+//       SIMD, which is what calls with few row tiles need (a 1024-row chunk of a 32-head layer has only 256
+//       row tiles for 256 CUs).
 //
 // The score tile is computed transposed, S^T = K Q^T, so that a lane owns one query row
 // (C layout: lane = column): row max / row sum are in-lane reductions plus one exchange with
 // lane^32, the rescale of O^T is a per-lane scalar, and P^T feeds the second product
 // O^T += V^T P^T straight from registers.  V^T comes from the row-major V tile through the
 // LDS transpose read.
-//
-// Short chunks (SPLIT = true).  With chunks of 32 .. 512 rows (the sizes of the paper's chunk-size study,
-// Sec. 6.3) a call has far fewer row tiles than the GPU has CUs and every tile would stream the whole cache
-// alone.  The split variant therefore (a) packs the rows of the G query heads that share a KV head into one row
-// space of G * roundup(C, 32) rows, so that a workgroup's K/V tiles serve several heads, and (b) divides the
-// visible cache rows of a row tile among n_splits workgroups; each writes its un-normalised partial O with its
-// reference maximum and sum (fp32) to the workspace, and fwd_merge_kernel combines the partials in split order.
 #include "mfma_tiles.h"
 #include "seco_internal.h"
 
@@ -36,9 +29,9 @@ constexpr int BM = 128;  // query rows per workgroup
 constexpr int BNW = 64;  // cache rows per wavefront and tile
 constexpr float kBig = 1099511627776.f;   // 2^40: a tile's exponentials may sum to this before the reference moves
 
-template <int KH, bool SPLIT>
-__global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
-  static_assert(!SPLIT || KH == 1, "the split variant uses the 4-wavefront shape");
+// 8-wavefront shape (see the head of the file)
+__global__ __launch_bounds__(512, 2) void fwd8_bf16_kernel(AttnParams p, int n_mtiles, int total_items) {
+  constexpr int KH = 2;
   constexpr int BN = BNW * KH;                 // cache rows per tile
   constexpr int kTileBytes = BN * kRowBytes;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];   // 4 * kTileBytes: [buf][K|V]
@@ -49,34 +42,14 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int rb = wave & 3, kh = wave >> 2;
-  int b, kvh, h, mt, m0, sp = 0;              // m0: first chunk-local row of this wavefront
-  if constexpr (SPLIT) {
-    // item -> (batch, kv head, row tile of the packed row space, split)
-    sp = item % p.n_splits;
-    int rest = item / p.n_splits;
-    mt = n_mtiles - 1 - rest % n_mtiles;
-    rest /= n_mtiles;
-    kvh = rest % p.Hkv;
-    b = rest / p.Hkv;
-    const int v0 = mt * BM + rb * 32;          // packed row: head v0 / Cpad of the group, row v0 % Cpad
-    int hg = v0 / p.Cpad;
-    m0 = v0 - hg * p.Cpad;
-    if (hg >= p.G) {                           // past the last head of the group: idle wavefront (m0 >= C)
-      hg = p.G - 1;
-      m0 = p.Cpad;
-    }
-    h = kvh * p.G + hg;
-  } else {
-    // item -> (batch, kv head, row tile (heavy first), head within the group)
-    const int hg = item % p.G;
-    int rest = item / p.G;
-    mt = n_mtiles - 1 - rest % n_mtiles;
-    rest /= n_mtiles;
-    kvh = rest % p.Hkv;
-    b = rest / p.Hkv;
-    h = kvh * p.G + hg;
-    m0 = mt * BM + rb * 32;
-  }
+  // item -> (batch, kv head, row tile (heavy first), head within the group)
+  const int hg = item % p.G;
+  int rest = item / p.G;
+  const int mt = n_mtiles - 1 - rest % n_mtiles;
+  rest /= n_mtiles;
+  const int kvh = rest % p.Hkv, b = rest / p.Hkv;
+  const int h = kvh * p.G + hg;
+  const int m0 = mt * BM + rb * 32;          // first chunk-local row of this wavefront
 
   const int kv_len = p.q_start + p.C;
   const int row = m0 + l32;                    // this lane's row
@@ -89,35 +62,10 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
   const __bf16* kbase = static_cast<const __bf16*>(p.k) + b * p.kvs[0] + kvh * p.kvs[1];
   const __bf16* vbase = static_cast<const __bf16*>(p.v) + b * p.kvs[0] + kvh * p.kvs[1];
 
-  int wg_kv_end;                               // columns any row of the workgroup sees
-  if constexpr (SPLIT) {
-    int rows_end = 0;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int v = mt * BM + r * 32, hh = v / p.Cpad, mm = v - hh * p.Cpad;
-      if (hh < p.G && mm < p.C) rows_end = max(rows_end, min(mm + 32, p.C));
-    }
-    wg_kv_end = rows_end ? p.q_start + rows_end : 0;
-  } else {
-    wg_kv_end = p.q_start + min((mt + 1) * BM, p.C);
-  }
+  const int wg_kv_end = p.q_start + min((mt + 1) * BM, p.C);   // columns any row of the workgroup sees
   const int n_tiles = (wg_kv_end + BN - 1) / BN;
   const int wave_kv_end = m0 < p.C ? p.q_start + min(m0 + 32, p.C) : 0;  // columns this wavefront sees
-  int n_begin = 0, n_end = n_tiles;            // tiles of this workgroup
-  [[maybe_unused]] int64_t part_row = 0;       // row of the partial-result arrays
-  if constexpr (SPLIT) {
-    const int per = (n_tiles + p.n_splits - 1) / p.n_splits;
-    n_begin = sp * per;
-    n_end = min(n_tiles, n_begin + per);
-    part_row = (int64_t)sp * p.B * p.Hq * p.C + ((int64_t)b * p.Hq + h) * p.C + row;
-    if (n_begin >= n_end) {                    // nothing to do for this split: an empty partial (max = -inf)
-      if (row < p.C && g == 0) {
-        p.part_ml[2 * part_row] = -INFINITY;
-        p.part_ml[2 * part_row + 1] = 0.f;
-      }
-      return;
-    }
-  }
+  const int n_begin = 0, n_end = n_tiles;      // tiles of this workgroup
 
   // asynchronous global -> LDS copy of one K and one V tile: each wavefront copies 4 groups of 4 rows of each.
   // The per-lane byte offsets inside a tile never change; a tile that lies entirely inside the cache is copied
@@ -255,7 +203,7 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
   }
 
   float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (KH == 2) {
+  {
     // merge the two column halves of each row block: kh = 1 publishes (m, l, O), kh = 0 combines
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     lds_char* slot = smem + rb * (17 * 1024);            // 16 KiB of O + 512 B of (m, l) per row block
@@ -288,26 +236,6 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
       }
   }
 
-  if constexpr (SPLIT) {
-    // un-normalised partial O (relative to the reference maximum m_run), fp32, plus (m_run, sum)
-    if (row < p.C) {
-      typedef float f32x4 __attribute__((ext_vector_type(4)));
-      float* po = p.part + part_row * kHeadDim;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const f32x4 v = {o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]};
-          *reinterpret_cast<f32x4*>(po + 32 * db + 8 * r4 + 4 * g) = v;
-        }
-      if (g == 0) {
-        p.part_ml[2 * part_row] = m_run;
-        p.part_ml[2 * part_row + 1] = l_tot;
-      }
-    }
-    return;
-  }
-
   if (row < p.C) {
     const float inv = 1.f / l_tot;
     __bf16* optr = static_cast<__bf16*>(p.o_out) + b * p.os[0] + h * p.os[1] + (int64_t)row * p.os[2];
@@ -324,16 +252,14 @@ __global__ __launch_bounds__(256 * KH, 2) void fwd_bf16_kernel(AttnParams p, int
   }
 }
 
-template <int KH, bool SPLIT>
-int launch_kh(const AttnParams& p, int n_mtiles, int total, hipStream_t s) {
-  constexpr int smem = 4 * BNW * KH * kRowBytes;
-  auto kern = fwd_bf16_kernel<KH, SPLIT>;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
-      hipSuccess)
+int launch_fwd8(const AttnParams& p, int n_mtiles, int total, hipStream_t s) {
+  constexpr int smem = 4 * BNW * 2 * kRowBytes;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(fwd8_bf16_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          smem) != hipSuccess)
     return SECO_ERR_LAUNCH;
   {
     ProfScope prof(kKernelFwd, s);
-    hipLaunchKernelGGL(kern, dim3(xcd_grid(total)), dim3(256 * KH), smem, s, p, n_mtiles, total);
+    hipLaunchKernelGGL(fwd8_bf16_kernel, dim3(xcd_grid(total)), dim3(512), smem, s, p, n_mtiles, total);
   }
   return launch_status();
 }
@@ -343,13 +269,13 @@ int launch_kh(const AttnParams& p, int n_mtiles, int total, hipStream_t s) {
 int launch_fwd_bf16(const AttnParams& p, hipStream_t s) {
   if (p.n_splits > 1) {
     const SplitPlan plan = split_plan(p.B, p.Hkv, p.G, p.C);
-    int rc = launch_kh<1, true>(p, plan.n_mtiles, plan.items * p.n_splits, s);
+    int rc = launch_fwd4_bf16(p, true, plan.n_mtiles, plan.items * p.n_splits, s);
     return rc ? rc : launch_fwd_merge(p, s);
   }
   const int n_mtiles = (p.C + BM - 1) / BM;
   const int total = p.B * p.Hq * n_mtiles;
   // fewer row tiles than two per CU: use the 8-wavefront shape so that every SIMD still has two wavefronts
-  return total < 2 * kNumCUs ? launch_kh<2, false>(p, n_mtiles, total, s) : launch_kh<1, false>(p, n_mtiles, total, s);
+  return total < 2 * kNumCUs ? launch_fwd8(p, n_mtiles, total, s) : launch_fwd4_bf16(p, false, n_mtiles, total, s);
 }
 
 }  // namespace seco
