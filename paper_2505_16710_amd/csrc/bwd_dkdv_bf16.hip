@@ -14,7 +14,7 @@
 // Each of the four products is computed exactly once, and a wavefront holds one 32x128 fp32
 // accumulator plus one operand fragment set instead of two of each, which is what lets two
 // wavefronts share a SIMD.  Role A runs one row tile ahead of role B, so the P hand-over
-// costs no extra barrier: one barrier per 32-row tile.
+// costs no extra barrier: one barrier per 64-row stage.
 //
 // Q, dO, -LSE and -delta of one stage of query rows stream through a three-deep ring of swizzled LDS
 // stages (A reads Q of stage i+1 while B reads Q and dO of stage i and stage i+2 is landing);
