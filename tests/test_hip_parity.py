@@ -603,3 +603,33 @@ def test_sparse_dq_special_cases(dtype, D, C):
     assert not zeros[0].any() and torch.equal(zeros[1], dense[1]) and torch.equal(zeros[2], dense[2])
     assert all(torch.equal(a, b) for a, b in zip(some, again))
     assert not torch.equal(some[0], dense[0])
+
+
+def test_sparse_dq_many_runs_and_extreme_weights():
+    """Dozens of runs of one isolated chunk each (the table holds 48), with weights from 1e-3 to 1e3 (the kernel
+    folds a weight into the exponent as log2 w): short-chunk kernel with 32-row chunks, and the 8-wavefront kernel."""
+    for Hq, Hkv, C, wlen, n_chunks in ((4, 2, 32, 32, 96), (32, 8, 1024, 64, 48)):
+        N = wlen * n_chunks
+        j_rows = N - C                                   # the call is for the last C rows
+        x = small_layer(52, 1, Hq, Hkv, N, 128, "bf16")
+        q, k, v, do = (to_dev(x[n], "bf16") for n in ("q", "k", "v", "do"))
+        s = 1 / np.sqrt(128)
+        qc, doc = q[:, :, j_rows:], do[:, :, j_rows:].contiguous()
+        o, lse = seco.seco_chunk_attn_fwd(qc, k, v, j_rows, s)
+        rng = np.random.default_rng(3)
+        wq = np.zeros(n_chunks, dtype=np.float32)
+        picked = np.sort(rng.choice(n_chunks - C // wlen, size=47 if n_chunks == 96 else 20, replace=False))
+        picked = picked[np.concatenate([[True], np.diff(picked) > 1])]          # isolated chunks: one run each
+        wq[picked] = np.float32(10.0) ** rng.uniform(-3, 3, size=len(picked)).astype(np.float32)
+        wq[n_chunks - C // wlen:] = 1.0                                          # the call's own rows
+        gk, gv = (torch.zeros(k.shape, dtype=torch.float32, device=DEV) for _ in range(2))
+        dq = seco.spaco_chunk_attn_bwd(qc, k, v, o, lse, doc, gk, gv, j_rows, s, [1.0] * n_chunks, wlen,
+                                       dq_weight=wq.tolist())
+        torch.cuda.synchronize()
+        q64, k64, v64, do64 = (x[n].astype(np.float64) for n in ("q", "k", "v", "do"))
+        o_ref, lse_ref = A.chunk_attn_fwd(q64[:, :, j_rows:], k64, v64, j_rows, s)
+        ref = A.chunk_attn_dq_weighted(q64[:, :, j_rows:], k64, v64, o_ref, lse_ref, do64[:, :, j_rows:], j_rows, s,
+                                       np.repeat(wq.astype(np.float64), wlen))
+        err = max_rel(to_host(dq), ref)
+        print(f"sparse dq, {len(picked) + 1} runs, weights {wq[wq > 0].min():.1e} .. {wq.max():.1e}: {err:.2e}", flush=True)
+        assert err <= TOL["bf16"]["dq"]
