@@ -13,6 +13,12 @@ supplies the per-layer derivatives, this file supplies the schedules of the pape
   * `spaco_grads`       - Alg. 2: only the selected chunks are rebuilt, and the gradient handed
     over from m'_i to m_i is multiplied by the compensation factor, so that a chain through p
     caches carries factor^p (Sec. 5, "Compensation Factor" and "Implementation").
+  * `dq_weights` of the last two (not in the paper, which keeps dQ exact): in the attention of
+    layer l of the call for chunk i, the part of dQ that flows through the scores of the columns
+    of chunk c is multiplied by dq_weights(i, l)[c]; dK and dV are untouched.  With weights whose
+    expectation is 1, drawn independently per call and layer, the parameter gradients stay
+    unbiased; one draw shared by the layers of a call does not (a path inside chunk i meets the
+    columns of chunk c once per layer and would carry the square of the weight).
 
 The model is a plain pre-norm decoder: RMSNorm, grouped-query causal attention (no positional
 encoding), RMSNorm, two-matrix MLP with SiLU, tied to nothing, cross-entropy loss summed over
@@ -66,20 +72,30 @@ def _rmsnorm(x, g):
     return x * torch.rsqrt((x * x).mean(dim=-1, keepdim=True) + 1e-6) * g
 
 
-def _attend(q, k_all, v_all, q_start, scale):
-    """q [B,Hq,C,D] against cache rows 0 .. q_start+C-1 ([B,Hkv,L,D]), causal with the diagonal included."""
+def _attend(q, k_all, v_all, q_start, scale, col_w=None):
+    """q [B,Hq,C,D] against cache rows 0 .. q_start+C-1 ([B,Hkv,L,D]), causal with the diagonal included.
+
+    col_w [L] (optional): weight of each cache column on the gradient that reaches q through that column's score.
+    The value of the scores is unchanged: they are written as s*(q' k^T) + s*w*((q - q') k'^T) with q', k' cut
+    off from the graph, so k receives its ordinary gradient and q receives w[c] * s * k[c] per column."""
     G = q.shape[1] // k_all.shape[1]
     C, L = q.shape[2], k_all.shape[2]
-    s = scale * torch.einsum("bhrd,bhcd->bhrc", q, k_all.repeat_interleave(G, 1))
+    k_rep = k_all.repeat_interleave(G, 1)
+    if col_w is None:
+        s = scale * torch.einsum("bhrd,bhcd->bhrc", q, k_rep)
+    else:
+        s = scale * (torch.einsum("bhrd,bhcd->bhrc", q.detach(), k_rep) +
+                     torch.einsum("bhrd,bhcd->bhrc", q - q.detach(), k_rep.detach()) * col_w)
     vis = torch.arange(L)[None, :] <= (q_start + torch.arange(C))[:, None]
     p = torch.softmax(s.masked_fill(~vis, float("-inf")), dim=-1)
     return torch.einsum("bhrc,bhcd->bhrd", p, v_all.repeat_interleave(G, 1))
 
 
-def _chunk_forward(cfg, params, tokens, targets, q_start, caches):
+def _chunk_forward(cfg, params, tokens, targets, q_start, caches, col_w=None):
     """One chunk through all layers (Eq. 1): returns (J_j, [(k_l, v_l)] of this chunk).
 
-    caches[l] = (K_prefix, V_prefix) of the earlier chunks at layer l, [B,Hkv,q_start,D] (may be empty)."""
+    caches[l] = (K_prefix, V_prefix) of the earlier chunks at layer l, [B,Hkv,q_start,D] (may be empty);
+    col_w[l] = per-column weights of layer l's dQ (see _attend), or None."""
     B, C = tokens.shape
     x = params["emb"][tokens]
     new_kv = []
@@ -91,7 +107,7 @@ def _chunk_forward(cfg, params, tokens, targets, q_start, caches):
         new_kv.append((k, v))
         k_all = torch.cat([caches[l][0], k], dim=2)
         v_all = torch.cat([caches[l][1], v], dim=2)
-        o = _attend(q, k_all, v_all, q_start, cfg.scale)
+        o = _attend(q, k_all, v_all, q_start, cfg.scale, None if col_w is None else col_w[l])
         x = x + o.transpose(1, 2).reshape(B, C, -1) @ params[f"l{l}.wo"]
         h = _rmsnorm(x, params[f"l{l}.norm2"])
         x = x + F.silu(h @ params[f"l{l}.w1"]) @ params[f"l{l}.w2"]
@@ -141,16 +157,26 @@ def _stage1(cfg, params, tokens, targets, chunk_len):
     return ckpt, total
 
 
-def _stage2(cfg, params, tokens, targets, chunk_len, ckpt, order, factor):
+def _stage2(cfg, params, tokens, targets, chunk_len, ckpt, order, factor, dq_weights=None):
     """Second loop: for every chunk in `order` (descending) rebuild its graph against the checkpoints,
-    hand factor * m'_i.grad to the recomputed m_i and back-propagate J_i."""
+    hand factor * m'_i.grad to the recomputed m_i and back-propagate J_i.
+    dq_weights(i, l) -> one weight per chunk 0..i for the dQ of layer l in the call of chunk i (or None)."""
     B, N = tokens.shape
     starts = list(range(0, N, chunk_len))
     for i in order:
         s0 = starts[i]
         caches = [(torch.cat([c[l][0] for c in ckpt[:i]], 2), torch.cat([c[l][1] for c in ckpt[:i]], 2)) if i
                   else _empty_caches(cfg, B, params["emb"].dtype)[l] for l in range(cfg.n_layers)]
-        loss, new_kv = _chunk_forward(cfg, params, tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, caches)
+        col_w = None
+        if dq_weights is not None:
+            lens = [min(chunk_len, N - a) for a in starts[:i + 1]]
+            col_w = []
+            for l in range(cfg.n_layers):
+                w = dq_weights(i, l)
+                col_w.append(None if w is None else torch.cat(
+                    [torch.full((n,), float(x), dtype=params["emb"].dtype) for n, x in zip(lens, w)]))
+        loss, new_kv = _chunk_forward(cfg, params, tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, caches,
+                                      col_w)
         roots, grads = [loss], [torch.ones_like(loss)]
         for l, (k, v) in enumerate(new_kv):
             gk, gv = ckpt[i][l][0].grad, ckpt[i][l][1].grad
@@ -160,17 +186,18 @@ def _stage2(cfg, params, tokens, targets, chunk_len, ckpt, order, factor):
         torch.autograd.backward(roots, grads)
 
 
-def seco_grads(cfg, params, tokens, targets, chunk_len):
-    """Alg. 1: exact gradients with one chunk's graph alive at a time."""
+def seco_grads(cfg, params, tokens, targets, chunk_len, dq_weights=None):
+    """Alg. 1: exact gradients with one chunk's graph alive at a time (dq_weights: see the module docstring)."""
     _zero_grads(params)
     ckpt, total = _stage1(cfg, params, tokens, targets, chunk_len)
-    _stage2(cfg, params, tokens, targets, chunk_len, ckpt, range(len(ckpt) - 1, -1, -1), 1.0)
+    _stage2(cfg, params, tokens, targets, chunk_len, ckpt, range(len(ckpt) - 1, -1, -1), 1.0, dq_weights)
     return total, _collect(params)
 
 
-def spaco_grads(cfg, params, tokens, targets, chunk_len, selected, factor):
+def spaco_grads(cfg, params, tokens, targets, chunk_len, selected, factor, dq_weights=None):
     """Alg. 2: back-propagate only the selected chunks, relayed KV gradient scaled by `factor`."""
     _zero_grads(params)
     ckpt, total = _stage1(cfg, params, tokens, targets, chunk_len)
-    _stage2(cfg, params, tokens, targets, chunk_len, ckpt, sorted({int(i) for i in selected}, reverse=True), float(factor))
+    _stage2(cfg, params, tokens, targets, chunk_len, ckpt, sorted({int(i) for i in selected}, reverse=True), float(factor),
+            dq_weights)
     return total, _collect(params)

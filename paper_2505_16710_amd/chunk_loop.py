@@ -40,7 +40,7 @@ class ChunkAttention(torch.autograd.Function):
     """Attention of one chunk against a layer's cache; backward deposits into the layer's KV-gradient buffers."""
 
     @staticmethod
-    def forward(ctx, q, k_new, v_new, state, q_start, scale, weights, weight_chunk_len, keep):
+    def forward(ctx, q, k_new, v_new, state, q_start, scale, weights, weight_chunk_len, keep, dq_weights=None):
         # keep: None = always compute; "store" = stage 1, remember (O, LSE); "reuse" = stage 2, take them back
         # (the rebuilt chunk has the same inputs and the kernels are deterministic, so the values are identical and
         # the cache rows already hold this chunk's K/V)
@@ -60,6 +60,7 @@ class ChunkAttention(torch.autograd.Function):
                 state.kept[q_start] = (o, lse)
         ctx.save_for_backward(q, o, lse)
         ctx.state, ctx.q_start, ctx.scale, ctx.weights, ctx.wlen = state, q_start, scale, weights, weight_chunk_len
+        ctx.dq_weights = dq_weights
         return o
 
     @staticmethod
@@ -67,13 +68,15 @@ class ChunkAttention(torch.autograd.Function):
         q, o, lse = ctx.saved_tensors
         st, s0, C = ctx.state, ctx.q_start, q.shape[2]
         d_o = d_o.contiguous()
-        if ctx.weights is None:
+        if ctx.weights is None and ctx.dq_weights is None:
             d_q = _b.seco_chunk_attn_bwd(q, st.k, st.v, o, lse, d_o, st.gk, st.gv, s0, ctx.scale)
         else:
+            n_chunks = len(ctx.dq_weights) if ctx.weights is None else len(ctx.weights)
+            w = [1.0] * n_chunks if ctx.weights is None else ctx.weights
             d_q = _b.spaco_chunk_attn_bwd(q, st.k, st.v, o, lse, d_o, st.gk, st.gv, s0, ctx.scale,
-                                          ctx.weights, ctx.wlen)
+                                          w, ctx.wlen, dq_weight=ctx.dq_weights)
         d_k, d_v = _b.kvgrad_readout(st.gk, st.gv, s0, C, q.dtype)
-        return d_q, d_k, d_v, None, None, None, None, None, None
+        return d_q, d_k, d_v, None, None, None, None, None, None, None
 
 
 def _rmsnorm(x, g):
@@ -90,7 +93,7 @@ class ChunkedDecoder:
         self.scale = float(head_dim) ** -0.5
         _b.load_library()          # fail here, loudly, if the HIP library has not been built
 
-    def _chunk(self, tokens, targets, q_start, states, weights, wlen, keep=None):
+    def _chunk(self, tokens, targets, q_start, states, weights, wlen, keep=None, dq_weights=None):
         p, B, C = self.p, tokens.shape[0], tokens.shape[1]
         x = p["emb"][tokens]
         for l in range(self.n_layers):
@@ -98,7 +101,8 @@ class ChunkedDecoder:
             q = (h @ p[f"l{l}.wq"]).view(B, C, self.Hq, self.D).transpose(1, 2)
             k = (h @ p[f"l{l}.wk"]).view(B, C, self.Hkv, self.D).transpose(1, 2)
             v = (h @ p[f"l{l}.wv"]).view(B, C, self.Hkv, self.D).transpose(1, 2)
-            o = ChunkAttention.apply(q, k, v, states[l], q_start, self.scale, weights, wlen, keep)
+            o = ChunkAttention.apply(q, k, v, states[l], q_start, self.scale, weights, wlen, keep,
+                                     None if dq_weights is None else dq_weights[l])
             x = x + o.transpose(1, 2).reshape(B, C, self.Hq * self.D) @ p[f"l{l}.wo"]
             h = _rmsnorm(x, p[f"l{l}.norm2"])
             x = x + F.silu(h @ p[f"l{l}.w1"]) @ p[f"l{l}.w2"]
@@ -106,7 +110,7 @@ class ChunkedDecoder:
         return F.cross_entropy(logits.reshape(B * C, -1).float(), targets.reshape(B * C), reduction="sum")
 
     def step(self, tokens, targets, chunk_len, selected=None, factor=1.0, keep_attention_outputs=False,
-             stage1_chunk_len=None):
+             stage1_chunk_len=None, dq_weights=None):
         """One SeCO step (selected is None: Alg. 1) or SpaCO step (Alg. 2, `selected` chunk indices,
         relay factor `factor`).  Returns (sum of the chunk losses from stage 1, {name: gradient}).
 
@@ -117,7 +121,11 @@ class ChunkedDecoder:
         GPU with room for one layer's activations of the whole sequence it can run as a single chunk (a plain
         prefill); together with keep_attention_outputs, stage 2 then launches backward kernels only.  The caches
         and kept outputs are then produced by differently shaped launches, so gradients agree with the chunked
-        stage 1 to rounding, not bit for bit."""
+        stage 1 to rounding, not bit for bit.
+        dq_weights: optional callable (chunk j, layer l) -> one non-negative weight per chunk 0..j (or None): the dQ
+        of that attention call visits only the chunks with a non-zero weight and scales their terms
+        (spaco_chunk_attn_bwd_sparse_dq; not part of the paper).  For unbiased gradients the weights must have
+        expectation 1 and be drawn independently for every layer of a call."""
         p = self.p
         B, N = tokens.shape
         dtype, dev = p["emb"].dtype, p["emb"].device
@@ -140,8 +148,9 @@ class ChunkedDecoder:
         for j in order:                                                 # stage 2: rebuild + back-propagate
             w = None if selected is None else _b.spaco_chunk_weights(order, j, factor)
             s0 = starts[j]
+            wq = None if dq_weights is None else [dq_weights(j, l) for l in range(self.n_layers)]
             loss = self._chunk(tokens[:, s0:s0 + chunk_len], targets[:, s0:s0 + chunk_len], s0, states, w, chunk_len,
-                               "reuse" if keep_attention_outputs else None)
+                               "reuse" if keep_attention_outputs else None, wq)
             loss.backward()
         grads = {n: (t.grad if t.grad is not None else torch.zeros_like(t)) for n, t in p.items()}
         return float(total), grads

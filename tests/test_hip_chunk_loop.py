@@ -109,3 +109,21 @@ def test_whole_sequence_stage1_with_kept_outputs_matches_oracle():
     _, g_ref = om.monolithic_grads(BF16_CFG, p64, tok, tgt)
     _, g = dec.step(tok.to(DEV), tgt.to(DEV), 64, keep_attention_outputs=True, stage1_chunk_len=256)
     _compare(g_ref, g, 6e-2)
+
+
+@pytest.mark.parametrize("dtype,cfg,tol", [(torch.float32, F32_CFG, 5e-4), (torch.bfloat16, BF16_CFG, 6e-2)])
+def test_column_weighted_dq_step_matches_oracle(dtype, cfg, tol):
+    """Alg. 2 with, beyond the paper, a dQ that visits only some chunks, a different weight vector in every layer
+    of every call (fixed here; a training loop would draw them)."""
+    N, C, sel, f = 320, 64, [4, 3, 1, 0], 1.25
+    p64, dec, tok, tgt = _setup(cfg, 13, 1, N, dtype)
+
+    def wq(j, l):
+        g = torch.Generator().manual_seed(1000 * j + l)
+        w = [float(x) * 2.0 for x in (torch.rand(j, generator=g) < 0.5)] + [1.0]
+        return w
+    _, g_ref = om.spaco_grads(cfg, p64, tok, tgt, C, sel, f, dq_weights=wq)
+    _, g = dec.step(tok.to(DEV), tgt.to(DEV), C, selected=sel, factor=f, dq_weights=wq)
+    _compare(g_ref, g, tol)
+    _, g_dense = om.spaco_grads(cfg, p64, tok, tgt, C, sel, f)
+    assert max(float((g_dense[n] - g_ref[n]).abs().max() / g_ref[n].abs().max()) for n in g_ref) > 1e-2

@@ -226,3 +226,68 @@ def test_chain_length_is_bounded_by_the_number_of_layers(n_layers):
     assert top > 1e-6 * _scale_of(gs[1])
     d = diff(d)                                            # order deg+1: must vanish
     assert max(_scale_of(x) for x in d) < 1e-9 * _scale_of(gs[-1])
+
+
+# ---- column-weighted dQ through several layers (an option beyond the paper) ---------------------------------------
+
+def test_attend_with_column_weights_matches_the_attention_oracle():
+    """The model oracle's formulation (scores rewritten so that autograd weights the query gradient per column)
+    against the attention oracle's explicit formula: two independent routes to the same dQ; dK/dV untouched."""
+    import numpy as np
+    from oracle import attention as A
+    g = torch.Generator().manual_seed(5)
+    B, Hq, Hkv, C, L, D, q_start, s = 1, 4, 2, 3, 9, 5, 6, 0.4
+    q = torch.randn(B, Hq, C, D, generator=g, dtype=torch.float64, requires_grad=True)
+    k = torch.randn(B, Hkv, L, D, generator=g, dtype=torch.float64, requires_grad=True)
+    v = torch.randn(B, Hkv, L, D, generator=g, dtype=torch.float64, requires_grad=True)
+    d_o = torch.randn(B, Hq, C, D, generator=g, dtype=torch.float64)
+    w = torch.tensor([0.0, 0.0, 0.0, 2.0, 2.0, 2.0, 1.0, 1.0, 0.5], dtype=torch.float64)
+    o = om._attend(q, k, v, q_start, s, w)
+    o.backward(d_o)
+    o_ref, lse_ref = A.chunk_attn_fwd(q.detach().numpy(), k.detach().numpy(), v.detach().numpy(), q_start, s)
+    assert np.abs(o.detach().numpy() - o_ref).max() < 1e-13
+    dq_ref = A.chunk_attn_dq_weighted(q.detach().numpy(), k.detach().numpy(), v.detach().numpy(), o_ref, lse_ref,
+                                      d_o.numpy(), q_start, s, w.numpy())
+    _, dk_ref, dv_ref = A.chunk_attn_bwd(q.detach().numpy(), k.detach().numpy(), v.detach().numpy(), o_ref, lse_ref,
+                                         d_o.numpy(), q_start, s)
+    assert np.abs(q.grad.numpy() - dq_ref).max() < 1e-12
+    assert np.abs(k.grad.numpy() - dk_ref).max() < 1e-12 and np.abs(v.grad.numpy() - dv_ref).max() < 1e-12
+
+
+def test_column_weighted_dq_needs_an_independent_draw_per_layer():
+    """Every chunk back-propagated (Alg. 1's order), dQ of each call visiting a random subset of the earlier chunks
+    (each with probability p, weight 1/p; own chunk always).  Averaged over every outcome, the parameter gradients
+    equal the exact ones when each layer of a call draws its own subset, and do not when the layers share one draw."""
+    cfg = om.ModelConfig(n_layers=2, d_model=16, n_q_heads=2, n_kv_heads=1, head_dim=8, d_ff=24, vocab=11)
+    params = om.init_params(cfg, seed=41)
+    k, C, p = 3, 2, 0.5
+    tok, tgt = _data(42, 1, k * C, cfg)
+    _, exact = om.seco_grads(cfg, params, tok, tgt, C)
+    _, ones = om.seco_grads(cfg, params, tok, tgt, C, dq_weights=lambda i, l: [1.0] * (i + 1))
+    assert _max_abs_diff(exact, ones) <= 1e-13 * _scale_of(exact)
+
+    def subsets(i):        # weight vectors of call i: every subset of its i earlier chunks, with its probability
+        out = []
+        for bits in itertools.product((0, 1), repeat=i):
+            out.append(([b / p for b in bits] + [1.0], p ** sum(bits) * (1 - p) ** (i - sum(bits))))
+        return out
+
+    calls = range(k)
+    for shared in (False, True):
+        slots = [(i,) if shared else (i, l) for i in calls for l in range(cfg.n_layers)]
+        slots = sorted(set(slots))
+        mean = {n: torch.zeros_like(t) for n, t in exact.items()}
+        for combo in itertools.product(*[subsets(s[0]) for s in slots]):
+            draw = {s: c for s, c in zip(slots, combo)}
+            prob = 1.0
+            for _, pr in combo:
+                prob *= pr
+            pick = (lambda i, l: draw[(i,)][0]) if shared else (lambda i, l: draw[(i, l)][0])
+            _, gr = om.seco_grads(cfg, params, tok, tgt, C, dq_weights=pick)
+            for n in mean:
+                mean[n] += prob * gr[n]
+        err = _max_abs_diff(mean, exact) / _scale_of(exact)
+        if shared:
+            assert err > 1e-3, err          # the square of a weight on paths that meet a chunk's columns in both layers
+        else:
+            assert err < 1e-12, err
