@@ -25,7 +25,7 @@ def chunk_list(N, C):
     return [(s, min(C, N - s)) for s in range(0, N, C)]
 
 
-def run_layer(x, chunk_len, scale, dtype, selected=None, factor=1.0, weights_fn=None):
+def run_layer(x, chunk_len, scale, dtype, selected=None, factor=1.0, weights_fn=None, dq_weights_fn=None):
     """SeCO (selected is None) or SpaCO schedule at one attention layer on the GPU.
 
     x: dict q, k, v, do of fp32 host arrays [B,H,N,D].  Returns dict of fp64 arrays
@@ -55,7 +55,8 @@ def run_layer(x, chunk_len, scale, dtype, selected=None, factor=1.0, weights_fn=
             dqc = seco.seco_chunk_attn_bwd(qc, k, v, oc, lc, doc, gk, gv, s0, scale)
         else:
             w = weights_fn(j) if weights_fn else seco.spaco_chunk_weights(selected, j, factor)
-            dqc = seco.spaco_chunk_attn_bwd(qc, k, v, oc, lc, doc, gk, gv, s0, scale, w, chunk_len)
+            wq = dq_weights_fn(j) if dq_weights_fn else None
+            dqc = seco.spaco_chunk_attn_bwd(qc, k, v, oc, lc, doc, gk, gv, s0, scale, w, chunk_len, dq_weight=wq)
         dq[:, :, s0:s0 + c] = dqc
     torch.cuda.synchronize()
     return {"o": to_host(o), "lse": to_host(lse), "dq": to_host(dq), "gk": to_host(gk), "gv": to_host(gv)}

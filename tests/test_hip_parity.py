@@ -633,3 +633,36 @@ def test_sparse_dq_many_runs_and_extreme_weights():
         err = max_rel(to_host(dq), ref)
         print(f"sparse dq, {len(picked) + 1} runs, weights {wq[wq > 0].min():.1e} .. {wq.max():.1e}: {err:.2e}", flush=True)
         assert err <= TOL["bf16"]["dq"]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_and_weights(seed):
+    """Seeded random small configurations through every entry point of the backward: shapes that are not multiples
+    of any tile, random selections with random dK/dV weights and random dQ weights (zeros included)."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = "f32" if seed % 4 == 3 else "bf16"
+    D = int(rng.choice([16, 40, 64])) if dtype == "f32" else 128
+    Hkv = int(rng.choice([1, 2, 3]))
+    Hq = Hkv * int(rng.choice([1, 2, 4]))
+    B = int(rng.choice([1, 2]))
+    C = int(rng.integers(1, 260 if dtype == "bf16" else 70))
+    k = int(rng.integers(1, 7))
+    N = C * (k - 1) + int(rng.integers(1, C + 1))           # ragged last chunk
+    x = small_layer(2000 + seed, B, Hq, Hkv, N, D, dtype)
+    s = float(rng.uniform(0.5, 1.5)) / np.sqrt(D)
+    sel = sorted({int(i) for i in rng.choice(k, size=int(rng.integers(1, k + 1)), replace=False)}, reverse=True)
+    w_of, wq_of = {}, {}
+    for j in sel:
+        w = np.where(rng.random(j + 1) < 0.6, rng.uniform(0.25, 4.0, j + 1), 0.0).astype(np.float32)
+        w[j] = 1.0
+        wq = np.where(rng.random(j + 1) < 0.6, rng.uniform(0.25, 4.0, j + 1), 0.0).astype(np.float32)
+        w_of[j], wq_of[j] = w, (wq if rng.random() < 0.7 else None)
+    got = run_layer(x, C, s, dtype, selected=sel, weights_fn=lambda j: w_of[j].tolist(),
+                    dq_weights_fn=lambda j: None if wq_of[j] is None else wq_of[j].tolist())
+    dq, gk, gv = A.weighted_layer(x["q"], x["k"], x["v"], x["do"], C, s, [(j, w_of[j], wq_of[j]) for j in sel])
+    o, lse, *_ = A.seco_layer(x["q"], x["k"], x["v"], x["do"], C, s)
+    what = f"random {seed}: {dtype} B{B} Hq{Hq} Hkv{Hkv} D{D} N{N} C{C} sel{sel}"
+    errs = {n: max_rel(got[n], r) for n, r in (("o", o), ("lse", lse), ("dq", dq), ("gk", gk), ("gv", gv))}
+    print(what, {n: f"{e:.1e}" for n, e in errs.items()}, flush=True)
+    for n, e in errs.items():
+        assert np.isfinite(got[n]).all() and e <= TOL[dtype][n], (what, n, e)
