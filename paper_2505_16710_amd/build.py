@@ -23,6 +23,7 @@ SOURCES = [
     "kernels_f32.hip",
     "fwd_bf16.hip",
     "fwd4_bf16.hip",
+    "fwd4_split_bf16.hip",
     "bwd_dq_bf16.hip",
     "bwd_dkdv_bf16.hip",
 ]
@@ -39,7 +40,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "
 SCHED = {"bwd_dq_bf16.hip": "iterative-ilp"}
 SCHED_DEFAULT = "max-memory-clause"
 # the 4-wavefront forward, whose source interleaves two instruction streams by hand, is 2 % faster when the
-# scheduler does not cluster memory operations
+# scheduler does not cluster memory operations (its split instantiation would spill registers with that option)
 PER_FILE = {"fwd4_bf16.hip": ["-mllvm", "-misched-cluster=false"]}
 
 

@@ -103,6 +103,7 @@ constexpr int kColTileF32 = 4;     // columns per workgroup in launch_dkdv_f32
 int launch_fwd_bf16(const AttnParams& p, hipStream_t s);
 // the 4-wavefront forward kernel (its own translation unit); split: the short-chunk variant that writes partials
 int launch_fwd4_bf16(const AttnParams& p, bool split, int n_mtiles, int total, hipStream_t s);
+int launch_fwd4_split_bf16(const AttnParams& p, int n_mtiles, int total, hipStream_t s);
 // dq_runs: NULL for all visible cache rows with weight 1; else runs of cache rows (ascending, disjoint), each with
 // a positive weight (tile_begin is not used)
 int launch_dq_bf16(const AttnParams& p, const SegTable* dq_runs, hipStream_t s);
