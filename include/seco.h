@@ -266,6 +266,18 @@ int seco_profile_read(double* total_ms_host, int64_t* launches_host);
 /* Workspace bytes an entry point needs for this desc (0 if none; (size_t)-1 on an invalid desc). */
 size_t seco_workspace_bytes(const seco_desc* desc, int op);
 
+/*
+ * How the bf16 kernels would be launched for this desc (host arithmetic only, nothing is launched; for tests and
+ * tuning).  n_col_tiles: number of 128-row cache tiles the dK/dV pass of the call covers (rows with non-zero
+ * weight, each run of equal weight rounded up to whole tiles).  plan_host receives four values:
+ *   [0] workgroups that share the cache rows of one row tile in the forward / dQ pass (1: no division)
+ *   [1] row tiles of the forward / dQ pass (work items before that division)
+ *   [2] cache tiles per (batch, KV head), counted from the last, that the dK/dV pass shares out by query head
+ *   [3] workgroups per such tile (1: none); [2] * [3] * batch * n_kv_heads never exceeds 256
+ * Returns SECO_OK, or the status of an invalid desc; SECO_ERR_DTYPE for fp32 (its kernels have one shape).
+ */
+int seco_launch_plan(const seco_desc* desc, int32_t n_col_tiles, int32_t* plan_host);
+
 /* Static English description of a status code. */
 const char* seco_strerror(int status);
 

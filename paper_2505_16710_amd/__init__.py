@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     load_library,
     seco_chunk_attn_bwd,
     seco_chunk_attn_fwd,
+    seco_launch_plan,
     seco_profile_enable,
     seco_profile_read,
     seco_profile_set,

@@ -69,6 +69,8 @@ def load_library():
     lib.spaco_compensation_factor.argtypes = [i32, i32, C.c_float]
     lib.spaco_compensation_factor.restype = C.c_float
     lib.seco_workspace_bytes.argtypes = [dp, C.c_int]
+    lib.seco_launch_plan.argtypes = [dp, i32, C.POINTER(i32)]
+    lib.seco_launch_plan.restype = C.c_int
     lib.seco_workspace_bytes.restype = sz
     lib.seco_strerror.argtypes = [C.c_int]
     lib.seco_strerror.restype = C.c_char_p
@@ -323,6 +325,13 @@ def spaco_chunk_weights(selected, j, factor):
 
 
 PROFILE_KINDS = ("fwd", "delta", "dq", "dkdv", "kvgrad", "merge")
+
+
+def seco_launch_plan(desc, n_col_tiles):
+    """(splits per row tile, row tiles, shared-out cache tiles per (batch, KV head), workgroups per such tile)."""
+    out = (C.c_int32 * 4)()
+    _check(load_library().seco_launch_plan(C.byref(desc), int(n_col_tiles), out), "seco_launch_plan")
+    return tuple(out)
 
 
 def seco_profile_enable(on=True, kinds=None):

@@ -273,6 +273,23 @@ extern "C" size_t seco_workspace_bytes(const seco_desc* desc, int op) {
   return (size_t)-1;
 }
 
+extern "C" int seco_launch_plan(const seco_desc* desc, int32_t n_col_tiles, int32_t* plan_host) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!plan_host) return SECO_ERR_NULL;
+  if (desc->dtype != SECO_BF16) return SECO_ERR_DTYPE;
+  if (n_col_tiles < 0) return SECO_ERR_RANGE;
+  const int G = desc->n_q_heads / desc->n_kv_heads;
+  const SplitPlan pl = split_plan(desc->batch, desc->n_kv_heads, G, desc->chunk_len);
+  const int n_splits = splits_for(desc);
+  plan_host[0] = n_splits;
+  plan_host[1] = n_splits > 1 ? pl.items : desc->batch * desc->n_q_heads * ((desc->chunk_len + 127) / 128);
+  const TailPlan tp = tail_plan(desc->batch * desc->n_kv_heads, n_col_tiles, G, desc->chunk_len);
+  plan_host[2] = tp.hs > 1 ? tp.n_tiles : 0;
+  plan_host[3] = tp.hs;
+  return SECO_OK;
+}
+
 extern "C" int seco_chunk_attn_fwd(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
                                    void* o, float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
   int rc = check_fwd_like(desc);

@@ -221,3 +221,35 @@ def test_percall_weights_match_oracle_bit_exactly():
     lib = seco.load_library()
     assert lib.spaco_percall_weights(0, 0, -1, 4, (C.c_float * 1)()) == -8
     assert lib.spaco_percall_weights(0, 0, 3, 4, None) == -1
+
+
+def test_launch_plan_host_logic():
+    """The host arithmetic that shapes the launches: division of the cache rows among workgroups for short chunks,
+    and the sharing-out of the dK/dV pass's last round by query head."""
+    big = desc(n_q_heads=32, n_kv_heads=8, chunk_len=1024, q_start=0)
+    units, G = 8, 4
+    for n_col_tiles in range(0, 200):
+        splits, row_tiles, n_tiles, hs = seco.seco_launch_plan(big, n_col_tiles)
+        assert (splits, row_tiles) == (1, 256)                       # 256 row tiles: no division of the cache rows
+        tail = units * n_col_tiles % 256
+        if tail == 0 or tail > 128:
+            assert (n_tiles, hs) == (0, 1)
+        else:
+            assert hs in (2, 4) and G % hs == 0 and n_tiles == -(-tail // units) <= n_col_tiles
+            assert units * n_tiles * hs <= 256 and 1024 * (G // hs) >= 512
+            assert hs == 4 or units * n_tiles * 4 > 256               # four ways whenever that fits in one round
+    # the benchmark's calls: 8 (j + 1) cache tiles per (batch, KV head)
+    assert [seco.seco_launch_plan(big, 8 * (j + 1))[2:] for j in range(4)] == [(8, 4), (16, 2), (0, 1), (0, 1)]
+    # short chunks: nothing is shared out (a share must keep 512 query rows), the cache rows are divided instead
+    short = desc(n_q_heads=32, n_kv_heads=8, chunk_len=128, q_start=128 * 100)
+    splits, row_tiles, n_tiles, hs = seco.seco_launch_plan(short, 101)
+    assert row_tiles == 8 * 4 and 2 <= splits <= 64 and (n_tiles, hs) == (0, 1)
+    assert splits * row_tiles <= 640 and (128 * 101 + 63) // 64 // splits >= 4     # about 512 workgroups, >= 4 tiles each
+    assert seco.seco_launch_plan(desc(n_q_heads=32, n_kv_heads=8, chunk_len=128, q_start=0), 1)[0] == 1   # too few rows to divide
+    # no grouped heads: nothing to share out
+    assert seco.seco_launch_plan(desc(n_q_heads=8, n_kv_heads=8, chunk_len=4096, q_start=0), 40)[2:] == (0, 1)
+    lib = seco.load_library()
+    out = (C.c_int32 * 4)()
+    assert lib.seco_launch_plan(C.byref(desc(dtype=B.SECO_F32)), 4, out) == -4
+    assert lib.seco_launch_plan(C.byref(big), -1, out) == -8
+    assert lib.seco_launch_plan(C.byref(big), 4, None) == -1
