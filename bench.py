@@ -8,7 +8,7 @@ per chunk, in the method's order, on one stream.  Inputs are resident in HBM bef
 
 Prints ONE JSON line: whole-job TFLOP/s (algorithmic FLOPs: 4*D per visible (row, col) pair
 forward, 10*D backward), the roofline of the dominant kernel measured with HIP events around
-every launch of the timed region, and the CPU oracle timed on a bounded sample.
+its launches in every fifth step of the timed region, and the CPU oracle timed on a bounded sample.
 """
 import argparse
 import json
