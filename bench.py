@@ -244,6 +244,9 @@ def main():
                            "frac": round(achieved / peak, 4),
                            "traffic": HBM_TRAFFIC_PER_LAUNCH.get((cfg.name, dom)),
                            "avg_launch_ms": round(ms / n, 5), "launches": int(n),
+                           # matrix work the kernel executes per algorithmic FLOP (dK/dV computes S and dP again)
+                           "executed_over_algorithmic": 2.0 if (bf16 and dom == "dkdv") else 1.0,
+                           "executed_frac": round(achieved * (2.0 if (bf16 and dom == "dkdv") else 1.0) / peak, 4),
                            "measured_in": f"timed steps (HIP events around every launch of this kernel in {n_prof_steps} "
                                           f"of the {args.steps} timed steps)"}
         out["kernels"] = kern
