@@ -195,6 +195,29 @@ int kvgrad_readout(const seco_desc* desc, const float* gk, const float* gv, void
                    float scaler, void* hip_stream);
 
 /*
+ * Rotary position embedding fused into the two calls above and available on its own.  Not part of the paper, whose
+ * model code is not shown; the model of its experiments (LLaMA-3) rotates queries and keys before attention, in
+ * the "rotate-half" pairing: the pair (x[i], x[i + D/2]), i < D/2, of the row at sequence position p turns by the
+ * angle p * rope_base^(-2 i / D).  Angles, sines and cosines are computed in fp64, the result is rounded once
+ * (fp64 -> fp32 -> dtype).  head_dim must be a multiple of 8; rope_base must be finite and > 1
+ * (SECO_ERR_RANGE otherwise).
+ *   kv_append_rope       as kv_append, with the keys rotated for their positions q_start + r on the way into the
+ *                        cache (the values are copied); one pass over the data instead of rotate, then copy.
+ *   kvgrad_readout_rope  as kvgrad_readout, with the key gradient turned back:
+ *                        d_k_new = (dtype) R(-theta)(scaler * gk[rows]); d_v_new as in kvgrad_readout.
+ *   rope_rotate          x_out[b, h, r, :] = R(+-theta(pos_start + r)) x_in[b, h, r, :] for [B, n_heads, C, D] tensors
+ *                        with q_stride (in) and o_stride (out), e.g. the chunk's queries (inverse = 0) and dQ
+ *                        (inverse = 1); uses batch, head_dim, chunk_len, dtype of desc and the given n_heads;
+ *                        x_out may be x_in.
+ */
+int kv_append_rope(const seco_desc* desc, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                   float rope_base, void* hip_stream);
+int kvgrad_readout_rope(const seco_desc* desc, const float* gk, const float* gv, void* d_k_new, void* d_v_new,
+                        float scaler, float rope_base, void* hip_stream);
+int rope_rotate(const seco_desc* desc, int32_t n_heads, const void* x_in, void* x_out, int64_t pos_start,
+                float rope_base, int32_t inverse, void* hip_stream);
+
+/*
  * SpaCO chunk selection (Alg. 2: "randomly select t distinct indices"), host only.
  * Deterministic in (seed, step): SplitMix64 stream keyed by (seed, step), unbiased bounded
  * draws by rejection, first t steps of a Fisher-Yates shuffle of 0..k-1, result sorted in

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     kvgrad_zero,
     library_path,
     load_library,
+    rope_rotate,
     seco_chunk_attn_bwd,
     seco_chunk_attn_fwd,
     seco_launch_plan,

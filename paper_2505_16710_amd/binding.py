@@ -60,6 +60,10 @@ def load_library():
     lib.kv_append.argtypes = [dp, vp, vp, vp, vp, vp]
     lib.kvgrad_readout.argtypes = [dp, fp, fp, vp, vp, C.c_float, vp]
     lib.kv_append.restype = lib.kvgrad_readout.restype = C.c_int
+    lib.kv_append_rope.argtypes = [dp, vp, vp, vp, vp, C.c_float, vp]
+    lib.kvgrad_readout_rope.argtypes = [dp, fp, fp, vp, vp, C.c_float, C.c_float, vp]
+    lib.rope_rotate.argtypes = [dp, i32, vp, vp, i64, C.c_float, i32, vp]
+    lib.kv_append_rope.restype = lib.kvgrad_readout_rope.restype = lib.rope_rotate.restype = C.c_int
     lib.spaco_select_chunks.argtypes = [C.c_uint64, C.c_uint64, i32, i32, C.POINTER(i32)]
     lib.spaco_chunk_weights.argtypes = [C.POINTER(i32), i32, i32, C.c_float, C.POINTER(C.c_float)]
     lib.spaco_percall_weights.argtypes = [C.c_uint64, C.c_uint64, i32, i32, C.POINTER(C.c_float)]
@@ -260,17 +264,23 @@ def _rows_desc(new, cache_or_g, row_begin, is_g):
     return d
 
 
-def kv_append(k_new, v_new, k_cache, v_cache, row_begin, stream=None):
-    """Write the chunk's keys / values ([B, Hkv, C, D]) into cache rows [row_begin, row_begin + C)."""
+def kv_append(k_new, v_new, k_cache, v_cache, row_begin, stream=None, rope_base=None):
+    """Write the chunk's keys / values ([B, Hkv, C, D]) into cache rows [row_begin, row_begin + C); with rope_base the
+    keys are rotated for their positions on the way (kv_append_rope)."""
     d = _rows_desc(k_new, k_cache, row_begin, False)
     if v_new.stride() != k_new.stride() or v_cache.stride() != k_cache.stride():
         raise ValueError("k/v must share strides")
+    if rope_base is not None:
+        _check(load_library().kv_append_rope(C.byref(d), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                             float(rope_base), _stream(stream)), "kv_append_rope")
+        return
     _check(load_library().kv_append(C.byref(d), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _stream(stream)),
            "kv_append")
 
 
-def kvgrad_readout(gk, gv, row_begin, n_rows, dtype, scaler=1.0, d_k=None, d_v=None, stream=None):
-    """(d_k, d_v) = scaler * (gk, gv)[rows row_begin .. row_begin + n_rows) in the storage dtype."""
+def kvgrad_readout(gk, gv, row_begin, n_rows, dtype, scaler=1.0, d_k=None, d_v=None, stream=None, rope_base=None):
+    """(d_k, d_v) = scaler * (gk, gv)[rows row_begin .. row_begin + n_rows) in the storage dtype; with rope_base the
+    key part is turned back by the rows' rotary angles (kvgrad_readout_rope)."""
     import torch
     B, H, _, D = gk.shape
     if d_k is None:
@@ -280,9 +290,29 @@ def kvgrad_readout(gk, gv, row_begin, n_rows, dtype, scaler=1.0, d_k=None, d_v=N
     if gv.stride() != gk.stride() or d_v.stride() != d_k.stride():
         raise ValueError("gk/gv and d_k/d_v must share strides")
     d = _rows_desc(d_k, gk, row_begin, True)
+    if rope_base is not None:
+        _check(load_library().kvgrad_readout_rope(C.byref(d), _ptr(gk), _ptr(gv), _ptr(d_k), _ptr(d_v), float(scaler),
+                                                  float(rope_base), _stream(stream)), "kvgrad_readout_rope")
+        return d_k, d_v
     _check(load_library().kvgrad_readout(C.byref(d), _ptr(gk), _ptr(gv), _ptr(d_k), _ptr(d_v), float(scaler),
                                          _stream(stream)), "kvgrad_readout")
     return d_k, d_v
+
+
+def rope_rotate(x, pos_start, rope_base, inverse=False, out=None, stream=None):
+    """Rotary position embedding of x [B, H, C, D] (row r at position pos_start + r), or its inverse / transpose."""
+    import torch
+    if out is None:
+        out = torch.empty_strided(x.size(), x.stride(), dtype=x.dtype, device=x.device)
+    d = SecoDesc()
+    d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = x.shape[0], x.shape[1], x.shape[1], x.shape[3]
+    d.chunk_len, d.q_start, d.softmax_scale = x.shape[2], 0, 1.0
+    d.dtype = SECO_BF16 if x.dtype == torch.bfloat16 else SECO_F32
+    d.q_stride = d.kv_stride = d.g_stride = _strides3(x)
+    d.o_stride = _strides3(out)
+    _check(load_library().rope_rotate(C.byref(d), x.shape[1], _ptr(x), _ptr(out), int(pos_start), float(rope_base),
+                                      1 if inverse else 0, _stream(stream)), "rope_rotate")
+    return out
 
 
 def spaco_select_chunks(seed, step, k, t):

@@ -268,6 +268,68 @@ int launch_readout(void* oa, void* ob, const float* ga, const float* gb, float s
   return launch_status();
 }
 
+// Rotary position embedding of rows: out[b, h, r, :] = R(sign * theta(pos0 + r)) (scale * in[b, h, r, :]), pairs
+// (i, i + D/2), theta_i = pos * base^(-2 i / D).  Work item = 4 consecutive i of one row (both halves); angles and
+// sines in fp64, one rounding of the result.  In / out element types are template parameters so that the same
+// kernel serves the cache append (storage type -> storage type, rows at r0 of the destination), the gradient
+// read-out (fp32 -> storage type, rows at r0 of the source) and the plain rotation.
+template <typename TIn, typename TOut>
+__global__ __launch_bounds__(256) void rope_rows_kernel(TOut* out, const TIn* in, int H, int C,   // (out may be in)
+                                                        int D, int64_t os0, int64_t os1, int64_t os2, int64_t is0,
+                                                        int64_t is1, int64_t is2, int64_t out_r0, int64_t in_r0,
+                                                        int64_t pos0, double log2_base, float sign, float scale,
+                                                        int64_t total) {
+  const int q4 = D / 8;                                   // groups of 4 pairs per row
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int grp = (int)(i % q4);
+    int64_t t = i / q4;
+    const int64_t row = t % C;
+    t /= C;
+    const int64_t h = t % H, b = t / H;
+    const TIn* src = in + b * is0 + h * is1 + (in_r0 + row) * is2 + grp * 4;
+    TOut* dst = out + b * os0 + h * os1 + (out_r0 + row) * os2 + grp * 4;
+    float lo[4], hi[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      lo[j] = (float)src[j] * scale;
+      hi[j] = (float)src[D / 2 + j] * scale;
+    }
+    const double pos = (double)(pos0 + row);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const double theta = pos * exp2(-2.0 * (double)(grp * 4 + j) / (double)D * log2_base);
+      double sn, cs;
+      sincos(theta, &sn, &cs);
+      sn *= (double)sign;
+      const double a = (double)lo[j], c = (double)hi[j];
+      dst[j] = (TOut)(float)(a * cs - c * sn);
+      dst[D / 2 + j] = (TOut)(float)(c * cs + a * sn);
+    }
+  }
+}
+
+int launch_rope_rows(void* out, const void* in, int in_kind, int out_kind, int B, int H, int C, int D,
+                     const int64_t out_s[3], const int64_t in_s[3], int64_t out_r0, int64_t in_r0, int64_t pos0,
+                     float base, bool inverse, float scale, hipStream_t s) {
+  const int64_t total = (int64_t)B * H * C * (D / 8);
+  if (total == 0 || !out) return SECO_OK;
+  const double l2b = log2((double)base);
+  const float sign = inverse ? -1.f : 1.f;
+  {
+    ProfScope prof(kKernelKvgrad, s);
+    const dim3 grid(grid_for(total));
+#define SECO_ROPE_LAUNCH(TI, TO)                                                                                       \
+  hipLaunchKernelGGL((rope_rows_kernel<TI, TO>), grid, dim3(256), 0, s, static_cast<TO*>(out),                         \
+                     static_cast<const TI*>(in), H, C, D, out_s[0], out_s[1], out_s[2], in_s[0], in_s[1], in_s[2],      \
+                     out_r0, in_r0, pos0, l2b, sign, scale, total)
+    if (in_kind == SECO_BF16 && out_kind == SECO_BF16) SECO_ROPE_LAUNCH(__bf16, __bf16);
+    else if (in_kind == SECO_F32 && out_kind == SECO_BF16) SECO_ROPE_LAUNCH(float, __bf16);
+    else SECO_ROPE_LAUNCH(float, float);
+#undef SECO_ROPE_LAUNCH
+  }
+  return launch_status();
+}
+
 int launch_fwd_merge(const AttnParams& p, hipStream_t s) {
   const int64_t threads = (int64_t)p.B * p.Hq * p.C * 32;
   {

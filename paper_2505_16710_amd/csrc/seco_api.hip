@@ -411,3 +411,66 @@ extern "C" int kvgrad_readout(const seco_desc* desc, const float* gk, const floa
   return launch_readout(d_k_new, d_v_new, gk, gv, scaler, bf16, desc->batch, desc->n_kv_heads, desc->chunk_len,
                         desc->head_dim, desc->q_stride, desc->g_stride, desc->q_start, s);
 }
+
+// ---- rotary position embedding fused into append / read-out (not part of the paper; see seco.h) -----------------------
+namespace {
+int check_rope(const seco_desc* d, float base) {
+  if (d->head_dim % 8 != 0) return SECO_ERR_HEAD_DIM;
+  if (!std::isfinite(base) || !(base > 1.f)) return SECO_ERR_RANGE;
+  return SECO_OK;
+}
+}  // namespace
+
+extern "C" int kv_append_rope(const seco_desc* desc, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                              float rope_base, void* hip_stream) {
+  int rc = check_append_like(desc, false);
+  if (rc) return rc;
+  if ((rc = check_rope(desc, rope_base))) return rc;
+  if ((k_new == nullptr) != (k_cache == nullptr) || (v_new == nullptr) != (v_cache == nullptr)) return SECO_ERR_NULL;
+  for (const void* ptr : {k_new, v_new, (const void*)k_cache, (const void*)v_cache})
+    if (ptr && !aligned16(ptr)) return SECO_ERR_ALIGN;
+  const int eb = desc->dtype == SECO_BF16 ? 2 : 4;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (k_new &&
+      (rc = launch_rope_rows(k_cache, k_new, desc->dtype, desc->dtype, desc->batch, desc->n_kv_heads, desc->chunk_len,
+                             desc->head_dim, desc->kv_stride, desc->q_stride, desc->q_start, 0, desc->q_start, rope_base,
+                             false, 1.f, s)))
+    return rc;
+  return launch_rows_copy(v_cache, nullptr, v_new, nullptr, eb, desc->batch, desc->n_kv_heads, desc->chunk_len,
+                          desc->head_dim, desc->kv_stride, desc->q_stride, desc->q_start, s);
+}
+
+extern "C" int kvgrad_readout_rope(const seco_desc* desc, const float* gk, const float* gv, void* d_k_new,
+                                   void* d_v_new, float scaler, float rope_base, void* hip_stream) {
+  int rc = check_append_like(desc, true);
+  if (rc) return rc;
+  if ((rc = check_rope(desc, rope_base))) return rc;
+  if ((gk == nullptr) != (d_k_new == nullptr) || (gv == nullptr) != (d_v_new == nullptr)) return SECO_ERR_NULL;
+  if (!std::isfinite(scaler)) return SECO_ERR_RANGE;
+  for (const void* ptr : {(const void*)gk, (const void*)gv, (const void*)d_k_new, (const void*)d_v_new})
+    if (ptr && !aligned16(ptr)) return SECO_ERR_ALIGN;
+  const bool bf16 = desc->dtype == SECO_BF16;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (gk && (rc = launch_rope_rows(d_k_new, gk, SECO_F32, desc->dtype, desc->batch, desc->n_kv_heads, desc->chunk_len,
+                                   desc->head_dim, desc->q_stride, desc->g_stride, 0, desc->q_start, desc->q_start,
+                                   rope_base, true, scaler, s)))
+    return rc;
+  return launch_readout(d_v_new, nullptr, gv, nullptr, scaler, bf16, desc->batch, desc->n_kv_heads, desc->chunk_len,
+                        desc->head_dim, desc->q_stride, desc->g_stride, desc->q_start, s);
+}
+
+extern "C" int rope_rotate(const seco_desc* desc, int32_t n_heads, const void* x_in, void* x_out, int64_t pos_start,
+                           float rope_base, int32_t inverse, void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  const int eb = desc->dtype == SECO_BF16 ? 2 : 4;
+  if ((rc = check_strides(desc->q_stride, eb, desc->head_dim))) return rc;
+  if ((rc = check_strides(desc->o_stride, eb, desc->head_dim))) return rc;
+  if ((rc = check_rope(desc, rope_base))) return rc;
+  if (!x_in || !x_out) return SECO_ERR_NULL;
+  if (!aligned16(x_in) || !aligned16(x_out)) return SECO_ERR_ALIGN;
+  if (n_heads < 1 || n_heads > 65535 || pos_start < 0 || pos_start > ((int64_t)1 << 40)) return SECO_ERR_RANGE;
+  return launch_rope_rows(x_out, x_in, desc->dtype, desc->dtype, desc->batch, n_heads, desc->chunk_len, desc->head_dim,
+                          desc->o_stride, desc->q_stride, 0, 0, pos_start, rope_base, inverse != 0, 1.f,
+                          static_cast<hipStream_t>(hip_stream));
+}

@@ -130,6 +130,12 @@ int launch_rows_copy(void* da, void* db, const void* sa, const void* sb, int eb,
 int launch_readout(void* oa, void* ob, const float* ga, const float* gb, float scaler, bool bf16, int B, int H, int C,
                    int D, const int64_t out_s[3], const int64_t gs[3], int64_t r0, hipStream_t s);
 
+// out rows [out_r0, out_r0 + C) <- rotary embedding (or its inverse) of scale * in rows [in_r0, in_r0 + C), row r at
+// position pos0 + r; in_kind / out_kind: SECO_F32 or SECO_BF16 (bf16 -> f32 is not needed and not provided)
+int launch_rope_rows(void* out, const void* in, int in_kind, int out_kind, int B, int H, int C, int D,
+                     const int64_t out_s[3], const int64_t in_s[3], int64_t out_r0, int64_t in_r0, int64_t pos0,
+                     float base, bool inverse, float scale, hipStream_t s);
+
 // Optional per-kernel timing (seco_profile_enable): a scope brackets one launch with HIP events
 // on the launch stream.  Disabled by default; then a scope costs one branch.
 enum KernelKind { kKernelFwd = 0, kKernelDelta, kKernelDq, kKernelDkdv, kKernelKvgrad, kKernelMerge, kKernelKinds };

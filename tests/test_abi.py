@@ -253,3 +253,20 @@ def test_launch_plan_host_logic():
     assert lib.seco_launch_plan(C.byref(desc(dtype=B.SECO_F32)), 4, out) == -4
     assert lib.seco_launch_plan(C.byref(big), -1, out) == -8
     assert lib.seco_launch_plan(C.byref(big), 4, None) == -1
+
+
+def test_rope_entry_points_validate_their_arguments():
+    lib = seco.load_library()
+    d = desc()
+    f32 = C.c_float
+    assert lib.kv_append_rope(C.byref(d), FAKE, FAKE, FAKE, FAKE, f32(1.0), None) == -8           # base must be > 1
+    assert lib.kv_append_rope(C.byref(d), FAKE, FAKE, FAKE, FAKE, f32(float("inf")), None) == -8
+    assert lib.kv_append_rope(C.byref(d), FAKE, FAKE, None, FAKE, f32(1e4), None) == -1
+    assert lib.kv_append_rope(C.byref(desc(dtype=B.SECO_F32, head_dim=20)), FAKE, FAKE, FAKE, FAKE, f32(1e4), None) == -3
+    assert lib.kvgrad_readout_rope(C.byref(d), FAKE, FAKE, FAKE, FAKE, f32(float("nan")), f32(1e4), None) == -8
+    assert lib.kvgrad_readout_rope(C.byref(d), FAKE, FAKE, FAKE, FAKE, f32(1.0), f32(0.5), None) == -8
+    assert lib.kvgrad_readout_rope(C.byref(d), FAKE, None, FAKE, FAKE, f32(1.0), f32(1e4), None) == -1
+    assert lib.rope_rotate(C.byref(d), 4, None, FAKE, 0, f32(1e4), 0, None) == -1
+    assert lib.rope_rotate(C.byref(d), 0, FAKE, FAKE, 0, f32(1e4), 0, None) == -8
+    assert lib.rope_rotate(C.byref(d), 4, FAKE, FAKE, -1, f32(1e4), 0, None) == -8
+    assert lib.rope_rotate(C.byref(d), 4, C.c_void_p(0x1004), FAKE, 0, f32(1e4), 0, None) == -5

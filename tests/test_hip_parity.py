@@ -666,3 +666,51 @@ def test_random_shapes_and_weights(seed):
     print(what, {n: f"{e:.1e}" for n, e in errs.items()}, flush=True)
     for n, e in errs.items():
         assert np.isfinite(got[n]).all() and e <= TOL[dtype][n], (what, n, e)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rope_append_readout_and_rotate(dtype):
+    """kv_append_rope / kvgrad_readout_rope / rope_rotate against oracle/relay.py: the kernels compute angles and
+    sines in fp64 and round once, so results agree with the oracle up to the last bit of the storage type (a sine
+    that differs in its last fp64 bit can flip a rounding)."""
+    from oracle import relay as R
+    from workloads import round_to
+    B, H, N, D, C, r0, base = 2, 3, 4200, 128 if dtype == "bf16" else 40, 48, 4096, 500000.0
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -23
+    rng = np.random.default_rng(71)
+    k_new = round_to(rng.standard_normal((B, H, C, D)).astype(np.float32), dtype)
+    v_new = round_to(rng.standard_normal((B, H, C, D)).astype(np.float32), dtype)
+    kc, vc = np.zeros((B, H, N, D), np.float32), np.zeros((B, H, N, D), np.float32)
+    kn_dev = to_dev(k_new.transpose(0, 2, 1, 3).copy(), dtype).transpose(1, 2)      # [B, C, H, D] storage
+    vn_dev = to_dev(v_new.transpose(0, 2, 1, 3).copy(), dtype).transpose(1, 2)
+    kc_dev, vc_dev = to_dev(kc, dtype), to_dev(vc, dtype)
+    seco.kv_append(kn_dev, vn_dev, kc_dev, vc_dev, r0, rope_base=base)
+    rk, rv = R.kv_append_rope(kc, vc, k_new, v_new, r0, base, dtype)
+
+    def close(got, ref, what):
+        got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+        same = np.mean(got == ref)
+        err = np.abs(got - ref).max() / np.abs(ref).max()
+        print(f"{what} {dtype}: {100 * same:.3f} % bit-equal, max rel diff {err:.1e}", flush=True)
+        assert same > 0.995 and err <= ulp, (what, same, err)
+    close(to_host(kc_dev), rk, "append")
+    np.testing.assert_array_equal(to_host(vc_dev), rv.astype(np.float64))
+    # the rotated keys really depend on the position: the same rows appended at another place differ
+    assert np.abs(rk[:, :, r0:r0 + C] - R.kv_append_rope(kc, vc, k_new, v_new, 7, base, dtype)[0][:, :, 7:7 + C]).max() > 0.1
+
+    gk = (rng.standard_normal((B, H, N, D)) * 3).astype(np.float32)
+    gv = (rng.standard_normal((B, H, N, D)) * 3).astype(np.float32)
+    gk_dev, gv_dev = torch.from_numpy(gk).to(DEV), torch.from_numpy(gv).to(DEV)
+    d_k = torch.empty(B, C, H, D, dtype=tdt, device=DEV).transpose(1, 2)          # strided output
+    d_k, d_v = seco.kvgrad_readout(gk_dev, gv_dev, r0, C, tdt, scaler=16 / 3, d_k=d_k, rope_base=base)
+    ref_k, ref_v = R.kvgrad_readout_rope(gk, gv, r0, r0 + C, 16 / 3, base, dtype)
+    close(to_host(d_k), ref_k, "read-out")
+    np.testing.assert_array_equal(to_host(d_v), ref_v.astype(np.float64))
+
+    q = round_to(rng.standard_normal((B, 5, C, D)).astype(np.float32), dtype)
+    q_dev = to_dev(q, dtype)
+    rot = seco.rope_rotate(q_dev, r0, base)
+    close(to_host(rot), R._to_storage(R.rope_rotate(q, r0, base), dtype), "rotate")
+    back = seco.rope_rotate(rot, r0, base, inverse=True, out=rot)                  # in place
+    assert np.abs(to_host(back) - q).max() <= 3 * ulp * np.abs(q).max()
