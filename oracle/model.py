@@ -21,7 +21,7 @@ supplies the per-layer derivatives, this file supplies the schedules of the pape
     columns of chunk c once per layer and would carry the square of the weight).
 
 The model is a plain pre-norm decoder: RMSNorm, grouped-query causal attention (no positional
-encoding), RMSNorm, two-matrix MLP with SiLU, tied to nothing, cross-entropy loss summed over
+encoding, or optionally the rotary embedding of LLaMA: `rope_base`; keys are cached rotated), RMSNorm, two-matrix MLP with SiLU, tied to nothing, cross-entropy loss summed over
 tokens; J_j is the loss of chunk j's tokens.  The chunk-level error components of Eq. 1 add
 up to the sequence loss.
 """
@@ -42,6 +42,7 @@ class ModelConfig:
     head_dim: int = 8
     d_ff: int = 48
     vocab: int = 17
+    rope_base: float = 0.0     # > 1: rotary position embedding of queries and keys with this base; 0: none
 
     @property
     def scale(self):
@@ -70,6 +71,16 @@ def init_params(cfg: ModelConfig, seed: int, dtype=torch.float64):
 
 def _rmsnorm(x, g):
     return x * torch.rsqrt((x * x).mean(dim=-1, keepdim=True) + 1e-6) * g
+
+
+def _rope(x, pos0, base):
+    """Rotary embedding of x [B,H,C,D], row r at position pos0 + r: pair (i, i + D/2) turns by pos * base^(-2i/D)."""
+    C, D = x.shape[2], x.shape[3]
+    inv = torch.pow(torch.tensor(float(base), dtype=torch.float64), -2.0 * torch.arange(D // 2, dtype=torch.float64) / D)
+    th = (pos0 + torch.arange(C, dtype=torch.float64))[:, None] * inv[None, :]
+    cos, sin = torch.cos(th).to(x.dtype), torch.sin(th).to(x.dtype)
+    a, b = x[..., :D // 2], x[..., D // 2:]
+    return torch.cat([a * cos - b * sin, b * cos + a * sin], dim=-1)
 
 
 def _attend(q, k_all, v_all, q_start, scale, col_w=None):
@@ -104,6 +115,8 @@ def _chunk_forward(cfg, params, tokens, targets, q_start, caches, col_w=None):
         q = (h @ params[f"l{l}.wq"]).view(B, C, cfg.n_q_heads, cfg.head_dim).transpose(1, 2)
         k = (h @ params[f"l{l}.wk"]).view(B, C, cfg.n_kv_heads, cfg.head_dim).transpose(1, 2)
         v = (h @ params[f"l{l}.wv"]).view(B, C, cfg.n_kv_heads, cfg.head_dim).transpose(1, 2)
+        if cfg.rope_base > 1.0:
+            q, k = _rope(q, q_start, cfg.rope_base), _rope(k, q_start, cfg.rope_base)
         new_kv.append((k, v))
         k_all = torch.cat([caches[l][0], k], dim=2)
         v_all = torch.cat([caches[l][1], v], dim=2)

@@ -40,7 +40,8 @@ class ChunkAttention(torch.autograd.Function):
     """Attention of one chunk against a layer's cache; backward deposits into the layer's KV-gradient buffers."""
 
     @staticmethod
-    def forward(ctx, q, k_new, v_new, state, q_start, scale, weights, weight_chunk_len, keep, dq_weights=None):
+    def forward(ctx, q, k_new, v_new, state, q_start, scale, weights, weight_chunk_len, keep, dq_weights=None,
+                rope_base=None):
         # keep: None = always compute; "store" = stage 1, remember (O, LSE); "reuse" = stage 2, take them back
         # (the rebuilt chunk has the same inputs and the kernels are deterministic, so the values are identical and
         # the cache rows already hold this chunk's K/V)
@@ -53,14 +54,14 @@ class ChunkAttention(torch.autograd.Function):
             else:
                 o, lse = o_all[:, :, a:b].contiguous(), lse_all[:, :, a:b].contiguous()
         else:
-            _b.kv_append(k_new, v_new, state.k, state.v, q_start)
+            _b.kv_append(k_new, v_new, state.k, state.v, q_start, rope_base=rope_base)   # keys are cached rotated
             o, lse = _b.seco_chunk_attn_fwd(q, state.k, state.v, q_start, scale,
                                             o=torch.empty(q.shape, dtype=q.dtype, device=q.device))
             if keep == "store":
                 state.kept[q_start] = (o, lse)
         ctx.save_for_backward(q, o, lse)
         ctx.state, ctx.q_start, ctx.scale, ctx.weights, ctx.wlen = state, q_start, scale, weights, weight_chunk_len
-        ctx.dq_weights = dq_weights
+        ctx.dq_weights, ctx.rope_base = dq_weights, rope_base
         return o
 
     @staticmethod
@@ -75,8 +76,21 @@ class ChunkAttention(torch.autograd.Function):
             w = [1.0] * n_chunks if ctx.weights is None else ctx.weights
             d_q = _b.spaco_chunk_attn_bwd(q, st.k, st.v, o, lse, d_o, st.gk, st.gv, s0, ctx.scale,
                                           w, ctx.wlen, dq_weight=ctx.dq_weights)
-        d_k, d_v = _b.kvgrad_readout(st.gk, st.gv, s0, C, q.dtype)
-        return d_q, d_k, d_v, None, None, None, None, None, None, None
+        d_k, d_v = _b.kvgrad_readout(st.gk, st.gv, s0, C, q.dtype, rope_base=ctx.rope_base)
+        return d_q, d_k, d_v, None, None, None, None, None, None, None, None
+
+
+class Rope(torch.autograd.Function):
+    """Rotary position embedding of the chunk's queries (rope_rotate); the gradient is turned back."""
+
+    @staticmethod
+    def forward(ctx, x, pos_start, base):
+        ctx.pos_start, ctx.base = pos_start, base
+        return _b.rope_rotate(x.contiguous(), pos_start, base)
+
+    @staticmethod
+    def backward(ctx, d_out):
+        return _b.rope_rotate(d_out.contiguous(), ctx.pos_start, ctx.base, inverse=True), None, None
 
 
 def _rmsnorm(x, g):
@@ -87,8 +101,9 @@ def _rmsnorm(x, g):
 class ChunkedDecoder:
     """Holds the parameters (dict name -> leaf tensor on the GPU) and runs SeCO / SpaCO steps."""
 
-    def __init__(self, params, n_layers, n_q_heads, n_kv_heads, head_dim):
+    def __init__(self, params, n_layers, n_q_heads, n_kv_heads, head_dim, rope_base=None):
         self.p = params
+        self.rope_base = rope_base      # rotary embedding of queries and keys (keys are cached rotated), or None
         self.n_layers, self.Hq, self.Hkv, self.D = n_layers, n_q_heads, n_kv_heads, head_dim
         self.scale = float(head_dim) ** -0.5
         _b.load_library()          # fail here, loudly, if the HIP library has not been built
@@ -101,8 +116,10 @@ class ChunkedDecoder:
             q = (h @ p[f"l{l}.wq"]).view(B, C, self.Hq, self.D).transpose(1, 2)
             k = (h @ p[f"l{l}.wk"]).view(B, C, self.Hkv, self.D).transpose(1, 2)
             v = (h @ p[f"l{l}.wv"]).view(B, C, self.Hkv, self.D).transpose(1, 2)
+            if self.rope_base is not None:
+                q = Rope.apply(q, q_start, self.rope_base)
             o = ChunkAttention.apply(q, k, v, states[l], q_start, self.scale, weights, wlen, keep,
-                                     None if dq_weights is None else dq_weights[l])
+                                     None if dq_weights is None else dq_weights[l], self.rope_base)
             x = x + o.transpose(1, 2).reshape(B, C, self.Hq * self.D) @ p[f"l{l}.wo"]
             h = _rmsnorm(x, p[f"l{l}.norm2"])
             x = x + F.silu(h @ p[f"l{l}.w1"]) @ p[f"l{l}.w2"]

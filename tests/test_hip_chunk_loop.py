@@ -24,7 +24,8 @@ def _setup(cfg, seed, B, N, dtype):
     g = torch.Generator().manual_seed(seed + 100)
     tok = torch.randint(0, cfg.vocab, (B, N), generator=g)
     tgt = torch.randint(0, cfg.vocab, (B, N), generator=g)
-    dec = ChunkedDecoder(pg, cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
+    dec = ChunkedDecoder(pg, cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                         rope_base=cfg.rope_base if cfg.rope_base > 1.0 else None)
     return p64, dec, tok, tgt
 
 
@@ -127,3 +128,22 @@ def test_column_weighted_dq_step_matches_oracle(dtype, cfg, tol):
     _compare(g_ref, g, tol)
     _, g_dense = om.spaco_grads(cfg, p64, tok, tgt, C, sel, f)
     assert max(float((g_dense[n] - g_ref[n]).abs().max() / g_ref[n].abs().max()) for n in g_ref) > 1e-2
+
+
+@pytest.mark.parametrize("dtype,base_cfg,tol", [(torch.float32, F32_CFG, 5e-4), (torch.bfloat16, BF16_CFG, 6e-2)])
+def test_step_with_rotary_embedding_matches_oracle(dtype, base_cfg, tol):
+    """Queries rotated by rope_rotate, keys rotated on their way into the cache (kv_append_rope), the key gradient
+    turned back at the read-out (kvgrad_readout_rope): SeCO against whole-sequence training, SpaCO against Alg. 2."""
+    import dataclasses
+    cfg = dataclasses.replace(base_cfg, rope_base=10000.0)
+    N, C = 320, 64
+    p64, dec, tok, tgt = _setup(cfg, 15, 1, N, dtype)
+    _, g_ref = om.monolithic_grads(cfg, p64, tok, tgt)
+    _, g = dec.step(tok.to(DEV), tgt.to(DEV), C, keep_attention_outputs=True)
+    _compare(g_ref, g, tol)
+    _, g_plain = om.monolithic_grads(base_cfg, p64, tok, tgt)          # the embedding is really there
+    assert max(float((g_plain[n] - g_ref[n]).abs().max() / g_ref[n].abs().max()) for n in g_ref) > 1e-2
+    sel, f = [4, 2, 1], 5.0 / 3.0
+    _, g_ref = om.spaco_grads(cfg, p64, tok, tgt, C, sel, f)
+    _, g = dec.step(tok.to(DEV), tgt.to(DEV), C, selected=sel, factor=f)
+    _compare(g_ref, g, tol)

@@ -291,3 +291,34 @@ def test_column_weighted_dq_needs_an_independent_draw_per_layer():
             assert err > 1e-3, err          # the square of a weight on paths that meet a chunk's columns in both layers
         else:
             assert err < 1e-12, err
+
+
+# ---- rotary position embedding in the model (keys cached rotated) --------------------------------------------------
+
+def test_rope_model_seco_is_exact_and_depends_on_distances_only():
+    import dataclasses
+    cfg = dataclasses.replace(CFG, rope_base=10000.0)
+    p = om.init_params(cfg, seed=51)
+    tok, tgt = _data(52, 2, 24, cfg)
+    loss_ref, g_ref = om.monolithic_grads(cfg, p, tok, tgt)
+    loss, g = om.seco_grads(cfg, p, tok, tgt, 6)
+    assert abs(loss - float(loss_ref)) < 1e-10 * abs(float(loss_ref))
+    assert _max_abs_diff(g, g_ref) <= 1e-11 * _scale_of(g_ref)
+    # the embedding matters ...
+    _, g_plain = om.monolithic_grads(CFG, p, tok, tgt)
+    assert _max_abs_diff(g_plain, g_ref) > 1e-3 * _scale_of(g_ref)
+    # ... and only through distances: the same tokens placed 1000 positions later give the same loss and gradients
+    # (the shift is applied to the rotation, which is the only place where positions enter)
+    orig = om._rope
+    try:
+        om._rope = lambda x, pos0, base: orig(x, pos0 + 1000, base)
+        loss_shift, g_shift = om.monolithic_grads(cfg, p, tok, tgt)
+    finally:
+        om._rope = orig
+    assert abs(float(loss_shift) - float(loss_ref)) < 1e-9 * abs(float(loss_ref))
+    assert _max_abs_diff(g_shift, g_ref) <= 1e-9 * _scale_of(g_ref)
+    # torch formulation against the NumPy one of oracle/relay.py
+    import numpy as np
+    from oracle import relay as R
+    x = torch.randn(1, 2, 5, 8, dtype=torch.float64, generator=torch.Generator().manual_seed(3))
+    assert np.abs(om._rope(x, 17, 500000.0).numpy() - R.rope_rotate(x.numpy(), 17, 500000.0)).max() < 1e-13
