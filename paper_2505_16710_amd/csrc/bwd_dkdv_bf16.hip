@@ -276,50 +276,53 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       // phase consumes x[t], the operand of the next phase is requested into the same register.
       bf16x8 x[8];
       auto p_half = [&](lds_char* pb, int t) { return *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 * t + lane * 16); };
+      // In both roles the vector work on row block 0 (exponentials; dS = P * (dP - delta)) is written between the
+      // MFMAs of the next chain, two values per MFMA, and that on row block 1 between the MFMAs of the chain after
+      // it, so that a wavefront keeps the matrix pipe fed while its own vector instructions issue.
       if (role == 0) {
         lds_char* qt1 = smem + slot1 * kStageBytes;
         SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt1 + 2 * kTileBytes);
 #pragma unroll
         for (int t = 0; t < 8; ++t) x[t] = lds_row8_at(qt1 + r_off[t], 0);
-        f32x16 s;
+        f32x16 s0, s1;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = lse_s[8 * (r >> 2) + 4 * g + (r & 3)];
+        for (int r = 0; r < 16; ++r) s0[r] = lse_s[8 * (r >> 2) + 4 * g + (r & 3)];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s1[r] = lse_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
         // log2 P of row block 0 (chain started from -LSE); Q rows of row block 1 come in behind
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-          s = mfma(x[t], frag[t], s);
+          s0 = mfma(x[t], frag[t], s0);
           x[t] = lds_row8_at(qt1 + r_off[t], 32);
         }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r]);
-        mask_above_diagonal(s, p.q_start + nxt.r0);
-        lds_char* pn0 = pslot((it + 1) & 1, 0);
-        *reinterpret_cast<SECO_LDS bf16x8*>(pn0 + lane * 16) = pack8(s, 0);
-        *reinterpret_cast<SECO_LDS bf16x8*>(pn0 + 1024 + lane * 16) = pack8(s, 1);
         lds_char* pb0 = pslot(it & 1, 0);
         const bf16x8 pa0[2] = {p_half(pb0, 0), p_half(pb0, 1)};
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = lse_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
-        // log2 P of row block 1; dO^T of row block 0 (stage `it`) comes in behind
+        // log2 P of row block 1, with the exponentials of row block 0; dO^T of row block 0 (stage `it`) comes in behind
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-          s = mfma(x[t], frag[t], s);
+          s1 = mfma(x[t], frag[t], s1);
           x[t] = lds_tr8_at(dot, t_off[t & 3], 16 * (t >> 2));
+          s0[2 * t] = fast_exp2(s0[2 * t]);
+          s0[2 * t + 1] = fast_exp2(s0[2 * t + 1]);
         }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r]);
-        mask_above_diagonal(s, p.q_start + nxt.r0 + 32);
-        lds_char* pn1 = pslot((it + 1) & 1, 1);
-        *reinterpret_cast<SECO_LDS bf16x8*>(pn1 + lane * 16) = pack8(s, 0);
-        *reinterpret_cast<SECO_LDS bf16x8*>(pn1 + 1024 + lane * 16) = pack8(s, 1);
+        mask_above_diagonal(s0, p.q_start + nxt.r0);
+        lds_char* pn0 = pslot((it + 1) & 1, 0);
+        *reinterpret_cast<SECO_LDS bf16x8*>(pn0 + lane * 16) = pack8(s0, 0);
+        *reinterpret_cast<SECO_LDS bf16x8*>(pn0 + 1024 + lane * 16) = pack8(s0, 1);
         lds_char* pb1 = pslot(it & 1, 1);
         const bf16x8 pa1[2] = {p_half(pb1, 0), p_half(pb1, 1)};
-        // dV of row block 0; dO^T of row block 1 comes in behind
+        // dV of row block 0, with the exponentials of row block 1; dO^T of row block 1 comes in behind
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           acc[i & 3] = mfma(pa0[i >> 2], x[i], acc[i & 3]);
           x[i] = lds_tr8_at(dot, t_off[i & 3], 32 + 16 * (i >> 2));
+          s1[2 * i] = fast_exp2(s1[2 * i]);
+          s1[2 * i + 1] = fast_exp2(s1[2 * i + 1]);
         }
+        mask_above_diagonal(s1, p.q_start + nxt.r0 + 32);
+        lds_char* pn1 = pslot((it + 1) & 1, 1);
+        *reinterpret_cast<SECO_LDS bf16x8*>(pn1 + lane * 16) = pack8(s1, 0);
+        *reinterpret_cast<SECO_LDS bf16x8*>(pn1 + 1024 + lane * 16) = pack8(s1, 1);
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i & 3] = mfma(pa1[i >> 2], x[i], acc[i & 3]);
       } else {
@@ -328,37 +331,37 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
         for (int t = 0; t < 8; ++t) x[t] = lds_row8_at(dot + r_off[t], 0);
         lds_char* pb0 = pslot(it & 1, 0);
         const bf16x8 ph0[2] = {p_half(pb0, 0), p_half(pb0, 1)};
-        f32x16 d;
+        f32x16 d0, d1;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) d[r] = delta_s[8 * (r >> 2) + 4 * g + (r & 3)];
+        for (int r = 0; r < 16; ++r) d0[r] = delta_s[8 * (r >> 2) + 4 * g + (r & 3)];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) d1[r] = delta_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
         // dP - delta of row block 0 (chain started from -delta); dO rows of row block 1 come in behind
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-          d = mfma(x[t], frag[t], d);
+          d0 = mfma(x[t], frag[t], d0);
           x[t] = lds_row8_at(dot + r_off[t], 32);
         }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) d[r] *= (float)ph0[r >> 3][r & 7];
-        const bf16x8 ds0[2] = {pack8(d, 0), pack8(d, 1)};
         lds_char* pb1 = pslot(it & 1, 1);
         const bf16x8 ph1[2] = {p_half(pb1, 0), p_half(pb1, 1)};
-#pragma unroll
-        for (int r = 0; r < 16; ++r) d[r] = delta_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
-        // dP - delta of row block 1; Q^T of row block 0 comes in behind
+        // dP - delta of row block 1, with dS of row block 0; Q^T of row block 0 comes in behind
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-          d = mfma(x[t], frag[t], d);
+          d1 = mfma(x[t], frag[t], d1);
           x[t] = lds_tr8_at(qt, t_off[t & 3], 16 * (t >> 2));
+          d0[2 * t] *= (float)ph0[t >> 2][(2 * t) & 7];
+          d0[2 * t + 1] *= (float)ph0[t >> 2][(2 * t + 1) & 7];
         }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) d[r] *= (float)ph1[r >> 3][r & 7];
-        const bf16x8 ds1[2] = {pack8(d, 0), pack8(d, 1)};
-        // dK of row block 0; Q^T of row block 1 comes in behind
+        const bf16x8 ds0[2] = {pack8(d0, 0), pack8(d0, 1)};
+        // dK of row block 0, with dS of row block 1; Q^T of row block 1 comes in behind
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           acc[i & 3] = mfma(ds0[i >> 2], x[i], acc[i & 3]);
           x[i] = lds_tr8_at(qt, t_off[i & 3], 32 + 16 * (i >> 2));
+          d1[2 * i] *= (float)ph1[i >> 2][(2 * i) & 7];
+          d1[2 * i + 1] *= (float)ph1[i >> 2][(2 * i + 1) & 7];
         }
+        const bf16x8 ds1[2] = {pack8(d1, 0), pack8(d1, 1)};
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i & 3] = mfma(ds1[i >> 2], x[i], acc[i & 3]);
       }
