@@ -22,7 +22,10 @@
 // S and dP are computed in the "row = query" orientation, so P and dS sit in the C layout
 // with lane = cache row and feed the second products as A operands; dO and Q for those
 // products come through the LDS transpose read.  P is written to LDS once (bf16, in operand
-// order) and read back by both roles, so it costs no registers across stages.
+// order) for role B; role A keeps its own copy in registers for the dV product of the next iteration.
+// Inside an iteration every wavefront runs four MFMA chains; the LDS operands of a chain are requested while
+// the chain before it runs (across the barrier too), and the exponentials / dS products of a row block are
+// written between the MFMAs of a later chain.
 //
 // Column tiles are enumerated from a by-value segment table (runs of cache rows that share
 // one non-zero weight); SpaCO's unselected chunks simply have no tiles.
@@ -257,6 +260,27 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   __syncthreads();
   Pos nxt2 = advance(nxt);
 
+  // One operand buffer x[8] rotates through the four MFMA chains of an iteration: while a chain consumes x[t], the
+  // operand of the next chain is requested into the same register ("comes in behind").  The last chain of an
+  // iteration requests the operands of the first chain of the next one, which read a stage that has already
+  // landed, so that no wavefront starts an iteration by waiting for LDS.  Role A also carries the probabilities of
+  // the stage it is about to use for dV (pa0, pa1: its own P blocks, as operands) in registers.
+  bf16x8 x[8];
+  bf16x8 pa0[2], pa1[2];
+  auto p_half = [&](lds_char* pb, int t) { return *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 * t + lane * 16); };
+  if (role == 0) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      pa0[t] = p_half(pslot(0, 0), t);
+      pa1[t] = p_half(pslot(0, 1), t);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = lds_tr8_at(smem + kTileBytes, t_off[i & 3], 16 * (i >> 2));
+  } else {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) x[t] = lds_row8_at(smem + kTileBytes + r_off[t], 0);
+  }
+
   int slot = 0;   // it % kStages
   for (int it = 0; it < n_iter; ++it) {
     const int slot1 = slot + 1 == kStages ? 0 : slot + 1;
@@ -267,103 +291,103 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     }
     lds_char* qt = smem + slot * kStageBytes;
     lds_char* dot = qt + kTileBytes;
-    // The two 32-row blocks of the stage are software-pipelined by hand: LDS operands of a phase are
-    // requested one phase ahead of the MFMA chain that consumes them.  Row blocks above the diagonal are
-    // not skipped: their probabilities are masked to zero and contribute nothing (only the first stages of
-    // a diagonal column tile are affected).
-    {
-      // One operand buffer x[8] rotates through the four phases of the iteration: while the MFMA chain of a
-      // phase consumes x[t], the operand of the next phase is requested into the same register.
-      bf16x8 x[8];
-      auto p_half = [&](lds_char* pb, int t) { return *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 * t + lane * 16); };
-      // In both roles the vector work on row block 0 (exponentials; dS = P * (dP - delta)) is written between the
-      // MFMAs of the next chain, two values per MFMA, and that on row block 1 between the MFMAs of the chain after
-      // it, so that a wavefront keeps the matrix pipe fed while its own vector instructions issue.
-      if (role == 0) {
-        lds_char* qt1 = smem + slot1 * kStageBytes;
-        SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt1 + 2 * kTileBytes);
+    lds_char* qt1 = smem + slot1 * kStageBytes;
+    lds_char* dot1 = qt1 + kTileBytes;
+    // Row blocks above the diagonal are not skipped: their probabilities are masked to zero and contribute nothing
+    // (only the first stages of a diagonal column tile are affected).  In both roles the vector work on a row block
+    // (exponentials; dS = P * (dP - delta)) is written between the MFMAs of a later chain, two values per MFMA, so
+    // that a wavefront keeps the matrix pipe fed while its own vector instructions issue.
+    if (role == 0) {
+      // stage `it`: dV += P^T dO (P from the previous iteration); stage `it + 1`: P = exp2(Q K^T c - LSE)
+      SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt1 + 2 * kTileBytes);
+      // dV of row block 0; Q rows of row block 0 of the next stage come in behind
 #pragma unroll
-        for (int t = 0; t < 8; ++t) x[t] = lds_row8_at(qt1 + r_off[t], 0);
-        f32x16 s0, s1;
+      for (int i = 0; i < 8; ++i) {
+        acc[i & 3] = mfma(pa0[i >> 2], x[i], acc[i & 3]);
+        x[i] = lds_row8_at(qt1 + r_off[i], 0);
+      }
+      f32x16 s0, s1;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s0[r] = lse_s[8 * (r >> 2) + 4 * g + (r & 3)];
+      for (int r = 0; r < 16; ++r) s0[r] = lse_s[8 * (r >> 2) + 4 * g + (r & 3)];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s1[r] = lse_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
-        // log2 P of row block 0 (chain started from -LSE); Q rows of row block 1 come in behind
+      for (int r = 0; r < 16; ++r) s1[r] = lse_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
+      // log2 P of row block 0 (chain started from -LSE); Q rows of row block 1 come in behind
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          s0 = mfma(x[t], frag[t], s0);
-          x[t] = lds_row8_at(qt1 + r_off[t], 32);
-        }
-        lds_char* pb0 = pslot(it & 1, 0);
-        const bf16x8 pa0[2] = {p_half(pb0, 0), p_half(pb0, 1)};
-        // log2 P of row block 1, with the exponentials of row block 0; dO^T of row block 0 (stage `it`) comes in behind
+      for (int t = 0; t < 8; ++t) {
+        s0 = mfma(x[t], frag[t], s0);
+        x[t] = lds_row8_at(qt1 + r_off[t], 32);
+      }
+      // log2 P of row block 1, with the exponentials of row block 0; dO^T of row block 1 (stage `it`) comes in behind
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          s1 = mfma(x[t], frag[t], s1);
-          x[t] = lds_tr8_at(dot, t_off[t & 3], 16 * (t >> 2));
-          s0[2 * t] = fast_exp2(s0[2 * t]);
-          s0[2 * t + 1] = fast_exp2(s0[2 * t + 1]);
-        }
-        mask_above_diagonal(s0, p.q_start + nxt.r0);
-        lds_char* pn0 = pslot((it + 1) & 1, 0);
-        *reinterpret_cast<SECO_LDS bf16x8*>(pn0 + lane * 16) = pack8(s0, 0);
-        *reinterpret_cast<SECO_LDS bf16x8*>(pn0 + 1024 + lane * 16) = pack8(s0, 1);
-        lds_char* pb1 = pslot(it & 1, 1);
-        const bf16x8 pa1[2] = {p_half(pb1, 0), p_half(pb1, 1)};
-        // dV of row block 0, with the exponentials of row block 1; dO^T of row block 1 comes in behind
+      for (int t = 0; t < 8; ++t) {
+        s1 = mfma(x[t], frag[t], s1);
+        x[t] = lds_tr8_at(dot, t_off[t & 3], 32 + 16 * (t >> 2));
+        s0[2 * t] = fast_exp2(s0[2 * t]);
+        s0[2 * t + 1] = fast_exp2(s0[2 * t + 1]);
+      }
+      mask_above_diagonal(s0, p.q_start + nxt.r0);
+      const bf16x8 pn0[2] = {pack8(s0, 0), pack8(s0, 1)};
+      lds_char* pw0 = pslot((it + 1) & 1, 0);
+      *reinterpret_cast<SECO_LDS bf16x8*>(pw0 + lane * 16) = pn0[0];
+      *reinterpret_cast<SECO_LDS bf16x8*>(pw0 + 1024 + lane * 16) = pn0[1];
+      // dV of row block 1, with the exponentials of row block 1 of the next stage; dO^T of row block 0 of the next
+      // stage comes in behind (for the first chain of the next iteration)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          acc[i & 3] = mfma(pa0[i >> 2], x[i], acc[i & 3]);
-          x[i] = lds_tr8_at(dot, t_off[i & 3], 32 + 16 * (i >> 2));
-          s1[2 * i] = fast_exp2(s1[2 * i]);
-          s1[2 * i + 1] = fast_exp2(s1[2 * i + 1]);
-        }
-        mask_above_diagonal(s1, p.q_start + nxt.r0 + 32);
-        lds_char* pn1 = pslot((it + 1) & 1, 1);
-        *reinterpret_cast<SECO_LDS bf16x8*>(pn1 + lane * 16) = pack8(s1, 0);
-        *reinterpret_cast<SECO_LDS bf16x8*>(pn1 + 1024 + lane * 16) = pack8(s1, 1);
+      for (int i = 0; i < 8; ++i) {
+        acc[i & 3] = mfma(pa1[i >> 2], x[i], acc[i & 3]);
+        x[i] = lds_tr8_at(dot1, t_off[i & 3], 16 * (i >> 2));
+        s1[2 * i] = fast_exp2(s1[2 * i]);
+        s1[2 * i + 1] = fast_exp2(s1[2 * i + 1]);
+      }
+      mask_above_diagonal(s1, p.q_start + nxt.r0 + 32);
+      pa0[0] = pn0[0];
+      pa0[1] = pn0[1];
+      pa1[0] = pack8(s1, 0);
+      pa1[1] = pack8(s1, 1);
+      lds_char* pw1 = pslot((it + 1) & 1, 1);
+      *reinterpret_cast<SECO_LDS bf16x8*>(pw1 + lane * 16) = pa1[0];
+      *reinterpret_cast<SECO_LDS bf16x8*>(pw1 + 1024 + lane * 16) = pa1[1];
+    } else {
+      // stage `it`: dS = P * (dO V^T - delta), dK += dS^T Q
+      SECO_LDS float* delta_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + BQ;
+      lds_char* pb0 = pslot(it & 1, 0);
+      const bf16x8 ph0[2] = {p_half(pb0, 0), p_half(pb0, 1)};
+      lds_char* pb1 = pslot(it & 1, 1);
+      const bf16x8 ph1[2] = {p_half(pb1, 0), p_half(pb1, 1)};
+      f32x16 d0, d1;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i & 3] = mfma(pa1[i >> 2], x[i], acc[i & 3]);
-      } else {
-        SECO_LDS float* delta_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + BQ;
+      for (int r = 0; r < 16; ++r) d0[r] = delta_s[8 * (r >> 2) + 4 * g + (r & 3)];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) x[t] = lds_row8_at(dot + r_off[t], 0);
-        lds_char* pb0 = pslot(it & 1, 0);
-        const bf16x8 ph0[2] = {p_half(pb0, 0), p_half(pb0, 1)};
-        f32x16 d0, d1;
+      for (int r = 0; r < 16; ++r) d1[r] = delta_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
+      // dP - delta of row block 0 (chain started from -delta); dO rows of row block 1 come in behind
 #pragma unroll
-        for (int r = 0; r < 16; ++r) d0[r] = delta_s[8 * (r >> 2) + 4 * g + (r & 3)];
+      for (int t = 0; t < 8; ++t) {
+        d0 = mfma(x[t], frag[t], d0);
+        x[t] = lds_row8_at(dot + r_off[t], 32);
+      }
+      // dP - delta of row block 1, with dS of row block 0; Q^T of row block 0 comes in behind
 #pragma unroll
-        for (int r = 0; r < 16; ++r) d1[r] = delta_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
-        // dP - delta of row block 0 (chain started from -delta); dO rows of row block 1 come in behind
+      for (int t = 0; t < 8; ++t) {
+        d1 = mfma(x[t], frag[t], d1);
+        x[t] = lds_tr8_at(qt, t_off[t & 3], 16 * (t >> 2));
+        d0[2 * t] *= (float)ph0[t >> 2][(2 * t) & 7];
+        d0[2 * t + 1] *= (float)ph0[t >> 2][(2 * t + 1) & 7];
+      }
+      const bf16x8 ds0[2] = {pack8(d0, 0), pack8(d0, 1)};
+      // dK of row block 0, with dS of row block 1; Q^T of row block 1 comes in behind
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          d0 = mfma(x[t], frag[t], d0);
-          x[t] = lds_row8_at(dot + r_off[t], 32);
-        }
-        lds_char* pb1 = pslot(it & 1, 1);
-        const bf16x8 ph1[2] = {p_half(pb1, 0), p_half(pb1, 1)};
-        // dP - delta of row block 1, with dS of row block 0; Q^T of row block 0 comes in behind
+      for (int i = 0; i < 8; ++i) {
+        acc[i & 3] = mfma(ds0[i >> 2], x[i], acc[i & 3]);
+        x[i] = lds_tr8_at(qt, t_off[i & 3], 32 + 16 * (i >> 2));
+        d1[2 * i] *= (float)ph1[i >> 2][(2 * i) & 7];
+        d1[2 * i + 1] *= (float)ph1[i >> 2][(2 * i + 1) & 7];
+      }
+      const bf16x8 ds1[2] = {pack8(d1, 0), pack8(d1, 1)};
+      // dK of row block 1; dO rows of row block 0 of the next stage come in behind (for the next iteration)
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          d1 = mfma(x[t], frag[t], d1);
-          x[t] = lds_tr8_at(qt, t_off[t & 3], 16 * (t >> 2));
-          d0[2 * t] *= (float)ph0[t >> 2][(2 * t) & 7];
-          d0[2 * t + 1] *= (float)ph0[t >> 2][(2 * t + 1) & 7];
-        }
-        const bf16x8 ds0[2] = {pack8(d0, 0), pack8(d0, 1)};
-        // dK of row block 0, with dS of row block 1; Q^T of row block 1 comes in behind
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          acc[i & 3] = mfma(ds0[i >> 2], x[i], acc[i & 3]);
-          x[i] = lds_tr8_at(qt, t_off[i & 3], 32 + 16 * (i >> 2));
-          d1[2 * i] *= (float)ph1[i >> 2][(2 * i) & 7];
-          d1[2 * i + 1] *= (float)ph1[i >> 2][(2 * i + 1) & 7];
-        }
-        const bf16x8 ds1[2] = {pack8(d1, 0), pack8(d1, 1)};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i & 3] = mfma(ds1[i >> 2], x[i], acc[i & 3]);
+      for (int i = 0; i < 8; ++i) {
+        acc[i & 3] = mfma(ds1[i >> 2], x[i], acc[i & 3]);
+        x[i] = lds_row8_at(dot1 + r_off[i], 0);
       }
     }
     dma_wait_all();
@@ -374,13 +398,18 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     slot = slot1;
   }
 
+  // The lane-dependent indices of the epilogue are derived again from the thread index (through an empty asm, so
+  // that the compiler does not keep the ones computed before the loop alive across it: the loop uses every register).
+  int tid_e = threadIdx.x;
+  asm volatile("" : "+v"(tid_e));
+  const int l32_e = tid_e & 31, g_e = (tid_e >> 5) & 1, n0_e = c0 + ((tid_e >> 6) % NCB) * 32;
   if (divided) {
     // a share of the heads: plain stores of the unweighted sums, all 32 rows (the merge drops rows past the tile's end)
     float* pb = ts.part + ((((int64_t)unit * ts.n_tiles + (tile - n_whole)) * ts.hs + share) * 2 + role) *
-                              (int64_t)(Cfg::kCols * 128) + (cb * 32) * 128 + l32;
+                              (int64_t)(Cfg::kCols * 128) + (cb * 32) * 128 + l32_e;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      float* pr = pb + (8 * (r >> 2) + 4 * g + (r & 3)) * 128;
+      float* pr = pb + (8 * (r >> 2) + 4 * g_e + (r & 3)) * 128;
 #pragma unroll
       for (int db = 0; db < 4; ++db) pr[32 * db] = acc[db][r];
     }
@@ -394,16 +423,16 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   float old[16][4];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const int kvrow = min(n0 + 8 * (r >> 2) + 4 * g + (r & 3), c_end - 1);
-    const float* gr = gbase + (int64_t)kvrow * p.gs[2] + l32;
+    const int kvrow = min(n0_e + 8 * (r >> 2) + 4 * g_e + (r & 3), c_end - 1);
+    const float* gr = gbase + (int64_t)kvrow * p.gs[2] + l32_e;
 #pragma unroll
     for (int db = 0; db < 4; ++db) old[r][db] = gr[32 * db];
   }
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const int kvrow = n0 + 8 * (r >> 2) + 4 * g + (r & 3);
+    const int kvrow = n0_e + 8 * (r >> 2) + 4 * g_e + (r & 3);
     if (kvrow < c_end) {
-      float* gr = gbase + (int64_t)kvrow * p.gs[2] + l32;
+      float* gr = gbase + (int64_t)kvrow * p.gs[2] + l32_e;
 #pragma unroll
       for (int db = 0; db < 4; ++db) gr[32 * db] = old[r][db] + wf * acc[db][r];
     }
