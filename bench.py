@@ -49,6 +49,10 @@ def main():
                          "report their GB/s against the 8 TB/s HBM peak")
     ap.add_argument("--schedules", action="store_true",
                     help="also time a whole layer of --config under Alg. 1 and Alg. 2 (needs a config with spaco_t)")
+    ap.add_argument("--context-scaling", action="store_true",
+                    help="also time the backward loop of Alg. 2 (t = 8 selected chunks of 2048 tokens, evenly spaced) at "
+                         "16K, 32K and 64K tokens, split into its dQ and dK/dV kernels: the paper's claim that the "
+                         "backward cost is decoupled from the context length (Sec. 5), and what is left of it")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time replays of it (removes the dispatch gaps between "
                          "the short kernels of small chunks); no per-kernel events in this mode")
@@ -354,6 +358,51 @@ def main():
             res[name] = round(best, 5)
         res["selected_chunks"] = sel
         return res
+
+    def context_scaling():
+        """Backward loop of Alg. 2 with C = 2048 and t = 8 fixed while the context grows (k = 8, 16, 32 chunks; the
+        selected chunks evenly spaced, the last one included; factor k/t; stage-1 outputs kept, so the loop is the
+        t backward calls only).  Per context length: milliseconds of the loop (host clock, best of 3) and, from the
+        library's per-kernel events in one extra pass, of its dQ and dK/dV kernels; the same with the dQ of a call
+        visiting the selected chunks only (spaco_chunk_attn_bwd_sparse_dq, weight (k-1)/(t-1))."""
+        Cx, tx, res = 2048, 8, {}
+        for Nx in (16384, 32768, 65536):
+            Lx = Layer(Nx, Cx)
+            kx = Nx // Cx
+            sel = [kx - 1 - i * (kx // tx) for i in range(tx)]
+            lam, lam_q = kx / tx, (kx - 1) / (tx - 1)
+            for j in range(kx):
+                Lx.fwd(j)
+
+            def loop(sparse_dq):
+                seco.kvgrad_zero(Lx.gk, Lx.gv)
+                for j in sel:
+                    Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam),
+                           seco.spaco_chunk_weights(sel, j, lam_q) if sparse_dq else None)
+
+            row = {"n_chunks": kx, "selected_chunks": sel}
+            for tag, sparse_dq in (("exact_dq", False), ("sparse_dq", True)):
+                loop(sparse_dq)
+                torch.cuda.synchronize()
+                best = 1e9
+                for _ in range(3):
+                    a = time.perf_counter()
+                    loop(sparse_dq)
+                    torch.cuda.synchronize()
+                    best = min(best, time.perf_counter() - a)
+                seco.seco_profile_enable(True)
+                loop(sparse_dq)
+                prof = seco.seco_profile_read()
+                seco.seco_profile_enable(False)
+                row[tag] = {"loop_ms": round(best * 1e3, 3), "dq_ms": round(prof["dq"][0], 3),
+                            "dkdv_ms": round(prof["dkdv"][0], 3)}
+            res[str(Nx)] = row
+            del Lx
+            torch.cuda.empty_cache()
+        return res
+
+    if args.context_scaling and cfg.dtype == "bf16":
+        out["context_scaling_c2048_t8"] = context_scaling()
 
     if args.schedules and cfg.dtype == "bf16" and cfg.spaco_t > 0:
         # the two schedules on the benchmarked configuration itself
