@@ -225,6 +225,13 @@ def main():
         "step_ms_min": round(per_step[0], 4), "step_ms_median": round(per_step[len(per_step) // 2], 4),
     }
 
+    # what the device reports: compute units x 4096 bf16 FLOP per clock and CU x its maximum clock (the published
+    # 2.5 PFLOP/s is 256 CUs at 2.4 GHz; the clock under load is lower and not readable from here)
+    cus, clock_khz = seco.binding.seco_device_info()
+    out["device"] = {"name": torch.cuda.get_device_properties(0).name, "compute_units": cus,
+                     "max_clock_mhz": round(clock_khz / 1e3),
+                     "bf16_peak_from_device_tflops": round(cus * 4096 * clock_khz * 1e3 / 1e12, 1)}
+
     if prof is not None:
         alg = {"fwd": flops_fwd, "dq": flops_dq, "dkdv": flops_dkdv}
         kern = {}

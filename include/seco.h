@@ -301,6 +301,13 @@ size_t seco_workspace_bytes(const seco_desc* desc, int op);
  */
 int seco_launch_plan(const seco_desc* desc, int32_t n_col_tiles, int32_t* plan_host);
 
+/*
+ * What the current HIP device reports, for benchmarks that state the matrix-core peak they compare against
+ * (compute units x 4096 bf16 FLOP per clock x clock): number of compute units and maximum engine clock in kHz,
+ * written to the two HOST integers.  SECO_ERR_NULL for a NULL pointer, SECO_ERR_LAUNCH if the runtime has no device.
+ */
+int seco_device_info(int32_t* compute_units_host, int32_t* max_clock_khz_host);
+
 /* Static English description of a status code. */
 const char* seco_strerror(int status);
 

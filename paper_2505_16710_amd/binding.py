@@ -75,6 +75,8 @@ def load_library():
     lib.seco_workspace_bytes.argtypes = [dp, C.c_int]
     lib.seco_launch_plan.argtypes = [dp, i32, C.POINTER(i32)]
     lib.seco_launch_plan.restype = C.c_int
+    lib.seco_device_info.argtypes = [C.POINTER(i32), C.POINTER(i32)]
+    lib.seco_device_info.restype = C.c_int
     lib.seco_workspace_bytes.restype = sz
     lib.seco_strerror.argtypes = [C.c_int]
     lib.seco_strerror.restype = C.c_char_p
@@ -362,6 +364,13 @@ def seco_launch_plan(desc, n_col_tiles):
     out = (C.c_int32 * 4)()
     _check(load_library().seco_launch_plan(C.byref(desc), int(n_col_tiles), out), "seco_launch_plan")
     return tuple(out)
+
+
+def seco_device_info():
+    """(compute units, maximum engine clock in kHz) of the current HIP device."""
+    cus, khz = C.c_int32(0), C.c_int32(0)
+    _check(load_library().seco_device_info(C.byref(cus), C.byref(khz)), "seco_device_info")
+    return cus.value, khz.value
 
 
 def seco_profile_enable(on=True, kinds=None):

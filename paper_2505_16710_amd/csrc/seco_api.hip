@@ -266,6 +266,20 @@ extern "C" int seco_profile_read(double* total_ms, int64_t* launches) {
   return rc;
 }
 
+extern "C" int seco_device_info(int32_t* compute_units_host, int32_t* max_clock_khz_host) {
+  if (!compute_units_host || !max_clock_khz_host) return SECO_ERR_NULL;
+  int dev = 0, cus = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return SECO_ERR_LAUNCH;
+  }
+  *compute_units_host = cus;
+  *max_clock_khz_host = khz;
+  return SECO_OK;
+}
+
 extern "C" size_t seco_workspace_bytes(const seco_desc* desc, int op) {
   if (check_desc(desc) != SECO_OK) return (size_t)-1;
   if (op == SECO_OP_FWD) return split_part_bytes(desc) + split_ml_bytes(desc);

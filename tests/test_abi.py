@@ -270,3 +270,15 @@ def test_rope_entry_points_validate_their_arguments():
     assert lib.rope_rotate(C.byref(d), 0, FAKE, FAKE, 0, f32(1e4), 0, None) == -8
     assert lib.rope_rotate(C.byref(d), 4, FAKE, FAKE, -1, f32(1e4), 0, None) == -8
     assert lib.rope_rotate(C.byref(d), 4, C.c_void_p(0x1004), FAKE, 0, f32(1e4), 0, None) == -5
+
+
+def test_device_info_rejects_null_and_reports_or_fails_cleanly():
+    lib = B.load_library()
+    one = C.c_int32(0)
+    assert lib.seco_device_info(None, C.byref(one)) == -1 and lib.seco_device_info(C.byref(one), None) == -1
+    cus, khz = C.c_int32(-7), C.c_int32(-7)
+    rc = lib.seco_device_info(C.byref(cus), C.byref(khz))
+    if rc == 0:                       # a GPU is present
+        assert cus.value > 0 and khz.value > 0
+    else:                             # no device: a status, and the outputs are left alone
+        assert rc == -9 and (cus.value, khz.value) == (-7, -7)
