@@ -208,6 +208,40 @@ def test_strided_inputs_bf16():
     assert max_rel(to_host(gk), dk_ref) < 2e-2 and max_rel(to_host(gv), dv_ref) < 2e-2
 
 
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,D", [("bf16", 2, 2, 1, 128), ("f32", 1, 2, 2, 64)])
+def test_heads_and_batches_more_than_2_to_31_elements_apart(dtype, B, Hq, Hkv, D):
+    """Every tensor laid out with its (batch, head) slices more than 2^31 elements apart, as in buffers sized for a
+    far longer sequence: the address arithmetic is 64-bit throughout (the strides are elements, not bytes)."""
+    N, C, far = 256, 128, 2 ** 31 + 4096
+    x = small_layer(77, B, Hq, Hkv, N, D, dtype)
+    s = 1 / np.sqrt(D)
+    tt = torch.bfloat16 if dtype == "bf16" else torch.float32
+
+    def spread(H, t):                 # uninitialised [B, H, N, D] view whose slices lie `far` elements apart
+        store = torch.empty((B * H - 1) * far + N * D, device=DEV, dtype=t)
+        return store.as_strided((B, H, N, D), (H * far, far, D, 1))
+
+    def placed(a):
+        v = spread(a.shape[1], tt)
+        v.copy_(to_dev(a, dtype))
+        return v
+
+    q, k, v, do = placed(x["q"]), placed(x["k"]), placed(x["v"]), placed(x["do"])
+    assert q.stride(1) > 2 ** 31 and k.stride(0) > 2 ** 31
+    o, dq = spread(Hq, tt), spread(Hq, tt)
+    gk, gv = spread(Hkv, torch.float32), spread(Hkv, torch.float32)
+    seco.kvgrad_zero(gk, gv)
+    o1, lse = seco.seco_chunk_attn_fwd(q[:, :, C:], k, v, C, s, o=o[:, :, C:])
+    dq1 = seco.seco_chunk_attn_bwd(q[:, :, C:], k, v, o1, lse, do[:, :, C:], gk, gv, C, s, d_q=dq[:, :, C:])
+    torch.cuda.synchronize()
+    o_ref, lse_ref = A.chunk_attn_fwd(x["q"][:, :, C:], x["k"], x["v"], C, s)
+    dq_ref, dk_ref, dv_ref = A.chunk_attn_bwd(x["q"][:, :, C:], x["k"], x["v"], o_ref, lse_ref, x["do"][:, :, C:], C, s)
+    tol_o, tol_g = (1e-2, 2e-2) if dtype == "bf16" else (1e-4, 1e-4)
+    assert max_rel(to_host(o1), o_ref) < tol_o and max_rel(to_host(lse), lse_ref) < 1e-4
+    assert max_rel(to_host(dq1), dq_ref) < tol_g
+    assert max_rel(to_host(gk), dk_ref) < tol_g and max_rel(to_host(gv), dv_ref) < tol_g
+
+
 def _device_group(cfg, b, kvh):
     """One (batch, KV head) unit of a configuration as a G-head layer: host dict + fp64 views."""
     grp = kv_group(cfg, b, kvh)
