@@ -242,6 +242,43 @@ def test_heads_and_batches_more_than_2_to_31_elements_apart(dtype, B, Hq, Hkv, D
     assert max_rel(to_host(gk), dk_ref) < tol_g and max_rel(to_host(gv), dv_ref) < tol_g
 
 
+def test_one_call_against_a_cache_of_a_million_rows():
+    """The last chunk (256 rows, two query heads on one KV head) of a 2^20-token context: 8192 column tiles, the
+    short-chunk path with its cache range divided among workgroups, fp32 row sums over a million terms.  The oracle
+    evaluates O and LSE in full, dQ on sampled rows and, with the true LSE and O of the chunk and a cache cut down to
+    a window plus the chunk's own rows, which returns exactly those rows' blocks of dK/dV, gK/gV on the first rows, on
+    rows in the middle that straddle a column tile, and on the chunk's own rows."""
+    from workloads import round_to
+    N, C, D, s = 2 ** 20, 256, 128, 1 / np.sqrt(128)
+    rng = np.random.default_rng(2 ** 20)
+    k32 = round_to(rng.standard_normal((1, 1, N, D), dtype=np.float32), "bf16")
+    v32 = round_to(rng.standard_normal((1, 1, N, D), dtype=np.float32), "bf16")
+    q32 = round_to(rng.standard_normal((1, 2, C, D), dtype=np.float32), "bf16")
+    do32 = round_to(rng.standard_normal((1, 2, C, D), dtype=np.float32), "bf16")
+    q, k, v, do = (to_dev(a, "bf16") for a in (q32, k32, v32, do32))
+    q0 = N - C
+    o, lse = seco.seco_chunk_attn_fwd(q, k, v, q0, s)
+    gk = torch.zeros(1, 1, N, D, device=DEV)
+    gv = torch.zeros(1, 1, N, D, device=DEV)
+    dq = seco.seco_chunk_attn_bwd(q, k, v, o, lse, do, gk, gv, q0, s)
+    torch.cuda.synchronize()
+    o_g, lse_g, dq_g = to_host(o), to_host(lse), to_host(dq)
+    q64, k64, v64, do64 = (a.astype(np.float64) for a in (q32, k32, v32, do32))
+    o_ref, lse_ref = A.chunk_attn_fwd(q64, k64, v64, q0, s)
+    assert max_rel(o_g, o_ref) <= 1e-2 and max_rel(lse_g, lse_ref) <= 1e-4
+    for r in (0, 101, C - 1):
+        dq_r, _, _ = A.chunk_attn_bwd(q64[:, :, r:r + 1], k64, v64, o_ref[:, :, r:r + 1], lse_ref[:, :, r:r + 1],
+                                      do64[:, :, r:r + 1], q0 + r, s)
+        assert np.abs(dq_g[:, :, r] - dq_r[:, :, 0]).max() <= 2e-2 * np.abs(dq_r).max()
+    # (the window is followed by the chunk's own rows, so that the cut-down cache has q_start + C rows)
+    for lo, hi in ((0, 200), (N // 2 - 70, N // 2 + 70), (q0, q0)):
+        kw = np.concatenate([k64[:, :, lo:hi], k64[:, :, q0:]], axis=2)
+        vw = np.concatenate([v64[:, :, lo:hi], v64[:, :, q0:]], axis=2)
+        _, dk_w, dv_w = A.chunk_attn_bwd(q64, kw, vw, o_ref, lse_ref, do64, hi - lo, s)
+        rows = np.r_[lo:hi, q0:N]
+        assert max_rel(to_host(gk)[:, :, rows], dk_w) <= 2e-2 and max_rel(to_host(gv)[:, :, rows], dv_w) <= 2e-2
+
+
 def _device_group(cfg, b, kvh):
     """One (batch, KV head) unit of a configuration as a G-head layer: host dict + fp64 views."""
     grp = kv_group(cfg, b, kvh)
