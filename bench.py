@@ -366,6 +366,39 @@ def main():
         res["selected_chunks"] = sel
         return res
 
+    def transposed_order():
+        """The same step with the backward calls in the transposed order (seco_chunk_attn_bwd_gather: the call of
+        chunk j forms the finished gK/gV rows of chunk j from the query rows of chunks j..k-1, instead of adding
+        to the rows of chunks 0..j): same forward calls, same dQ, same final gK/gV up to the order of summation."""
+        stats = torch.empty(2, B, Hq, (N + 3) // 4 * 4, device=dev, dtype=torch.float32)
+
+        def step_t():
+            seco.kvgrad_zero(L.gk, L.gv)
+            for j in range(k_chunks - 1, -1, -1):
+                L.fwd(j)
+                seco.seco_chunk_attn_bwd_gather(L.q[:, :, j * C:], L.kc, L.vc, L.rows(L.o, j), L.lse[j],
+                                                L.do[:, :, j * C:], L.gk, L.gv, j * C, scale, C, stats,
+                                                d_q=L.rows(L.dq, j), ws=L.ws)
+
+        for _ in range(max(args.warmup, 1)):
+            step_t()
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(args.steps):
+            step_t()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - a) * 1e3 / args.steps
+        seco.seco_profile_enable(True)
+        step_t()
+        prof_t = seco.seco_profile_read()
+        seco.seco_profile_enable(False)
+        return {"ms_per_step": round(ms, 4), "tflops": round(flops_step / (ms * 1e-3) / 1e12, 2),
+                "dkdv_ms_per_step": round(prof_t["dkdv"][0], 4), "dq_ms_per_step": round(prof_t["dq"][0], 4),
+                "fwd_ms_per_step": round(prof_t["fwd"][0], 4)}
+
+    if cfg.dtype == "bf16" and N % C == 0 and not args.graph:
+        out["transposed_backward_order"] = transposed_order()
+
     def context_scaling():
         """Backward loop of Alg. 2 with C = 2048 and t = 8 fixed while the context grows (k = 8, 16, 32 chunks; the
         selected chunks evenly spaced, the last one included; factor k/t; stage-1 outputs kept, so the loop is the

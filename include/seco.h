@@ -62,7 +62,8 @@ typedef enum seco_status {
 
 typedef enum seco_op {
   SECO_OP_FWD = 0,
-  SECO_OP_BWD = 1            /* seco_chunk_attn_bwd, spaco_chunk_attn_bwd, spaco_chunk_attn_bwd_sparse_dq */
+  SECO_OP_BWD = 1            /* seco_chunk_attn_bwd, spaco_chunk_attn_bwd, spaco_chunk_attn_bwd_sparse_dq,
+                                seco_chunk_attn_bwd_gather */
 } seco_op;
 
 /* One chunk call.  kv_len = q_start + chunk_len cache rows are visible. */
@@ -159,6 +160,33 @@ int spaco_chunk_attn_bwd_sparse_dq(const seco_desc* desc, const void* q, const v
                                    const float* chunk_weight_host, const float* dq_weight_host,
                                    int32_t n_chunks, int32_t weight_chunk_len,
                                    void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Backward of one chunk in the transposed order (bf16 only).  Alg. 1 lets the backward of chunk j add its dK/dV to
+ * the gradient of every earlier checkpoint m'_i; the sum that m'_i.grad holds when chunk i is reached,
+ *     gK[rows of chunk i] = sum over chunks j >= i of (dK of chunk j's queries on those rows),
+ * can as well be formed when chunk i is reached, because the terms of a later chunk need only its Q, dO, LSE and
+ * delta, all known by then.  This call does that for chunk i = desc: it returns dQ of the chunk exactly as
+ * seco_chunk_attn_bwd does, and ADDS to rows [q_start, q_start + chunk_len) of gk/gv the contributions of the
+ * chunk's own query rows and of the n_later_rows query rows that follow it; no other row of gk/gv is touched.
+ * Called for every chunk in descending order with all later rows, the result equals that of seco_chunk_attn_bwd
+ * called for every chunk (to rounding: the summation order differs; both orders are fixed, so both are
+ * reproducible).  Every call has the same number of cache rows to cover, so its workgroups are equal in length
+ * and none re-reads gk/gv rows that another call wrote.
+ *   q_rows     in   [B, Hq, chunk_len + n_later_rows, D] (q_stride): queries of sequence rows q_start, q_start+1, ...
+ *   d_o_rows   in   the same rows of dO (o_stride)
+ *   o, lse     in   forward outputs of the chunk itself ([B, Hq, C, D] with o_stride, [B, Hq, C])
+ *   d_q        out  [B, Hq, C, D] (q_stride)
+ *   row_stats  i/o  fp32 [2, B, Hq, stat_rows], 16-byte aligned, kept by the caller for the whole backward pass:
+ *                   the call writes the entries of its own rows (at positions q_start ..) and reads those of the
+ *                   later rows, which the calls of the later chunks wrote.  stat_rows: a multiple of 4 that is
+ *                   >= q_start + chunk_len + n_later_rows (SECO_ERR_RANGE otherwise).
+ *   ws         as seco_chunk_attn_bwd (same size)
+ */
+int seco_chunk_attn_bwd_gather(const seco_desc* desc, const void* q_rows, const void* k_cache, const void* v_cache,
+                               const void* o, const float* lse, const void* d_o_rows,
+                               void* d_q, float* gk, float* gv, float* row_stats, int64_t stat_rows,
+                               int32_t n_later_rows, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
  * Zero rows [row_begin, row_end) of the KV gradient buffers (start of a training iteration;

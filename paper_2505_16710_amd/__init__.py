@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     load_library,
     rope_rotate,
     seco_chunk_attn_bwd,
+    seco_chunk_attn_bwd_gather,
     seco_chunk_attn_fwd,
     seco_device_info,
     seco_launch_plan,

@@ -134,7 +134,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 
   const __bf16* qbase = static_cast<const __bf16*>(p.q) + b * p.qs[0] + (int64_t)kvh * p.G * p.qs[1];
   const __bf16* dobase = static_cast<const __bf16*>(p.d_o) + b * p.os[0] + (int64_t)kvh * p.G * p.os[1];
-  const int64_t stat_base = ((int64_t)b * p.Hq + (int64_t)kvh * p.G) * p.C;
+  const int64_t stat_base = ((int64_t)b * p.Hq + (int64_t)kvh * p.G) * p.stat_stride + p.stat_off;
   // asynchronous global -> LDS copy of the Q and dO tiles of one stage (4 rows per wavefront and copy).  A stage
   // that lies entirely inside the chunk is copied from scalar base addresses with constant per-lane offsets (no
   // vector arithmetic); the last, ragged one uses clamped per-lane addresses.
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   auto copy_stat = [&](Pos x, int slot) {
     if (x.r0 + BQ <= p.C) {
       if (wave_u < 2) {
-        const uint64_t a = (uint64_t)(uintptr_t)((wave_u == 0 ? p.nlse2 : p.delta) + stat_base + (int64_t)x.hg * p.C + x.r0);
+        const uint64_t a = (uint64_t)(uintptr_t)((wave_u == 0 ? p.nlse2 : p.delta) + stat_base + (int64_t)x.hg * p.stat_stride + x.r0);
         // (wavefront-uniform by construction; the halves go through readfirstlane so that the compiler keeps them
         // in scalar registers; each half is widened from an unsigned 32-bit value)
         const uint64_t src = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(a >> 32)) << 32) |
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       }
     } else if (wave_u < 2) {             // (wavefront-uniform control flow only: the copies above need scalar addresses)
       const int rr = x.r0 + lane;
-      const float v = (wave_u == 0 ? p.nlse2 : p.delta)[stat_base + (int64_t)x.hg * p.C + min(rr, p.C - 1)];
+      const float v = (wave_u == 0 ? p.nlse2 : p.delta)[stat_base + (int64_t)x.hg * p.stat_stride + min(rr, p.C - 1)];
       const float stat = wave_u == 0 && rr >= p.C ? -INFINITY : v;
       *reinterpret_cast<SECO_LDS float*>(smem + slot * kStageBytes + 2 * kTileBytes + (wave_u * BQ + lane) * 4) = stat;
     }

@@ -100,8 +100,9 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, SegT
     }
     delta += __shfl_xor(delta, 32);
     if (kh == 0 && sp == 0 && g == 0 && row < p.C) {
-      p.delta[stat] = -delta;
-      p.nlse2[stat] = -lse_c;
+      const int64_t kept = ((int64_t)b * p.Hq + h) * p.stat_stride + p.stat_off + crow;
+      p.delta[kept] = -delta;
+      p.nlse2[kept] = -lse_c;
     }
   }
   const float c = p.scale * kLog2e;

@@ -52,6 +52,8 @@ AttnParams make_params(const seco_desc* d) {
   p.q_start = d->q_start;
   p.G = d->n_q_heads / d->n_kv_heads;
   p.scale = d->softmax_scale;
+  p.stat_stride = d->chunk_len;
+  p.stat_off = 0;
   for (int i = 0; i < 3; ++i) {
     p.qs[i] = d->q_stride[i];
     p.os[i] = d->o_stride[i];
@@ -201,6 +203,58 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
   return SECO_OK;
 }
 
+
+// Backward of chunk i in the transposed order: dQ of the chunk as usual, and the chunk's own gK/gV rows from the
+// query rows of the chunk and of every later row handed in (their -delta and -LSE are read from row_stats, where
+// the dQ kernels of their own calls left them).
+int backward_gather(const seco_desc* d, const void* q_rows, const void* k, const void* v, const void* o,
+                    const float* lse, const void* d_o_rows, void* d_q, float* gk, float* gv, float* row_stats,
+                    int64_t stat_rows, int32_t n_later_rows, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_fwd_like(d);
+  if (rc) return rc;
+  if (d->dtype != SECO_BF16) return SECO_ERR_DTYPE;
+  if ((rc = check_strides(d->g_stride, 4, d->head_dim))) return rc;
+  if (!q_rows || !k || !v || !o || !lse || !d_o_rows || !d_q || !gk || !gv || !row_stats) return SECO_ERR_NULL;
+  if (!aligned16(q_rows) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o_rows) ||
+      !aligned16(d_q) || !aligned16(gk) || !aligned16(gv) || !aligned16(lse) || !aligned16(row_stats))
+    return SECO_ERR_ALIGN;
+  if (n_later_rows < 0) return SECO_ERR_RANGE;
+  const int64_t rows = (int64_t)d->chunk_len + n_later_rows;
+  const int64_t last = (int64_t)d->q_start + rows;
+  if (last > (int64_t)1 << 30) return SECO_ERR_TOO_LARGE;
+  if ((int64_t)d->batch * d->n_q_heads * ((rows + 3) / 4) > (int64_t)1 << 31) return SECO_ERR_TOO_LARGE;
+  if (stat_rows < last || stat_rows % 4 != 0) return SECO_ERR_RANGE;
+  if (stat_rows > (int64_t)1 << 30) return SECO_ERR_TOO_LARGE;
+  if (!ws || ws_bytes < delta_bytes(d) + bwd_part_bytes(d) || (reinterpret_cast<uintptr_t>(ws) & 255u))
+    return SECO_ERR_WORKSPACE;
+
+  AttnParams p = make_params(d);
+  p.q = q_rows; p.k = k; p.v = v; p.o = o; p.d_o = d_o_rows; p.d_q = d_q;
+  p.lse = const_cast<float*>(lse);
+  p.delta = row_stats;
+  p.nlse2 = row_stats + (int64_t)d->batch * d->n_q_heads * stat_rows;
+  p.stat_stride = (int)stat_rows;
+  p.stat_off = d->q_start;
+  p.gk = gk; p.gv = gv;
+  p.n_splits = splits_for(d);
+  p.Cpad = (d->chunk_len + 31) / 32 * 32;
+  p.part = reinterpret_cast<float*>(static_cast<char*>(ws) + delta_bytes(d));
+  p.tail_part = tail_part_bytes(d) ? p.part : nullptr;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if ((rc = launch_dq_bf16(p, nullptr, s))) return rc;
+  // dK/dV: the query rows are the chunk's and the later ones, the cache rows the chunk's own
+  AttnParams pr = p;
+  pr.C = (int)rows;
+  SegTable seg;
+  std::memset(&seg, 0, sizeof(seg));
+  seg.n = 1;
+  seg.col_begin[0] = d->q_start;
+  seg.col_end[0] = d->q_start + d->chunk_len;
+  seg.weight[0] = 1.f;
+  seg.tile_begin[1] = (d->chunk_len + kColTileBf16 - 1) / kColTileBf16;
+  return launch_dkdv_bf16(pr, seg, s);
+}
+
 }  // namespace
 }  // namespace seco
 
@@ -338,6 +392,14 @@ extern "C" int spaco_chunk_attn_bwd(const seco_desc* desc, const void* q, const 
   if (!chunk_weight_host) return SECO_ERR_NULL;
   return backward(desc, q, k_cache, v_cache, o, lse, d_o, d_q, gk, gv, chunk_weight_host, nullptr, n_chunks,
                   weight_chunk_len, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int seco_chunk_attn_bwd_gather(const seco_desc* desc, const void* q_rows, const void* k_cache,
+                                          const void* v_cache, const void* o, const float* lse, const void* d_o_rows,
+                                          void* d_q, float* gk, float* gv, float* row_stats, int64_t stat_rows,
+                                          int32_t n_later_rows, void* ws, size_t ws_bytes, void* hip_stream) {
+  return backward_gather(desc, q_rows, k_cache, v_cache, o, lse, d_o_rows, d_q, gk, gv, row_stats, stat_rows,
+                         n_later_rows, ws, ws_bytes, hip_stream);
 }
 
 extern "C" int spaco_chunk_attn_bwd_sparse_dq(const seco_desc* desc, const void* q, const void* k_cache,

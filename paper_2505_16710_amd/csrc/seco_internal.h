@@ -16,8 +16,10 @@ struct AttnParams {
   void* o_out;
   void* d_q;
   float* lse;        // [B, Hq, C] contiguous
-  float* delta;      // [B, Hq, C] contiguous (workspace), backward only: rowsum(dO * O); NEGATED on the bf16 path
-  float* nlse2;      // bf16 backward: -LSE * log2(e), [B, Hq, C] (workspace), written by the dQ kernel for the dK/dV kernel
+  float* delta;      // [B, Hq, stat_stride], backward only: rowsum(dO * O); NEGATED on the bf16 path
+  float* nlse2;      // bf16 backward: -LSE * log2(e), [B, Hq, stat_stride], written by the dQ kernel for the dK/dV kernel
+  int stat_stride;   // rows per (batch, head) of delta / nlse2: C (workspace of one call), or the length of
+  int stat_off;      // arrays kept for the whole sequence, in which this call's first query row sits at stat_off
   float* gk;
   float* gv;
   float* part;       // split path: partial O (forward) or partial dQ (backward), fp32 [n_splits, B, Hq, C, D]

@@ -282,3 +282,24 @@ def test_device_info_rejects_null_and_reports_or_fails_cleanly():
         assert cus.value > 0 and khz.value > 0
     else:                             # no device: a status, and the outputs are left alone
         assert rc == -9 and (cus.value, khz.value) == (-7, -7)
+
+
+def test_gather_backward_validates_its_arguments():
+    """seco_chunk_attn_bwd_gather: bf16 only, row counts and the row-statistics length are checked before anything
+    is enqueued (no GPU needed: every call here fails validation)."""
+    lib = B.load_library()
+    d = desc(dtype=B.SECO_BF16, head_dim=128, n_q_heads=4, n_kv_heads=2, chunk_len=256, q_start=512)
+    p = C.c_void_p(4096)
+    ws = C.c_void_p(1 << 20)
+    n_ws = lib.seco_workspace_bytes(C.byref(d), B.SECO_OP_BWD)
+
+    def call(dd=d, stat_rows=1024, later=256, stats=p, ws_bytes=n_ws):
+        return lib.seco_chunk_attn_bwd_gather(C.byref(dd), p, p, p, p, p, p, p, p, p, stats, stat_rows, later, ws,
+                                              ws_bytes, None)
+
+    assert call(dd=desc(dtype=B.SECO_F32, head_dim=64, chunk_len=256, q_start=512)) == -4      # fp32: not provided
+    assert call(stats=None) == -1
+    assert call(later=-1) == -8
+    assert call(stat_rows=1020) == -8          # shorter than q_start + chunk_len + later rows
+    assert call(stat_rows=1026) == -8          # not a multiple of 4
+    assert call(ws_bytes=n_ws - 1) == -6

@@ -279,6 +279,43 @@ def test_one_call_against_a_cache_of_a_million_rows():
         assert max_rel(to_host(gk)[:, :, rows], dk_w) <= 2e-2 and max_rel(to_host(gv)[:, :, rows], dv_w) <= 2e-2
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,N,C", [
+    (1, 4, 1, 512, 256),      # aligned, G = 4
+    (2, 4, 2, 640, 256),      # short last chunk
+    (1, 2, 2, 700, 200),      # nothing aligned to the tiles
+    (1, 8, 2, 4096, 1024),    # every column tile divided among the four query heads of its group
+    (3, 4, 4, 1536, 512),     # G = 1: nothing to divide
+])
+def test_transposed_backward_order_gives_the_same_layer_gradients(B, Hq, Hkv, N, C):
+    """seco_chunk_attn_bwd_gather for every chunk in descending order, each call with all later rows: the finished
+    gK/gV and dQ of Alg. 1's second loop, against the same oracle as the accumulating order; and bit-identical reruns."""
+    x = small_layer(55, B, Hq, Hkv, N, 128, "bf16")
+    s = 1 / np.sqrt(128)
+    q, k, v, do = (to_dev(x[n], "bf16") for n in ("q", "k", "v", "do"))
+    stat_rows = (N + 3) // 4 * 4
+
+    def layer():
+        o, dq = torch.empty_like(q), torch.empty_like(q)
+        lse_all = torch.empty(B, Hq, N, device=DEV)
+        gk = torch.zeros(B, Hkv, N, 128, device=DEV)
+        gv = torch.zeros_like(gk)
+        stats = torch.full((2, B, Hq, stat_rows), float("nan"), device=DEV)   # every entry is written before it is read
+        for s0 in range((N - 1) // C * C, -1, -C):
+            c = min(C, N - s0)
+            oc, lse = seco.seco_chunk_attn_fwd(q[:, :, s0:s0 + c], k, v, s0, s, o=o[:, :, s0:s0 + c])
+            lse_all[:, :, s0:s0 + c] = lse
+            seco.seco_chunk_attn_bwd_gather(q[:, :, s0:], k, v, oc, lse, do[:, :, s0:], gk, gv, s0, s, c, stats,
+                                            d_q=dq[:, :, s0:s0 + c])
+        torch.cuda.synchronize()
+        return {"o": to_host(o), "lse": to_host(lse_all), "dq": to_host(dq), "gk": to_host(gk), "gv": to_host(gv)}
+
+    got = layer()
+    ref = A.seco_layer(x["q"], x["k"], x["v"], x["do"], C, s)
+    check(got, ref, "bf16", f"transposed order {B,Hq,Hkv,N,C}")
+    again = layer()
+    assert np.array_equal(got["gk"], again["gk"]) and np.array_equal(got["gv"], again["gv"])
+
+
 def _device_group(cfg, b, kvh):
     """One (batch, KV head) unit of a configuration as a G-head layer: host dict + fp64 views."""
     grp = kv_group(cfg, b, kvh)
