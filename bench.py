@@ -49,6 +49,9 @@ def main():
                          "report their GB/s against the 8 TB/s HBM peak")
     ap.add_argument("--schedules", action="store_true",
                     help="also time a whole layer of --config under Alg. 1 and Alg. 2 (needs a config with spaco_t)")
+    ap.add_argument("--transposed-order", action="store_true",
+                    help="also time the step with the backward calls in the transposed order "
+                         "(seco_chunk_attn_bwd_gather) and report it as transposed_backward_order")
     ap.add_argument("--context-scaling", action="store_true",
                     help="also time the backward loop of Alg. 2 (t = 8 selected chunks of 2048 tokens, evenly spaced) at "
                          "16K, 32K and 64K tokens, split into its dQ and dK/dV kernels: the paper's claim that the "
@@ -396,7 +399,7 @@ def main():
                 "dkdv_ms_per_step": round(prof_t["dkdv"][0], 4), "dq_ms_per_step": round(prof_t["dq"][0], 4),
                 "fwd_ms_per_step": round(prof_t["fwd"][0], 4)}
 
-    if cfg.dtype == "bf16" and N % C == 0 and not args.graph:
+    if args.transposed_order and cfg.dtype == "bf16" and N % C == 0 and not args.graph:
         out["transposed_backward_order"] = transposed_order()
 
     def context_scaling():
