@@ -303,3 +303,31 @@ def test_gather_backward_validates_its_arguments():
     assert call(stat_rows=1020) == -8          # shorter than q_start + chunk_len + later rows
     assert call(stat_rows=1026) == -8          # not a multiple of 4
     assert call(ws_bytes=n_ws - 1) == -6
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/seco.h compiles as C99 with warnings as errors, and a C program that takes the address of every
+    declared function links against libseco_hip.so (no C++ or torch types at the boundary) and runs its host-only
+    calls."""
+    import subprocess
+    header = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    names = sorted(set(re.findall(r"\b((?:seco|spaco|kvgrad|kv|rope)_\w+)\s*\(", open(os.path.join(header, "seco.h")).read())))
+    assert len(names) >= 25
+    src = tmp_path / "abi.c"
+    src.write_text('#include <stdio.h>\n#include "seco.h"\nint main(void) {\n  void* f[] = {'
+                   + ", ".join(f"(void*){n}" for n in names)
+                   + '};\n  int32_t sel[3]; float w[6];\n'
+                     '  if (spaco_select_chunks(1, 2, 8, 3, sel) != SECO_OK) return 1;\n'
+                     '  if (!(sel[0] > sel[1] && sel[1] > sel[2] && sel[2] >= 0 && sel[0] < 8)) return 2;\n'
+                     '  if (spaco_chunk_weights(sel, 3, 5, 2.0f, w) != SECO_OK) return 3;\n'
+                     '  if (spaco_compensation_factor(32, 8, 2.0f) != 2.0f) return 4;\n'
+                     '  printf("%d %s\\n", (int)(sizeof f / sizeof f[0]), seco_strerror(SECO_ERR_WORKSPACE));\n  return 0;\n}\n')
+    exe = tmp_path / "abi"
+    lib_dir = os.path.dirname(B.library_path())
+    r = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-Wno-pedantic", "-I", header,
+                        str(src), "-o", str(exe), "-L", lib_dir, "-l:libseco_hip.so", f"-Wl,-rpath,{lib_dir}"],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stderr)
+    assert r.stdout.split()[0] == str(len(names))
