@@ -62,6 +62,7 @@ CONFIGS = {
     "small_c256": Config("small_c256", "bf16", 1, 32, 8, 128, 16384, 256, seed=5, spaco_t=8),
     "small_c512": Config("small_c512", "bf16", 1, 32, 8, 128, 16384, 512, seed=5, spaco_t=8),
     # longer contexts than the paper trains on (its limit is 16K tokens on 24 GB), chunks sized for this GPU
+    "cfg2_b2": Config("cfg2_b2", "bf16", 2, 32, 8, 128, 16384, 1024, seed=1),   # cfg2 with two sequences per call
     "long_128k": Config("long_128k", "bf16", 1, 32, 8, 128, 131072, 4096, seed=6, spaco_t=8),
     "long_256k": Config("long_256k", "bf16", 1, 32, 8, 128, 262144, 8192, seed=6, spaco_t=8),
 }
