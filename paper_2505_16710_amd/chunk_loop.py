@@ -13,7 +13,7 @@ The projections, norms, MLP and loss around the attention are ordinary PyTorch G
 (library GEMMs); only one chunk's graph is alive at a time, as in the paper.  There is no CPU path.
 
 Model (fixed here so that a checker can build the same function): pre-norm decoder, RMSNorm with
-eps 1e-6, grouped-query causal attention without positional encoding, MLP x + silu(h W1) W2, final
+eps 1e-6, grouped-query causal attention (optionally with rotary position embedding), MLP x + silu(h W1) W2, final
 RMSNorm, linear head, cross-entropy summed over tokens.  Parameter names: emb, head, norm_f and
 l{i}.norm1, l{i}.norm2, l{i}.wq, l{i}.wk, l{i}.wv, l{i}.wo, l{i}.w1, l{i}.w2, all stored [in, out].
 """
@@ -34,6 +34,14 @@ class LayerState:
         self.gk = torch.empty(B, Hkv, N, D, dtype=torch.float32, device=device)
         self.gv = torch.empty_like(self.gk)
         self.kept = {}      # q_start -> (O, LSE) of stage 1, when attention outputs are kept for stage 2
+        self.gather = None  # transposed backward order: (Q of the layer, dO of the layer, row statistics)
+
+    def enable_gather(self, B, Hq, N, D, dtype, device):
+        """Buffers of the transposed backward order: the layer's Q, dO, O and dQ over the whole sequence,
+        [B, Hq, N, D] each (a call takes row ranges of them, so all share one set of strides), and the per-row
+        statistics the dK/dV kernel reads, fp32 [2, B, Hq, N rounded up to 4]."""
+        self.gather = tuple(torch.empty(B, Hq, N, D, dtype=dtype, device=device) for _ in range(4)) + (
+            torch.empty(2, B, Hq, (N + 3) // 4 * 4, dtype=torch.float32, device=device),)
 
 
 class ChunkAttention(torch.autograd.Function):
@@ -69,7 +77,17 @@ class ChunkAttention(torch.autograd.Function):
         q, o, lse = ctx.saved_tensors
         st, s0, C = ctx.state, ctx.q_start, q.shape[2]
         d_o = d_o.contiguous()
-        if ctx.weights is None and ctx.dq_weights is None:
+        if st.gather is not None:
+            # transposed order (Alg. 1 only): this chunk's finished gK/gV rows from its own and every later chunk's
+            # query rows, whose Q and dO the layer has kept; nothing is added to earlier rows
+            q_all, do_all, o_all, dq_all, stats = st.gather
+            q_all[:, :, s0:s0 + C] = q
+            do_all[:, :, s0:s0 + C] = d_o
+            o_all[:, :, s0:s0 + C] = o
+            d_q = _b.seco_chunk_attn_bwd_gather(q_all[:, :, s0:], st.k, st.v, o_all[:, :, s0:s0 + C], lse,
+                                                do_all[:, :, s0:], st.gk, st.gv, s0, ctx.scale, C, stats,
+                                                d_q=dq_all[:, :, s0:s0 + C]).contiguous()
+        elif ctx.weights is None and ctx.dq_weights is None:
             d_q = _b.seco_chunk_attn_bwd(q, st.k, st.v, o, lse, d_o, st.gk, st.gv, s0, ctx.scale)
         else:
             n_chunks = len(ctx.dq_weights) if ctx.weights is None else len(ctx.weights)
@@ -127,7 +145,7 @@ class ChunkedDecoder:
         return F.cross_entropy(logits.reshape(B * C, -1).float(), targets.reshape(B * C), reduction="sum")
 
     def step(self, tokens, targets, chunk_len, selected=None, factor=1.0, keep_attention_outputs=False,
-             stage1_chunk_len=None, dq_weights=None):
+             stage1_chunk_len=None, dq_weights=None, transposed_backward=False):
         """One SeCO step (selected is None: Alg. 1) or SpaCO step (Alg. 2, `selected` chunk indices,
         relay factor `factor`).  Returns (sum of the chunk losses from stage 1, {name: gradient}).
 
@@ -142,12 +160,19 @@ class ChunkedDecoder:
         dq_weights: optional callable (chunk j, layer l) -> one non-negative weight per chunk 0..j (or None): the dQ
         of that attention call visits only the chunks with a non-zero weight and scales their terms
         (spaco_chunk_attn_bwd_sparse_dq; not part of the paper).  For unbiased gradients the weights must have
-        expectation 1 and be drawn independently for every layer of a call."""
+        expectation 1 and be drawn independently for every layer of a call.
+        transposed_backward: Alg. 1 with the attention backward in the transposed order (seco_chunk_attn_bwd_gather;
+        bf16 parameters, no selection): same gradients up to the order of summation."""
         p = self.p
         B, N = tokens.shape
         dtype, dev = p["emb"].dtype, p["emb"].device
         starts = list(range(0, N, chunk_len))
         states = [LayerState(B, self.Hkv, N, self.D, dtype, dev) for _ in range(self.n_layers)]
+        if transposed_backward:
+            if selected is not None or dq_weights is not None or dtype != torch.bfloat16:
+                raise ValueError("the transposed backward order is for Alg. 1 (no selection) with bf16 parameters")
+            for st in states:
+                st.enable_gather(B, self.Hq, N, self.D, dtype, dev)
         for t in p.values():
             t.grad = None
         total = torch.zeros((), dtype=torch.float32, device=dev)

@@ -147,3 +147,20 @@ def test_step_with_rotary_embedding_matches_oracle(dtype, base_cfg, tol):
     _, g_ref = om.spaco_grads(cfg, p64, tok, tgt, C, sel, f)
     _, g = dec.step(tok.to(DEV), tgt.to(DEV), C, selected=sel, factor=f)
     _compare(g_ref, g, tol)
+
+
+def test_seco_step_with_the_transposed_backward_order_matches_whole_sequence_training():
+    """Alg. 1 with every layer's attention backward in the transposed order (seco_chunk_attn_bwd_gather): parameter
+    gradients against ordinary whole-sequence training, ragged last chunk included, and against the accumulating
+    order to rounding."""
+    cfg, tol = BF16_CFG, 6e-2
+    N, C = 448, 128
+    p64, dec, tok, tgt = _setup(cfg, 19, 2, N, torch.bfloat16)
+    _, g_ref = om.monolithic_grads(cfg, p64, tok, tgt)
+    loss_t, g_t = dec.step(tok.to(DEV), tgt.to(DEV), C, transposed_backward=True)
+    _compare(g_ref, g_t, tol)
+    loss_a, g_a = dec.step(tok.to(DEV), tgt.to(DEV), C)
+    assert loss_t == loss_a
+    for n in g_a:
+        d = (g_t[n].float() - g_a[n].float()).abs().max() / g_a[n].float().abs().max()
+        assert float(d) < 2e-2, (n, float(d))
