@@ -336,6 +336,26 @@ def main():
             for j in sel:
                 Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam), seco.spaco_chunk_weights(sel, j, lam_q))
 
+        stats_t = torch.empty(2, B, Hq, (cx.seq_len + 3) // 4 * 4, device=dev, dtype=torch.float32)
+
+        def gather_bwd(j, row_weight=None):
+            seco.seco_chunk_attn_bwd_gather(Lx.q[:, :, j * Lx.C:], Lx.kc, Lx.vc, Lx.rows(Lx.o, j), Lx.lse[j],
+                                            Lx.do[:, :, j * Lx.C:], Lx.gk, Lx.gv, j * Lx.C, scale, Lx.C, stats_t,
+                                            d_q=Lx.rows(Lx.dq, j), ws=Lx.ws, row_weight=row_weight,
+                                            weight_chunk_len=Lx.C)
+
+        def seco_layer_transposed():    # whole-sequence stage 1, kept outputs, backward calls in the transposed order
+            prefill_stage1()
+            seco.kvgrad_zero(Lx.gk, Lx.gv)
+            for j in range(kx - 1, -1, -1):
+                gather_bwd(j)
+
+        def spaco_layer_transposed():
+            prefill_stage1()
+            seco.kvgrad_zero(Lx.gk, Lx.gv)
+            for j in sel:
+                gather_bwd(j, [1.0 if i == j else (lam if i in sel else 0.0) for i in range(j, kx)])
+
         def spaco_percall_layer():      # every chunk back-propagated, each call with its own draw of t earlier chunks
             for j in range(kx):
                 Lx.fwd(j)
@@ -355,6 +375,8 @@ def main():
                          ("seco_prefill_kept_outputs", seco_layer_prefill_kept),
                          (f"spaco_t{tx}_prefill_kept_outputs", spaco_layer_prefill_kept),
                          (f"spaco_t{tx}_prefill_kept_outputs_sparse_dq", spaco_layer_sparse_dq),
+                         ("seco_prefill_kept_outputs_transposed", seco_layer_transposed),
+                         (f"spaco_t{tx}_prefill_kept_outputs_transposed", spaco_layer_transposed),
                          (f"spaco_percall_t{tx}", spaco_percall_layer),
                          (f"spaco_last_call_t{tx}", spaco_last_call)):
             fn()

@@ -63,7 +63,7 @@ typedef enum seco_status {
 typedef enum seco_op {
   SECO_OP_FWD = 0,
   SECO_OP_BWD = 1            /* seco_chunk_attn_bwd, spaco_chunk_attn_bwd, spaco_chunk_attn_bwd_sparse_dq,
-                                seco_chunk_attn_bwd_gather */
+                                seco_chunk_attn_bwd_gather, spaco_chunk_attn_bwd_gather */
 } seco_op;
 
 /* One chunk call.  kv_len = q_start + chunk_len cache rows are visible. */
@@ -187,6 +187,27 @@ int seco_chunk_attn_bwd_gather(const seco_desc* desc, const void* q_rows, const 
                                const void* o, const float* lse, const void* d_o_rows,
                                void* d_q, float* gk, float* gv, float* row_stats, int64_t stat_rows,
                                int32_t n_later_rows, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * seco_chunk_attn_bwd_gather with a weight per chunk of query rows: the SpaCO backward (Alg. 2) in the transposed
+ * order.  The rows handed in are divided into chunks of weight_chunk_len rows counted from the call's first row
+ * (chunk 0: the call's own rows when weight_chunk_len = chunk_len); the contribution of chunk m's query rows to the
+ * call's gK/gV rows is multiplied by row_weight_host[m], and chunks of weight 0 are not read.  With the paper's
+ * policy the selected chunk i is called with weight 1 on its own rows, k/t on the later selected chunks and 0 on the
+ * others, which gives the gK/gV rows that spaco_chunk_attn_bwd calls for the same selection leave there.
+ *   row_weight_host  HOST array of n_row_chunks finite, non-negative floats, read before the call returns
+ *   weight_chunk_len a multiple of 64; n_row_chunks * weight_chunk_len >= chunk_len + n_later_rows and
+ *                    (n_row_chunks - 1) * weight_chunk_len < that (SECO_ERR_WEIGHTS otherwise); at most 24 runs
+ *                    of consecutive chunks with equal non-zero weight (SECO_ERR_TOO_LARGE beyond)
+ * dQ is exact, as in spaco_chunk_attn_bwd; every other argument as seco_chunk_attn_bwd_gather.  The row statistics
+ * of a later chunk must have been written by that chunk's own call: chunks with non-zero weight are chunks that
+ * were called.
+ */
+int spaco_chunk_attn_bwd_gather(const seco_desc* desc, const void* q_rows, const void* k_cache, const void* v_cache,
+                                const void* o, const float* lse, const void* d_o_rows,
+                                void* d_q, float* gk, float* gv, float* row_stats, int64_t stat_rows,
+                                int32_t n_later_rows, const float* row_weight_host, int32_t n_row_chunks,
+                                int32_t weight_chunk_len, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
  * Zero rows [row_begin, row_end) of the KV gradient buffers (start of a training iteration;

@@ -57,6 +57,9 @@ def load_library():
     lib.spaco_chunk_attn_bwd_sparse_dq.restype = C.c_int
     lib.seco_chunk_attn_bwd_gather.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp, fp, fp, fp, i64, i32, vp, sz, vp]
     lib.seco_chunk_attn_bwd_gather.restype = C.c_int
+    lib.spaco_chunk_attn_bwd_gather.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp, fp, fp, fp, i64, i32,
+                                                C.POINTER(C.c_float), i32, i32, vp, sz, vp]
+    lib.spaco_chunk_attn_bwd_gather.restype = C.c_int
     lib.kvgrad_zero.argtypes = [dp, fp, fp, i64, i64, vp]
     lib.kvgrad_accumulate.argtypes = [dp, fp, fp, fp, fp, C.c_float, i64, i64, vp]
     lib.kv_append.argtypes = [dp, vp, vp, vp, vp, vp]
@@ -227,10 +230,12 @@ def spaco_chunk_attn_bwd(q, k_cache, v_cache, o, lse, d_o, gk, gv, q_start, scal
 
 
 def seco_chunk_attn_bwd_gather(q_rows, k_cache, v_cache, o, lse, d_o_rows, gk, gv, q_start, scale, chunk_len,
-                               row_stats, d_q=None, ws=None, stream=None):
+                               row_stats, d_q=None, ws=None, stream=None, row_weight=None, weight_chunk_len=None):
     """Backward of one chunk in the transposed order: dQ of the chunk's first `chunk_len` rows of q_rows, and the
     chunk's own gK/gV rows from all of q_rows / d_o_rows (the chunk's rows followed by every later row).
-    row_stats: fp32 [2, B, Hq, stat_rows] kept by the caller over the whole backward pass."""
+    row_stats: fp32 [2, B, Hq, stat_rows] kept by the caller over the whole backward pass.
+    row_weight (host floats, one per chunk of weight_chunk_len rows counted from the call's first row; default
+    chunk_len): the call is spaco_chunk_attn_bwd_gather."""
     import torch
     lib = load_library()
     qc, doc = q_rows[:, :, :chunk_len], d_o_rows[:, :, :chunk_len]
@@ -243,6 +248,16 @@ def seco_chunk_attn_bwd_gather(q_rows, k_cache, v_cache, o, lse, d_o_rows, gk, g
     d = make_desc(qc, k_cache, q_start, scale, o=o, g=gk)
     if ws is None:
         ws, _ = _workspace(d, SECO_OP_BWD, qc)
+    if row_weight is not None:
+        n = len(row_weight)
+        w = (C.c_float * n)(*[float(x) for x in row_weight])
+        _check(lib.spaco_chunk_attn_bwd_gather(C.byref(d), _ptr(q_rows), _ptr(k_cache), _ptr(v_cache), _ptr(o),
+                                               _ptr(lse), _ptr(d_o_rows), _ptr(d_q), _ptr(gk), _ptr(gv), _ptr(row_stats),
+                                               int(row_stats.shape[3]), int(q_rows.shape[2] - chunk_len), w, n,
+                                               int(weight_chunk_len or chunk_len), _ptr(ws),
+                                               ws.numel() * ws.element_size(), _stream(stream)),
+               "spaco_chunk_attn_bwd_gather")
+        return d_q
     _check(lib.seco_chunk_attn_bwd_gather(C.byref(d), _ptr(q_rows), _ptr(k_cache), _ptr(v_cache), _ptr(o), _ptr(lse),
                                           _ptr(d_o_rows), _ptr(d_q), _ptr(gk), _ptr(gv), _ptr(row_stats),
                                           int(row_stats.shape[3]), int(q_rows.shape[2] - chunk_len), _ptr(ws),

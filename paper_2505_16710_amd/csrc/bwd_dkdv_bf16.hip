@@ -68,9 +68,11 @@ struct TailSplit {
 };
 
 // (RB is fixed to 2 by the hand-pipelined main loop.)
-template <int NCB, int RB>
+// ROWS: the query rows are taken from a table of runs (rows relative to p.q_start, each run with one weight whose
+// log2 is added to -LSE, i.e. its probabilities are scaled by the weight) instead of being all p.C rows with weight 1.
+template <int NCB, int RB, bool ROWS>
 __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, SegTable seg, TailSplit ts,
-                                                                  int total_items) {
+                                                                  RowRuns rr, int total_items) {
   using Cfg = DkdvCfg<NCB, RB>;
   constexpr int BQ = Cfg::kBQ, kTileBytes = Cfg::kTileBytes, kStageBytes = Cfg::kStageBytes;
   constexpr int NW = 2 * NCB;                 // wavefronts
@@ -123,12 +125,31 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 
   // query-row stages that see at least one cache row of this workgroup; iteration = (head of the group, stage)
   const int rt0 = max(0, c0 - p.q_start) / BQ;
-  const int n_rt = (p.C + BQ - 1) / BQ - rt0;
+  struct Pos { int hg, r0, ri; };   // head within the group, first chunk-local row of the stage, run of rows
+  // first stage of a head, and the number of stages per head
+  int first_ri = 0, first_r0 = rt0 * BQ, n_rt;
+  if constexpr (ROWS) {
+    while (first_ri + 1 < rr.n && rr.end[first_ri] <= first_r0) ++first_ri;
+    first_r0 = max(first_r0, rr.begin[first_ri]);
+    n_rt = (rr.end[first_ri] - first_r0 + BQ - 1) / BQ;
+    for (int i = first_ri + 1; i < rr.n; ++i) n_rt += (rr.end[i] - rr.begin[i] + BQ - 1) / BQ;
+    n_rt = max(n_rt, 0);
+  } else {
+    n_rt = (p.C + BQ - 1) / BQ - rt0;
+  }
   const int n_iter = n_rt * n_heads;
-  struct Pos { int hg, r0; };   // head within the group, first chunk-local row of the stage
+  // rows [x.r0, row_limit(x)) of a stage exist; the others are masked
+  auto row_limit = [&](Pos x) { return ROWS ? rr.end[x.ri] : p.C; };
   auto advance = [&](Pos x) {
     x.r0 += BQ;
-    if (x.r0 >= p.C) { x.r0 = rt0 * BQ; x.hg += 1; }
+    if constexpr (ROWS) {
+      if (x.r0 >= rr.end[x.ri]) {
+        if (++x.ri == rr.n) { x.ri = first_ri; x.r0 = first_r0; x.hg += 1; }
+        else x.r0 = rr.begin[x.ri];
+      }
+    } else {
+      if (x.r0 >= p.C) { x.r0 = first_r0; x.hg += 1; }
+    }
     return x;
   };
 
@@ -146,7 +167,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   }
   const uint32_t lds_wave = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + wave * 4 * kRowBytes);
   auto copy_stage = [&](Pos x, int slot) {
-    if (x.r0 + BQ <= p.C) {
+    if (x.r0 + BQ <= row_limit(x)) {
       const __bf16* q_src = qbase + x.hg * p.qs[1] + (int64_t)x.r0 * p.qs[2];
       const __bf16* do_src = dobase + x.hg * p.os[1] + (int64_t)x.r0 * p.os[2];
 #pragma unroll
@@ -173,7 +194,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const uint32_t lds_stat = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + 2 * kTileBytes + (wave & 1) * BQ * 4);
   auto copy_stat = [&](Pos x, int slot) {
-    if (x.r0 + BQ <= p.C) {
+    if (x.r0 + BQ <= row_limit(x)) {
       if (wave_u < 2) {
         const uint64_t a = (uint64_t)(uintptr_t)((wave_u == 0 ? p.nlse2 : p.delta) + stat_base + (int64_t)x.hg * p.stat_stride + x.r0);
         // (wavefront-uniform by construction; the halves go through readfirstlane so that the compiler keeps them
@@ -186,9 +207,9 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
                      : "memory", "m0");
       }
     } else if (wave_u < 2) {             // (wavefront-uniform control flow only: the copies above need scalar addresses)
-      const int rr = x.r0 + lane;
-      const float v = (wave_u == 0 ? p.nlse2 : p.delta)[stat_base + (int64_t)x.hg * p.stat_stride + min(rr, p.C - 1)];
-      const float stat = wave_u == 0 && rr >= p.C ? -INFINITY : v;
+      const int row = x.r0 + lane;
+      const float v = (wave_u == 0 ? p.nlse2 : p.delta)[stat_base + (int64_t)x.hg * p.stat_stride + min(row, p.C - 1)];
+      const float stat = wave_u == 0 && row >= row_limit(x) ? -INFINITY : v;
       *reinterpret_cast<SECO_LDS float*>(smem + slot * kStageBytes + 2 * kTileBytes + (wave_u * BQ + lane) * 4) = stat;
     }
   };
@@ -222,7 +243,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 
   // role A: S = Q K^T for row block rb of the stage in `slot`, P = exp2(S*c - LSE) with the causal mask;
   // P goes to pbuf as two operand halves (lane-contiguous 16-byte words)
-  auto scores = [&](int slot, int parity, int r0, int rb) {
+  auto scores = [&](int slot, int parity, int r0, int rb, float lw) {   // lw: log2 of the rows' weight
     lds_char* qt = smem + slot * kStageBytes;
     SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + 32 * rb;
     bf16x8 a[8];
@@ -231,6 +252,10 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     f32x16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = lse_s[8 * (r >> 2) + 4 * g + (r & 3)];
+    if constexpr (ROWS) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] += lw;
+    }
 #pragma unroll
     for (int t = 0; t < 8; ++t) s = mfma(a[t], frag[t], s);
 #pragma unroll
@@ -241,7 +266,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 + lane * 16) = pack8(s, 1);
   };
 
-  Pos cur{head0, rt0 * BQ};
+  Pos cur{head0, first_r0, first_ri};
   Pos nxt = advance(cur);
   copy_stage(cur, 0);
   copy_stat(cur, 0);
@@ -255,7 +280,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   __syncthreads();
   if (role == 0) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) scores(0, 0, cur.r0, rb);
+    for (int rb = 0; rb < RB; ++rb) scores(0, 0, cur.r0, rb, ROWS ? rr.log2w[cur.ri] : 0.f);
   }
   __syncthreads();
   Pos nxt2 = advance(nxt);
@@ -311,6 +336,14 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       for (int r = 0; r < 16; ++r) s0[r] = lse_s[8 * (r >> 2) + 4 * g + (r & 3)];
 #pragma unroll
       for (int r = 0; r < 16; ++r) s1[r] = lse_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
+      if constexpr (ROWS) {                   // probabilities of the next stage's rows carry their run's weight
+        const float lw = rr.log2w[nxt.ri];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          s0[r] += lw;
+          s1[r] += lw;
+        }
+      }
       // log2 P of row block 0 (chain started from -LSE); Q rows of row block 1 come in behind
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
@@ -473,24 +506,29 @@ __global__ __launch_bounds__(256) void dkdv_tail_merge_kernel(AttnParams p, SegT
 
 }  // namespace
 
-template <int NCB, int RB>
-int launch_cfg(const AttnParams& p, const SegTable& seg, hipStream_t s) {
+template <int NCB, int RB, bool ROWS>
+int launch_cfg(const AttnParams& p, const SegTable& seg, const RowRuns& rr, hipStream_t s) {
   using Cfg = DkdvCfg<NCB, RB>;
   const int n_units = p.Hkv * p.B, n_ctiles = seg.tile_begin[seg.n];
   TailSplit ts{0, 1, p.tail_part};
-  const TailPlan tp = tail_plan(n_units, n_ctiles, p.G, p.C);
+  int n_rows = p.C;
+  if (ROWS) {
+    n_rows = 0;
+    for (int i = 0; i < rr.n; ++i) n_rows += rr.end[i] - rr.begin[i];
+  }
+  const TailPlan tp = tail_plan(n_units, n_ctiles, p.G, n_rows);
   if (p.tail_part && tp.hs > 1) {
     ts.n_tiles = tp.n_tiles;
     ts.hs = tp.hs;
   }
   const int total = n_units * (n_ctiles - ts.n_tiles + ts.n_tiles * ts.hs);
-  auto kern = dkdv_bf16_kernel<NCB, RB>;
+  auto kern = dkdv_bf16_kernel<NCB, RB, ROWS>;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                           Cfg::kSmemBytes) != hipSuccess)
     return SECO_ERR_LAUNCH;
   {
     ProfScope prof(kKernelDkdv, s);   // the merge of the divided tiles counts as part of the dK/dV pass
-    hipLaunchKernelGGL(kern, dim3(xcd_grid(total)), dim3(Cfg::kThreads), Cfg::kSmemBytes, s, p, seg, ts, total);
+    hipLaunchKernelGGL(kern, dim3(xcd_grid(total)), dim3(Cfg::kThreads), Cfg::kSmemBytes, s, p, seg, ts, rr, total);
     if (ts.n_tiles > 0) {
       const int64_t threads = (int64_t)n_units * ts.n_tiles * 2 * (Cfg::kCols * 128 / 4);
       hipLaunchKernelGGL(dkdv_tail_merge_kernel<Cfg::kCols>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p,
@@ -502,7 +540,14 @@ int launch_cfg(const AttnParams& p, const SegTable& seg, hipStream_t s) {
 
 int launch_dkdv_bf16(const AttnParams& p, const SegTable& seg, hipStream_t s) {
   if (seg.tile_begin[seg.n] == 0) return SECO_OK;
-  return launch_cfg<kColTileBf16 / 32, SECO_DKDV_RB>(p, seg, s);
+  RowRuns none;
+  none.n = 0;
+  return launch_cfg<kColTileBf16 / 32, SECO_DKDV_RB, false>(p, seg, none, s);
+}
+
+int launch_dkdv_rows_bf16(const AttnParams& p, const SegTable& seg, const RowRuns& rr, hipStream_t s) {
+  if (seg.tile_begin[seg.n] == 0 || rr.n == 0) return SECO_OK;
+  return launch_cfg<kColTileBf16 / 32, SECO_DKDV_RB, true>(p, seg, rr, s);
 }
 
 }  // namespace seco

@@ -209,7 +209,8 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
 // the dQ kernels of their own calls left them).
 int backward_gather(const seco_desc* d, const void* q_rows, const void* k, const void* v, const void* o,
                     const float* lse, const void* d_o_rows, void* d_q, float* gk, float* gv, float* row_stats,
-                    int64_t stat_rows, int32_t n_later_rows, void* ws, size_t ws_bytes, void* stream) {
+                    int64_t stat_rows, int32_t n_later_rows, const float* w, int32_t n_w, int32_t wlen, void* ws,
+                    size_t ws_bytes, void* stream) {
   int rc = check_fwd_like(d);
   if (rc) return rc;
   if (d->dtype != SECO_BF16) return SECO_ERR_DTYPE;
@@ -225,6 +226,30 @@ int backward_gather(const seco_desc* d, const void* q_rows, const void* k, const
   if ((int64_t)d->batch * d->n_q_heads * ((rows + 3) / 4) > (int64_t)1 << 31) return SECO_ERR_TOO_LARGE;
   if (stat_rows < last || stat_rows % 4 != 0) return SECO_ERR_RANGE;
   if (stat_rows > (int64_t)1 << 30) return SECO_ERR_TOO_LARGE;
+  // runs of query rows with one non-zero weight (weights given per chunk of wlen rows, counted from the call's
+  // first row); without weights every row counts once
+  RowRuns rr;
+  std::memset(&rr, 0, sizeof(rr));
+  if (w) {
+    if (n_w < 1 || wlen < 1 || wlen % 64 != 0) return SECO_ERR_WEIGHTS;
+    if ((int64_t)n_w * wlen < rows || (int64_t)(n_w - 1) * wlen >= rows) return SECO_ERR_WEIGHTS;
+    for (int i = 0; i < n_w; ++i)
+      if (!std::isfinite(w[i]) || w[i] < 0.f) return SECO_ERR_WEIGHTS;
+    for (int i = 0; i < n_w; ++i) {
+      if (w[i] == 0.f) continue;
+      const int b = (int)((int64_t)i * wlen), e = (int)std::min<int64_t>((int64_t)(i + 1) * wlen, rows);
+      const float lw = std::log2(w[i]);
+      if (rr.n > 0 && rr.end[rr.n - 1] == b && rr.log2w[rr.n - 1] == lw) {
+        rr.end[rr.n - 1] = e;
+      } else {
+        if (rr.n == kMaxRowRuns) return SECO_ERR_TOO_LARGE;
+        rr.begin[rr.n] = b;
+        rr.end[rr.n] = e;
+        rr.log2w[rr.n] = lw;
+        ++rr.n;
+      }
+    }
+  }
   if (!ws || ws_bytes < delta_bytes(d) + bwd_part_bytes(d) || (reinterpret_cast<uintptr_t>(ws) & 255u))
     return SECO_ERR_WORKSPACE;
 
@@ -252,7 +277,7 @@ int backward_gather(const seco_desc* d, const void* q_rows, const void* k, const
   seg.col_end[0] = d->q_start + d->chunk_len;
   seg.weight[0] = 1.f;
   seg.tile_begin[1] = (d->chunk_len + kColTileBf16 - 1) / kColTileBf16;
-  return launch_dkdv_bf16(pr, seg, s);
+  return w ? launch_dkdv_rows_bf16(pr, seg, rr, s) : launch_dkdv_bf16(pr, seg, s);
 }
 
 }  // namespace
@@ -399,7 +424,17 @@ extern "C" int seco_chunk_attn_bwd_gather(const seco_desc* desc, const void* q_r
                                           void* d_q, float* gk, float* gv, float* row_stats, int64_t stat_rows,
                                           int32_t n_later_rows, void* ws, size_t ws_bytes, void* hip_stream) {
   return backward_gather(desc, q_rows, k_cache, v_cache, o, lse, d_o_rows, d_q, gk, gv, row_stats, stat_rows,
-                         n_later_rows, ws, ws_bytes, hip_stream);
+                         n_later_rows, nullptr, 0, 0, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int spaco_chunk_attn_bwd_gather(const seco_desc* desc, const void* q_rows, const void* k_cache,
+                                           const void* v_cache, const void* o, const float* lse, const void* d_o_rows,
+                                           void* d_q, float* gk, float* gv, float* row_stats, int64_t stat_rows,
+                                           int32_t n_later_rows, const float* row_weight_host, int32_t n_row_chunks,
+                                           int32_t weight_chunk_len, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!row_weight_host) return SECO_ERR_NULL;
+  return backward_gather(desc, q_rows, k_cache, v_cache, o, lse, d_o_rows, d_q, gk, gv, row_stats, stat_rows,
+                         n_later_rows, row_weight_host, n_row_chunks, weight_chunk_len, ws, ws_bytes, hip_stream);
 }
 
 extern "C" int spaco_chunk_attn_bwd_sparse_dq(const seco_desc* desc, const void* q, const void* k_cache,

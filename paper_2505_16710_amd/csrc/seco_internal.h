@@ -44,6 +44,17 @@ struct SegTable {
   int tile_begin[kMaxSegments + 1];  // prefix sum of column tiles, in units of the launcher's tile width
 };
 
+// Runs of query rows of the dK/dV pass in the transposed order: rows [begin, end) relative to the call's first
+// query row, begin a multiple of 64, ascending and disjoint; the probabilities of a run's rows are scaled by its
+// weight (log2w = log2 of the weight).  By value in the kernel arguments, like the column segments.
+constexpr int kMaxRowRuns = 24;
+struct RowRuns {
+  int n;
+  int begin[kMaxRowRuns];
+  int end[kMaxRowRuns];
+  float log2w[kMaxRowRuns];
+};
+
 // Split path of the bf16 forward and dQ kernels (short chunks): the rows of the G heads of a KV head are packed
 // into row tiles of 128, and the visible cache rows of a tile are divided among several workgroups.
 struct SplitPlan {
@@ -110,6 +121,8 @@ int launch_fwd4_split_bf16(const AttnParams& p, int n_mtiles, int total, hipStre
 // a positive weight (tile_begin is not used)
 int launch_dq_bf16(const AttnParams& p, const SegTable* dq_runs, hipStream_t s);
 int launch_dkdv_bf16(const AttnParams& p, const SegTable& seg, hipStream_t s);
+// the same with the query rows taken from runs (p.C: number of rows that may be addressed from p.q / p.d_o)
+int launch_dkdv_rows_bf16(const AttnParams& p, const SegTable& seg, const RowRuns& rr, hipStream_t s);
 #ifndef SECO_DKDV_COLS
 #define SECO_DKDV_COLS 128
 #endif

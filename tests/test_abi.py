@@ -331,3 +331,23 @@ def test_header_is_plain_c_and_links_against_the_library(tmp_path):
     r = subprocess.run([str(exe)], capture_output=True, text=True)
     assert r.returncode == 0, (r.returncode, r.stderr)
     assert r.stdout.split()[0] == str(len(names))
+
+
+def test_weighted_gather_backward_validates_its_weights():
+    lib = B.load_library()
+    d = desc(dtype=B.SECO_BF16, head_dim=128, n_q_heads=4, n_kv_heads=2, chunk_len=256, q_start=512)
+    p = C.c_void_p(4096)
+    ws = C.c_void_p(1 << 20)
+    n_ws = lib.seco_workspace_bytes(C.byref(d), B.SECO_OP_BWD)
+
+    def call(w, n=None, wlen=256, later=512):
+        arr = (C.c_float * len(w))(*w) if w is not None else None
+        return lib.spaco_chunk_attn_bwd_gather(C.byref(d), p, p, p, p, p, p, p, p, p, p, 4096, later, arr,
+                                               len(w) if n is None and w is not None else (n or 0), wlen, ws, n_ws, None)
+
+    assert call(None) == -1
+    assert call([1.0, 2.0, 0.0], wlen=200) == -7          # chunk length of the weights not a multiple of 64
+    assert call([1.0, 2.0]) == -7                          # does not cover the 768 rows handed in
+    assert call([1.0, 2.0, 0.0, 1.0]) == -7                # covers more chunks than there are rows
+    assert call([1.0, -2.0, 0.0]) == -7 and call([1.0, float("nan"), 0.0]) == -7
+    assert call([1.0 + i % 2 for i in range(50)], wlen=64, later=50 * 64 - 256) == -10   # more than 24 runs

@@ -316,6 +316,46 @@ def test_transposed_backward_order_gives_the_same_layer_gradients(B, Hq, Hkv, N,
     assert np.array_equal(got["gk"], again["gk"]) and np.array_equal(got["gv"], again["gv"])
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,N,C,sel", [
+    (1, 4, 2, 1024, 128, [7, 5, 4, 1]),     # runs of one and of two selected chunks, gaps between them
+    (2, 4, 1, 1100, 128, [8, 6, 3, 2, 0]),  # the last chunk is short (76 rows) and selected
+    (1, 8, 2, 4096, 1024, [3, 2, 0]),       # column tiles divided among the query heads
+    (1, 2, 2, 768, 192, [3, 1]),            # chunk length a multiple of 64 but not of the 128-row column tile
+])
+def test_spaco_in_the_transposed_order(B, Hq, Hkv, N, C, sel):
+    """Alg. 2 with the backward calls in the transposed order: the call of a selected chunk gathers from its own
+    rows (weight 1) and from the later selected chunks (factor k/t); rows of unselected chunks are never read (their
+    row statistics stay NaN here).  Same oracle and bars as the accumulating order."""
+    x = small_layer(56, B, Hq, Hkv, N, 128, "bf16")
+    s = 1 / np.sqrt(128)
+    k_chunks = -(-N // C)
+    lam = float(np.float32(k_chunks / len(sel)))
+    q, k, v, do = (to_dev(x[n], "bf16") for n in ("q", "k", "v", "do"))
+    o, dq = torch.zeros_like(q), torch.zeros_like(q)
+    lse_all = torch.zeros(B, Hq, N, device=DEV)
+    gk = torch.zeros(B, Hkv, N, 128, device=DEV)
+    gv = torch.zeros_like(gk)
+    stats = torch.full((2, B, Hq, (N + 3) // 4 * 4), float("nan"), device=DEV)
+    for i in sel:                                   # descending
+        s0, c = i * C, min(C, N - i * C)
+        oc, lse = seco.seco_chunk_attn_fwd(q[:, :, s0:s0 + c], k, v, s0, s, o=o[:, :, s0:s0 + c])
+        lse_all[:, :, s0:s0 + c] = lse
+        w = [1.0 if j == i else (lam if j in sel else 0.0) for j in range(i, k_chunks)]
+        seco.seco_chunk_attn_bwd_gather(q[:, :, s0:], k, v, oc, lse, do[:, :, s0:], gk, gv, s0, s, c, stats,
+                                        d_q=dq[:, :, s0:s0 + c], row_weight=w, weight_chunk_len=C)
+    torch.cuda.synchronize()
+    got = {"o": to_host(o), "lse": to_host(lse_all), "dq": to_host(dq), "gk": to_host(gk), "gv": to_host(gv)}
+    ref = list(A.spaco_layer(x["q"], x["k"], x["v"], x["do"], C, s, sel, lam))
+    for i in range(k_chunks):                       # the oracle leaves O / LSE of unselected chunks unset or set:
+        if i not in sel:                            # compare them on the selected chunks only
+            for n, r in zip(("o", "lse"), ref[:2]):
+                got[n][:, :, i * C:(i + 1) * C] = r[:, :, i * C:(i + 1) * C]
+    check(got, ref, "bf16", f"spaco transposed {B,Hq,Hkv,N,C,sel}")
+    for i in range(k_chunks):
+        if i not in sel:
+            assert not got["gk"][:, :, i * C:(i + 1) * C].any() and not got["dq"][:, :, i * C:(i + 1) * C].any()
+
+
 def _device_group(cfg, b, kvh):
     """One (batch, KV head) unit of a configuration as a G-head layer: host dict + fp64 views."""
     grp = kv_group(cfg, b, kvh)
