@@ -244,6 +244,8 @@ def main():
                 kern[kind] = {"launches": int(n), "avg_ms": round(ms / n, 5), "total_ms_per_step": round(ms / ksteps, 4)}
                 if kind in alg:
                     kern[kind]["tflops"] = round(alg[kind] * ksteps / (ms * 1e-3) / 1e12, 2)
+                    if cfg.dtype == "bf16":      # fraction of the dense bf16 matrix-core peak (algorithmic work)
+                        kern[kind]["frac_of_mfma_peak"] = round(kern[kind]["tflops"] / PEAK_BF16_TFLOPS, 4)
         kern["measured_in"] = "last warm-up step (every launch bracketed by events)" if warm_prof is not None else "timed steps"
         if dom is None:
             dom = max(alg, key=lambda kd: prof[kd][0])
