@@ -34,7 +34,8 @@ class LayerState:
         self.gk = torch.empty(B, Hkv, N, D, dtype=torch.float32, device=device)
         self.gv = torch.empty_like(self.gk)
         self.kept = {}      # q_start -> (O, LSE) of stage 1, when attention outputs are kept for stage 2
-        self.gather = None  # transposed backward order: (Q of the layer, dO of the layer, row statistics)
+        self.gather = None  # transposed backward order: (Q, dO, O, dQ of the layer, row statistics)
+        self.gather_rows = None   # ... under Alg. 2: (selected chunks, factor, chunk length, number of chunks)
 
     def enable_gather(self, B, Hq, N, D, dtype, device):
         """Buffers of the transposed backward order: the layer's Q, dO, O and dQ over the whole sequence,
@@ -84,9 +85,15 @@ class ChunkAttention(torch.autograd.Function):
             q_all[:, :, s0:s0 + C] = q
             do_all[:, :, s0:s0 + C] = d_o
             o_all[:, :, s0:s0 + C] = o
+            row_w, wlen = None, None
+            if st.gather_rows is not None:      # Alg. 2: 1 on the chunk's own rows, the factor on later selected chunks
+                sel, factor, wlen, k = st.gather_rows
+                j = s0 // wlen
+                row_w = [1.0 if i == j else (factor if i in sel else 0.0) for i in range(j, k)]
             d_q = _b.seco_chunk_attn_bwd_gather(q_all[:, :, s0:], st.k, st.v, o_all[:, :, s0:s0 + C], lse,
                                                 do_all[:, :, s0:], st.gk, st.gv, s0, ctx.scale, C, stats,
-                                                d_q=dq_all[:, :, s0:s0 + C]).contiguous()
+                                                d_q=dq_all[:, :, s0:s0 + C], row_weight=row_w,
+                                                weight_chunk_len=wlen).contiguous()
         elif ctx.weights is None and ctx.dq_weights is None:
             d_q = _b.seco_chunk_attn_bwd(q, st.k, st.v, o, lse, d_o, st.gk, st.gv, s0, ctx.scale)
         else:
@@ -161,18 +168,22 @@ class ChunkedDecoder:
         of that attention call visits only the chunks with a non-zero weight and scales their terms
         (spaco_chunk_attn_bwd_sparse_dq; not part of the paper).  For unbiased gradients the weights must have
         expectation 1 and be drawn independently for every layer of a call.
-        transposed_backward: Alg. 1 with the attention backward in the transposed order (seco_chunk_attn_bwd_gather;
-        bf16 parameters, no selection): same gradients up to the order of summation."""
+        transposed_backward: the attention backward in the transposed order (seco_chunk_attn_bwd_gather, under Alg. 2
+        spaco_chunk_attn_bwd_gather; bf16 parameters): same gradients up to the order of summation."""
         p = self.p
         B, N = tokens.shape
         dtype, dev = p["emb"].dtype, p["emb"].device
         starts = list(range(0, N, chunk_len))
         states = [LayerState(B, self.Hkv, N, self.D, dtype, dev) for _ in range(self.n_layers)]
         if transposed_backward:
-            if selected is not None or dq_weights is not None or dtype != torch.bfloat16:
-                raise ValueError("the transposed backward order is for Alg. 1 (no selection) with bf16 parameters")
+            if dq_weights is not None or dtype != torch.bfloat16:
+                raise ValueError("the transposed backward order takes bf16 parameters and the exact dQ")
+            if selected is not None and chunk_len % 64 != 0:
+                raise ValueError("Alg. 2 in the transposed order needs a chunk length that is a multiple of 64")
             for st in states:
                 st.enable_gather(B, self.Hq, N, self.D, dtype, dev)
+                if selected is not None:
+                    st.gather_rows = ({int(i) for i in selected}, float(factor), chunk_len, len(starts))
         for t in p.values():
             t.grad = None
         total = torch.zeros((), dtype=torch.float32, device=dev)

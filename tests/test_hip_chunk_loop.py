@@ -164,3 +164,14 @@ def test_seco_step_with_the_transposed_backward_order_matches_whole_sequence_tra
     for n in g_a:
         d = (g_t[n].float() - g_a[n].float()).abs().max() / g_a[n].float().abs().max()
         assert float(d) < 2e-2, (n, float(d))
+
+
+def test_spaco_step_with_the_transposed_backward_order_matches_oracle():
+    """Alg. 2 with every layer's attention backward in the transposed order (row weights 1 / factor / 0)."""
+    cfg, tol = BF16_CFG, 6e-2
+    N, C = 320, 64
+    p64, dec, tok, tgt = _setup(cfg, 23, 1, N, torch.bfloat16)
+    sel, f = [4, 2, 1], 5.0 / 3.0
+    _, g_ref = om.spaco_grads(cfg, p64, tok, tgt, C, sel, f)
+    _, g = dec.step(tok.to(DEV), tgt.to(DEV), C, selected=sel, factor=f, transposed_backward=True)
+    _compare(g_ref, g, tol)
