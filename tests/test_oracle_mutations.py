@@ -1,0 +1,129 @@
+"""The pins of the attention oracle catch planted mistakes.
+
+Each case below takes the SOURCE of oracle/attention.py, plants one plausible mistake in the tier that the parity
+tests use (a dropped factor, a wrong sign, an off-by-one mask, a transposed operand, a wrong head mapping, ...),
+loads the result as a throw-away module and runs the pins of tests/test_oracle_attention.py against it.  At least
+one pin has to fail for every mutant, and all pass for the untouched source.  Nothing here touches the GPU path.
+"""
+import inspect
+import types
+
+import pytest
+
+import oracle.attention as real
+import test_oracle_attention as pins
+import test_oracle_spaco as spaco_pins
+
+SOURCE = inspect.getsource(real)
+
+# (name, text in the matmul tier, replacement)
+MUTANTS = [
+    ("mask excludes the diagonal", "np.arange(L)[None, :] <= (q_start + np.arange(C))[:, None]",
+     "np.arange(L)[None, :] < (q_start + np.arange(C))[:, None]"),
+    ("mask ignores q_start", "np.arange(L)[None, :] <= (q_start + np.arange(C))[:, None]",
+     "np.arange(L)[None, :] <= (np.arange(C))[:, None]"),
+    ("forward: scale dropped", "            s = scale * (q[b, h] @ kk.T)\n            s[~vis] = -np.inf",
+     "            s = (q[b, h] @ kk.T)\n            s[~vis] = -np.inf"),
+    ("forward: LSE without the shift", "lse[b, h] = (top + np.log(z))[:, 0]", "lse[b, h] = (np.log(z))[:, 0]"),
+    ("forward: wrong KV head", "            kk = k_cache[b, h // G, :L]\n            vv = v_cache[b, h // G, :L]\n            s = scale * (q[b, h] @ kk.T)\n            s[~vis]",
+     "            kk = k_cache[b, h % Hkv, :L]\n            vv = v_cache[b, h % Hkv, :L]\n            s = scale * (q[b, h] @ kk.T)\n            s[~vis]"),
+    ("backward: sign of delta", "ds = prob * (dp - delta)", "ds = prob * (dp + delta)"),
+    ("backward: delta from dO alone", "delta = (d_o[b, h] * o[b, h]).sum(axis=1, keepdims=True)",
+     "delta = (d_o[b, h] * d_o[b, h]).sum(axis=1, keepdims=True)"),
+    ("backward: dQ without the scale", "dq[b, h] = scale * (ds @ kk)", "dq[b, h] = (ds @ kk)"),
+    ("backward: dK without the scale", "dk[b, g] += scale * (ds.T @ q[b, h])", "dk[b, g] += (ds.T @ q[b, h])"),
+    ("backward: dK from dO", "dk[b, g] += scale * (ds.T @ q[b, h])", "dk[b, g] += scale * (ds.T @ d_o[b, h])"),
+    ("backward: dV from dS", "dv[b, g] += prob.T @ d_o[b, h]", "dv[b, g] += ds.T @ d_o[b, h]"),
+    ("backward: dP from K", "dp = d_o[b, h] @ vv.T", "dp = d_o[b, h] @ kk.T"),
+    ("backward: group sum overwritten", "dv[b, g] += prob.T @ d_o[b, h]", "dv[b, g] = prob.T @ d_o[b, h]"),
+    ("backward: masked probabilities kept", "prob = np.where(vis, np.exp(s - lse[b, h][:, None]), 0.0)",
+     "prob = np.exp(s - lse[b, h][:, None])"),
+    ("layer: contributions of a call overwrite gK", "        gK[:, :, :s0 + c] += dk\n        gV[:, :, :s0 + c] += dv\n    return O, LSE, dQ, gK, gV",
+     "        gK[:, :, :s0 + c] = dk\n        gV[:, :, :s0 + c] += dv\n    return O, LSE, dQ, gK, gV"),
+    ("layer: contributions of a call overwrite gV", "        gV[:, :, :s0 + c] += dv\n    return O, LSE, dQ, gK, gV",
+     "        gV[:, :, :s0 + c] = dv\n    return O, LSE, dQ, gK, gV"),
+]
+
+
+def _load(source):
+    mod = types.ModuleType("oracle_attention_mutant")
+    mod.__dict__["__name__"] = "oracle_attention_mutant"
+    exec(compile(source, "oracle_attention_mutant", "exec"), mod.__dict__)
+    return mod
+
+
+def _pin_calls(pins=pins):
+    """Every pin of a test module, with its parameter grid expanded by hand from the marks."""
+    calls = []
+    for name, fn in inspect.getmembers(pins, inspect.isfunction):
+        if not name.startswith("test_") or name == "test_argument_checks":
+            continue
+        grids = [[]]
+        for mark in getattr(fn, "pytestmark", []):
+            if mark.name != "parametrize":
+                continue
+            names = [n.strip() for n in mark.args[0].split(",")]
+            new = []
+            for g in grids:
+                for vals in mark.args[1]:
+                    vals = vals if isinstance(vals, (tuple, list)) and len(names) > 1 else (vals,)
+                    new.append(g + list(zip(names, vals)))
+            grids = new
+        for g in grids:
+            kw = dict(g)
+            if kw.get("tier") == "loops":        # the mistakes are planted in the matmul tier
+                continue
+            calls.append((name, fn, kw))
+    return calls
+
+
+def _failures(module, monkeypatch, pins=pins):
+    monkeypatch.setattr(pins, "A", module)
+    failed = []
+    for name, fn, kw in _pin_calls(pins):
+        try:
+            fn(**kw)
+        except AssertionError:
+            failed.append(name)
+        except (ValueError, FloatingPointError, IndexError):
+            failed.append(name)
+    return failed
+
+
+def test_untouched_source_passes_every_pin(monkeypatch):
+    assert len(_pin_calls()) >= 15
+    assert _failures(_load(SOURCE), monkeypatch) == []
+
+
+@pytest.mark.parametrize("what,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(what, old, new, monkeypatch):
+    assert SOURCE.count(old) >= 1, f"the oracle no longer contains the text this case edits: {old!r}"
+    failed = _failures(_load(SOURCE.replace(old, new)), monkeypatch)
+    assert failed, f"no pin noticed: {what}"
+
+
+# mistakes in the SpaCO schedule (Alg. 2 at one layer), against the pins of tests/test_oracle_spaco.py
+SPACO_MUTANTS = [
+    ("factor also on the chunk's own rows", "gK[:, :, s0:s0 + c] += dk[:, :, s0:s0 + c]            # own rows: weight 1",
+     "gK[:, :, s0:s0 + c] += factor * dk[:, :, s0:s0 + c]"),
+    ("factor not applied to earlier chunks", "gK[:, :, t0:t0 + ci] += factor * dk[:, :, t0:t0 + ci]",
+     "gK[:, :, t0:t0 + ci] += dk[:, :, t0:t0 + ci]"),
+    ("deposits on later selected chunks instead of earlier ones", "            if i < j:                                         # earlier selected chunk",
+     "            if i > j:"),
+    ("deposits on every earlier chunk, selected or not", "        for i in sel:\n            if i < j:                                         # earlier selected chunk",
+     "        for i in range(len(chunks)):\n            if i < j:"),
+    ("dQ of selected chunks dropped", "        dQ[:, :, s0:s0 + c] = dq\n        gK[:, :, s0:s0 + c] += dk[:, :, s0:s0 + c]",
+     "        gK[:, :, s0:s0 + c] += dk[:, :, s0:s0 + c]"),
+]
+
+
+def test_untouched_source_passes_every_spaco_pin(monkeypatch):
+    assert len(_pin_calls(spaco_pins)) >= 10
+    assert _failures(_load(SOURCE), monkeypatch, spaco_pins) == []
+
+
+@pytest.mark.parametrize("what,old,new", SPACO_MUTANTS, ids=[m[0] for m in SPACO_MUTANTS])
+def test_planted_mistake_in_the_sparse_schedule_is_caught(what, old, new, monkeypatch):
+    assert SOURCE.count(old) == 1, f"the oracle no longer contains the text this case edits: {old!r}"
+    failed = _failures(_load(SOURCE.replace(old, new)), monkeypatch, spaco_pins)
+    assert failed, f"no pin noticed: {what}"
