@@ -13,6 +13,8 @@ import pytest
 import oracle.attention as real
 import test_oracle_attention as pins
 import test_oracle_spaco as spaco_pins
+import oracle.relay as real_relay
+import test_oracle_relay as relay_pins
 
 SOURCE = inspect.getsource(real)
 
@@ -127,3 +129,38 @@ def test_planted_mistake_in_the_sparse_schedule_is_caught(what, old, new, monkey
     assert SOURCE.count(old) == 1, f"the oracle no longer contains the text this case edits: {old!r}"
     failed = _failures(_load(SOURCE.replace(old, new)), monkeypatch, spaco_pins)
     assert failed, f"no pin noticed: {what}"
+
+
+# mistakes in the cache append / gradient read-out / rotary embedding oracle, against tests/test_oracle_relay.py
+RELAY_SOURCE = inspect.getsource(real_relay)
+RELAY_MUTANTS = [
+    ("rotation turns the wrong way", "return np.concatenate([a * cos - b * sin, b * cos + a * sin], axis=-1)",
+     "return np.concatenate([a * cos + b * sin, b * cos - a * sin], axis=-1)"),
+    ("frequency exponent -i/D instead of -2i/D", "np.power(float(base), -2.0 * i / D)", "np.power(float(base), -1.0 * i / D)"),
+    ("positions start one late", "th = rope_angles(pos0 + np.arange(C), D, base)", "th = rope_angles(pos0 + 1 + np.arange(C), D, base)"),
+    ("inverse does not turn back", "np.sin(th) * (-1.0 if inverse else 1.0)", "np.sin(th)"),
+    ("pairs (2i, 2i+1) instead of (i, i + D/2)", "a, b = x[..., :D // 2], x[..., D // 2:]\n    return np.concatenate([a * cos - b * sin, b * cos + a * sin], axis=-1)",
+     "a, b = x[..., 0::2], x[..., 1::2]\n    return np.stack([a * cos - b * sin, b * cos + a * sin], axis=-1).reshape(x.shape)"),
+]
+
+
+def _relay_failures(module, monkeypatch):
+    monkeypatch.setattr(relay_pins, "R", module)
+    failed = []
+    for name, fn in inspect.getmembers(relay_pins, inspect.isfunction):
+        if name.startswith("test_"):
+            try:
+                fn()
+            except AssertionError:
+                failed.append(name)
+    return failed
+
+
+def test_untouched_relay_source_passes_its_pins(monkeypatch):
+    assert _relay_failures(_load(RELAY_SOURCE), monkeypatch) == []
+
+
+@pytest.mark.parametrize("what,old,new", RELAY_MUTANTS, ids=[m[0] for m in RELAY_MUTANTS])
+def test_planted_mistake_in_the_rotary_embedding_is_caught(what, old, new, monkeypatch):
+    assert RELAY_SOURCE.count(old) == 1, f"the oracle no longer contains the text this case edits: {old!r}"
+    assert _relay_failures(_load(RELAY_SOURCE.replace(old, new)), monkeypatch), f"no pin noticed: {what}"
