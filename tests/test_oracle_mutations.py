@@ -15,6 +15,8 @@ import test_oracle_attention as pins
 import test_oracle_spaco as spaco_pins
 import oracle.relay as real_relay
 import test_oracle_relay as relay_pins
+import oracle.model as real_model
+import test_oracle_model as model_pins
 
 SOURCE = inspect.getsource(real)
 
@@ -48,9 +50,14 @@ MUTANTS = [
 
 
 def _load(source):
-    mod = types.ModuleType("oracle_attention_mutant")
-    mod.__dict__["__name__"] = "oracle_attention_mutant"
-    exec(compile(source, "oracle_attention_mutant", "exec"), mod.__dict__)
+    import sys
+    name = "oracle_mutant"
+    mod = types.ModuleType(name)
+    sys.modules[name] = mod            # (dataclasses look the defining module up while a class is created)
+    try:
+        exec(compile(source, name, "exec"), mod.__dict__)
+    finally:
+        del sys.modules[name]
     return mod
 
 
@@ -164,3 +171,41 @@ def test_untouched_relay_source_passes_its_pins(monkeypatch):
 def test_planted_mistake_in_the_rotary_embedding_is_caught(what, old, new, monkeypatch):
     assert RELAY_SOURCE.count(old) == 1, f"the oracle no longer contains the text this case edits: {old!r}"
     assert _relay_failures(_load(RELAY_SOURCE.replace(old, new)), monkeypatch), f"no pin noticed: {what}"
+
+
+# mistakes in the multi-layer schedules (Alg. 1 / Alg. 2 over a decoder), against tests/test_oracle_model.py
+MODEL_SOURCE = inspect.getsource(real_model)
+MODEL_MUTANTS = [
+    ("factor on the key gradient only", "grads += [factor * gk, factor * gv]", "grads += [factor * gk, gv]"),
+    ("value gradient not handed over", "                roots += [k, v]\n                grads += [factor * gk, factor * gv]",
+     "                roots += [k]\n                grads += [factor * gk]"),
+    ("second loop in ascending order", "range(len(ckpt) - 1, -1, -1), 1.0, dq_weights)", "range(len(ckpt)), 1.0, dq_weights)"),
+    ("a chunk also sees its own checkpoint", "(torch.cat([c[l][0] for c in ckpt[:i]], 2), torch.cat([c[l][1] for c in ckpt[:i]], 2)) if i",
+     "(torch.cat([c[l][0] for c in ckpt[:i + 1]], 2), torch.cat([c[l][1] for c in ckpt[:i + 1]], 2)) if i"),
+    ("mask without the diagonal", "vis = torch.arange(L)[None, :] <= (q_start + torch.arange(C))[:, None]",
+     "vis = torch.arange(L)[None, :] <= (q_start + torch.arange(C) - 1)[:, None]"),
+    ("query heads mapped to the wrong KV head", "    k_rep = k_all.repeat_interleave(G, 1)\n", "    k_rep = k_all.repeat(1, G, 1, 1)\n"),
+]
+
+
+def _model_failures(module, monkeypatch):
+    monkeypatch.setattr(model_pins, "om", module)
+    failed = []
+    for name, fn, kw in _pin_calls(model_pins):
+        if "monkeypatch" in inspect.signature(fn).parameters:
+            kw = dict(kw, monkeypatch=monkeypatch)
+        try:
+            fn(**kw)
+        except (AssertionError, RuntimeError, ValueError, IndexError):
+            failed.append(name)
+    return failed
+
+
+def test_untouched_model_source_passes_its_pins(monkeypatch):
+    assert _model_failures(_load(MODEL_SOURCE), monkeypatch) == []
+
+
+@pytest.mark.parametrize("what,old,new", MODEL_MUTANTS, ids=[m[0] for m in MODEL_MUTANTS])
+def test_planted_mistake_in_the_multi_layer_schedule_is_caught(what, old, new, monkeypatch):
+    assert MODEL_SOURCE.count(old) == 1, f"the oracle no longer contains the text this case edits: {old!r}"
+    assert _model_failures(_load(MODEL_SOURCE.replace(old, new)), monkeypatch), f"no pin noticed: {what}"
