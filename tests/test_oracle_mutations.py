@@ -16,6 +16,8 @@ import test_oracle_spaco as spaco_pins
 import oracle.relay as real_relay
 import test_oracle_relay as relay_pins
 import oracle.model as real_model
+import oracle.selection as real_selection
+import test_oracle_selection as selection_pins
 import test_oracle_model as model_pins
 
 SOURCE = inspect.getsource(real)
@@ -209,3 +211,38 @@ def test_untouched_model_source_passes_its_pins(monkeypatch):
 def test_planted_mistake_in_the_multi_layer_schedule_is_caught(what, old, new, monkeypatch):
     assert MODEL_SOURCE.count(old) == 1, f"the oracle no longer contains the text this case edits: {old!r}"
     assert _model_failures(_load(MODEL_SOURCE.replace(old, new)), monkeypatch), f"no pin noticed: {what}"
+
+
+# mistakes in the selection of Alg. 2, against tests/test_oracle_selection.py
+SELECTION_SOURCE = inspect.getsource(real_selection)
+SELECTION_MUTANTS = [
+    ("a wrong multiplier in the generator's finaliser", "0xBF58476D1CE4E5B9", "0xBF58476D1CE4E5B7"),
+    ("bounded draw without rejection", "            if u < limit:\n                return u % m", "            return u % m"),
+    ("draws with replacement", "        r = i + rng.below(k - i)\n", "        r = rng.below(k)\n"),
+    ("ascending output", "return np.array(sorted(perm[:t], reverse=True), dtype=np.int32)",
+     "return np.array(sorted(perm[:t]), dtype=np.int32)"),
+    ("the step does not enter the key", "_finalise((seed & _MASK) ^ _finalise((step + _GOLDEN) & _MASK))",
+     "_finalise((seed & _MASK) ^ _finalise(_GOLDEN & _MASK))"),
+    ("never selects the last chunk", "        r = i + rng.below(k - i)\n", "        r = i + rng.below(max(k - i - 1, 1))\n"),
+]
+
+
+def _selection_failures(module, monkeypatch):
+    monkeypatch.setattr(selection_pins, "S", module)
+    failed = []
+    for name, fn, kw in _pin_calls(selection_pins):
+        try:
+            fn(**kw)
+        except (AssertionError, ValueError, IndexError):
+            failed.append(name)
+    return failed
+
+
+def test_untouched_selection_source_passes_its_pins(monkeypatch):
+    assert _selection_failures(_load(SELECTION_SOURCE), monkeypatch) == []
+
+
+@pytest.mark.parametrize("what,old,new", SELECTION_MUTANTS, ids=[m[0] for m in SELECTION_MUTANTS])
+def test_planted_mistake_in_the_selection_is_caught(what, old, new, monkeypatch):
+    assert SELECTION_SOURCE.count(old) == 1, f"the oracle no longer contains the text this case edits: {old!r}"
+    assert _selection_failures(_load(SELECTION_SOURCE.replace(old, new)), monkeypatch), f"no pin noticed: {what}"
