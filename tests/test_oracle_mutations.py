@@ -18,6 +18,7 @@ import test_oracle_relay as relay_pins
 import oracle.model as real_model
 import oracle.selection as real_selection
 import test_oracle_selection as selection_pins
+import test_oracle_sparse_dq as sparse_dq_pins
 import test_oracle_model as model_pins
 
 SOURCE = inspect.getsource(real)
@@ -246,3 +247,21 @@ def test_untouched_selection_source_passes_its_pins(monkeypatch):
 def test_planted_mistake_in_the_selection_is_caught(what, old, new, monkeypatch):
     assert SELECTION_SOURCE.count(old) == 1, f"the oracle no longer contains the text this case edits: {old!r}"
     assert _selection_failures(_load(SELECTION_SOURCE.replace(old, new)), monkeypatch), f"no pin noticed: {what}"
+
+
+# mistakes in the column-weighted dQ, against tests/test_oracle_sparse_dq.py
+SPARSE_DQ_MUTANTS = [
+    ("weights squared", "dq[b, h] = scale * ((ds * w[None, :]) @ kk)", "dq[b, h] = scale * ((ds * w[None, :] * w[None, :]) @ kk)"),
+    ("weights applied to the rows", "dq[b, h] = scale * ((ds * w[None, :]) @ kk)", "dq[b, h] = scale * ((ds * w[-C:, None]) @ kk)"),
+    ("delta restricted to the weighted columns", "            ds = prob * (d_o[b, h] @ vv.T - delta)\n            dq[b, h] = scale * ((ds * w[None, :]) @ kk)",
+     "            ds = prob * (d_o[b, h] @ vv.T - ((prob * w[None, :]) * (d_o[b, h] @ vv.T)).sum(axis=1, keepdims=True))\n"
+     "            dq[b, h] = scale * ((ds * w[None, :]) @ kk)"),
+]
+
+
+@pytest.mark.parametrize("what,old,new", [("untouched", "", "")] + SPARSE_DQ_MUTANTS,
+                         ids=["untouched"] + [m[0] for m in SPARSE_DQ_MUTANTS])
+def test_planted_mistake_in_the_weighted_dq_is_caught(what, old, new, monkeypatch):
+    assert what == "untouched" or SOURCE.count(old) == 1, f"the oracle no longer contains the text this case edits: {old!r}"
+    failed = _failures(_load(SOURCE.replace(old, new) if old else SOURCE), monkeypatch, sparse_dq_pins)
+    assert (failed == []) if what == "untouched" else failed, f"{what}: {failed}"
