@@ -534,10 +534,12 @@ def test_short_chunk_forward_with_and_without_workspace():
         assert max_rel(to_host(l), ref_l) <= 1e-2
 
 
-def test_step_captured_in_a_hip_graph_replays_identically():
+@pytest.mark.parametrize("order", ["accumulating", "transposed"])
+def test_step_captured_in_a_hip_graph_replays_identically(order):
     """The library allocates nothing, never synchronises and clears gK/gV with a kernel, so a whole SeCO step can be
-    captured into a HIP graph.  Every replay (with eager work and synchronisations in between, and the outputs
-    poisoned before each replay) must reproduce the eager result bit for bit (the kernels are deterministic)."""
+    captured into a HIP graph, in either backward order.  Every replay (with eager work and synchronisations in
+    between, and the outputs poisoned before each replay) must reproduce the eager result bit for bit (the kernels
+    are deterministic)."""
     B, Hq, Hkv, N, C = 1, 8, 2, 768, 128           # short chunks: split kernels and merges are in the graph too
     x = small_layer(50, B, Hq, Hkv, N, 128, "bf16")
     s = 1 / np.sqrt(128)
@@ -556,9 +558,14 @@ def test_step_captured_in_a_hip_graph_replays_identically():
         for j in range(N // C - 1, -1, -1):
             sl = slice(j * C, (j + 1) * C)
             seco.seco_chunk_attn_fwd(q[:, :, sl], k, v, j * C, s, o=o[:, :, sl], lse=lse, ws=ws_f)
-            seco.seco_chunk_attn_bwd(q[:, :, sl], k, v, o[:, :, sl], lse, do[:, :, sl], gk, gv, j * C, s,
-                                     d_q=dq[:, :, sl], ws=ws_b)
+            if order == "accumulating":
+                seco.seco_chunk_attn_bwd(q[:, :, sl], k, v, o[:, :, sl], lse, do[:, :, sl], gk, gv, j * C, s,
+                                         d_q=dq[:, :, sl], ws=ws_b)
+            else:
+                seco.seco_chunk_attn_bwd_gather(q[:, :, j * C:], k, v, o[:, :, sl], lse, do[:, :, j * C:], gk, gv,
+                                                j * C, s, C, stats, d_q=dq[:, :, sl], ws=ws_b)
 
+    stats = torch.empty(2, B, Hq, N, dtype=torch.float32, device=DEV)
     outs = (o, dq, gk, gv)
     step()
     torch.cuda.synchronize()
@@ -576,7 +583,7 @@ def test_step_captured_in_a_hip_graph_replays_identically():
     with torch.cuda.graph(graph):
         step()
     for rep in range(3):
-        for t in outs:
+        for t in outs + (stats,):
             t.fill_(float("nan"))
         torch.cuda.synchronize()
         graph.replay()
