@@ -35,6 +35,12 @@
 // of every (batch, KV head) are therefore divided among 2 or 4 workgroups by query head: each writes its
 // fp32 sums to the workspace and dkdv_tail_merge_kernel adds them to gK/gV in head order (still one writer
 // per element and a fixed summation order, so results stay reproducible).
+//
+// The same kernel serves the transposed order of the backward pass (seco_chunk_attn_bwd_gather): there the column
+// run is one chunk and the query rows are that chunk's and every later one's, p.C of them from p.q_start on, with
+// -delta and -LSE read from arrays kept for the whole sequence (stat_stride, stat_off).  With ROWS the rows come as
+// runs with one weight each (Alg. 2 in that order): rows outside the runs are never read, and a run's weight
+// enters as log2 w added to -LSE, i.e. as a factor on P and through it on dV and dS alike.
 #include "mfma_tiles.h"
 #include "seco_internal.h"
 
