@@ -13,9 +13,13 @@ Contents
   selection.py  SpaCO chunk selection (Alg. 2, "select t distinct indices"),
                 compensation factor (Sec. 5 "Compensation Factor", Sec. 6.4 cap)
                 and the per-call chunk weight vector
+  model.py      Alg. 1 and Alg. 2 over a small multi-layer decoder (torch fp64 autograd per chunk, the
+                schedules and the relay of factor * m'_i.grad written out)
+  relay.py      cache append, gradient read-out with its rounding, rotary position embedding
 
 Pins (tests/test_oracle_*.py): library softmax-attention + autograd in fp64,
 central finite differences, closed-form special cases, brute-force enumeration
 of every chunk selection, a published test vector for the integer generator
 and the factor values the paper states.  No function here is "parity unpinned".
+tests/test_oracle_mutations.py plants mistakes in copies of these sources and checks that the pins fail.
 """
