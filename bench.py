@@ -22,9 +22,23 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak (published)
-# HBM bytes per launch (mean over the 16 calls of cfg2) from rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0; the
-# factors come from a streaming kernel of known size in the same runs (profiles/cfg2_hbm_traffic_pmc.txt).
-HBM_TRAFFIC_PER_LAUNCH = {("cfg2", "dkdv"): 254.7e6}
+TOL = {"f32": {"o": 1e-4, "lse": 1e-4, "dq": 1e-4, "gk": 1e-4, "gv": 1e-4},
+       "bf16": {"o": 1e-2, "lse": 1e-2, "dq": 2e-2, "gk": 2e-2, "gv": 2e-2}}
+
+
+def hbm_traffic_per_launch(workload, kernel):
+    """HBM bytes per launch of `kernel` in `workload`, from the committed table of rocprofv3 FETCH_SIZE / WRITE_SIZE
+    measurements (profiles/hbm_traffic_per_launch.txt: one `workload kernel bytes` line per measured pair, with the
+    commands and the calibration beside it).  None for a pair that has not been measured."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")) as f:
+            for line in f:
+                parts = line.split("#")[0].split()
+                if len(parts) == 3 and parts[0] == workload and parts[1] == kernel:
+                    return float(parts[2])
+    except OSError:
+        pass
+    return None
 
 
 def pairs(j, C):
@@ -37,7 +51,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--config", default="cfg3",
+                    help="workload of the headline figure (default: the 32K-token layer the metric is quoted on)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the extra objects (cfg2, cfg4 and the Alg. 2 steps) of the default run")
+    ap.add_argument("--device-inputs", action="store_true",
+                    help="draw the inputs on the device (torch generator) instead of uploading the seeded host arrays "
+                         "of `workloads`; no parity object then")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-layer32k", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events in the timed region")
@@ -64,11 +84,12 @@ def main():
                          "size: reads 2 GiB, writes 1 GiB) so that rocprofv3 FETCH_SIZE / WRITE_SIZE can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build is single-GPU by design (one process, one MI355X); run with --gpus 1")
+        sys.exit("bench.py: this build is single-GPU by design (one process, one MI355X, no collectives); "
+                 "run with --gpus 1")
 
     import torch
     import paper_2505_16710_amd as seco
-    from workloads import CONFIGS
+    from workloads import CONFIGS, f32_to_bf16_bits, head_slice
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
@@ -79,22 +100,52 @@ def main():
     k_chunks = cfg.n_chunks
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     scale = cfg.scale
+    G = Hq // Hkv
+    # (batch, KV head) units whose host arrays are kept for the oracle: it is timed on them (cpu_baseline) and the
+    # GPU results of the very same arrays are compared with what it returns (parity)
+    oracle_units = [] if (args.no_cpu_baseline or args.device_inputs) else [(0, Hkv // 2), (B - 1, Hkv - 1)]
+    host_units = {}
 
-    def make_inputs(N):
-        gen = torch.Generator(device=dev).manual_seed(cfg.seed)
-        mk = lambda h: torch.randn(B, h, N, D, generator=gen, device=dev, dtype=torch.float32).to(tdt)
-        return mk(Hq), mk(Hkv), mk(Hkv), mk(Hq)
+    def device_inputs(cx):
+        gen = torch.Generator(device=dev).manual_seed(cx.seed)
+        mk = lambda h: torch.randn(cx.batch, h, cx.seq_len, cx.head_dim, generator=gen, device=dev,
+                                   dtype=torch.float32).to(tdt)
+        return mk(cx.n_q_heads), mk(cx.n_kv_heads), mk(cx.n_kv_heads), mk(cx.n_q_heads)
+
+    def uploaded_inputs(cx, keep):
+        """The seeded host arrays of `workloads` (already rounded to the storage type), uploaded head by head; the
+        fp32 host copies of the units in `keep` stay in host_units for the oracle."""
+        out = {}
+        for name, H in (("q", cx.n_q_heads), ("k", cx.n_kv_heads), ("v", cx.n_kv_heads), ("do", cx.n_q_heads)):
+            t = torch.empty(cx.batch, H, cx.seq_len, cx.head_dim, dtype=tdt, device=dev)
+            for b in range(cx.batch):
+                for h in range(H):
+                    x = head_slice(cx, name, b, h)
+                    if cx.dtype == "bf16":
+                        t[b, h] = torch.from_numpy(f32_to_bf16_bits(x).view(np.int16)).to(dev).view(torch.bfloat16)
+                    else:
+                        t[b, h] = torch.from_numpy(x).to(dev)
+                    u = (b, h // (cx.n_q_heads // cx.n_kv_heads) if H == cx.n_q_heads else h)
+                    if u in keep:
+                        host_units.setdefault(u, {}).setdefault(name, []).append(x)
+            out[name] = t
+        return out["q"], out["k"], out["v"], out["do"]
 
     class Layer:
-        """Device buffers of one layer; O is kept whole so that O and dO chunk views share strides."""
+        """Device buffers of one layer of configuration cx; O is kept whole so that O and dO chunk views share
+        strides."""
 
-        def __init__(self, N, C):
-            self.N, self.C, self.k = N, C, N // C
-            self.q, self.kc, self.vc, self.do = make_inputs(N)
+        def __init__(self, cx, inputs=None, seq_len=None):
+            if seq_len is not None:                 # same shape, another context length (device-generated inputs)
+                from dataclasses import replace
+                cx = replace(cx, seq_len=seq_len)
+            self.cx, self.N, self.C, self.k = cx, cx.seq_len, cx.chunk_len, cx.n_chunks
+            self.q, self.kc, self.vc, self.do = inputs if inputs is not None else device_inputs(cx)
+            Bx, Hqx, Hkvx, Dx = cx.batch, cx.n_q_heads, cx.n_kv_heads, cx.head_dim
             self.o = torch.empty_like(self.q)
-            self.lse = torch.empty(self.k, B, Hq, C, device=dev, dtype=torch.float32)   # kept per chunk
+            self.lse = torch.empty(self.k, Bx, Hqx, self.C, device=dev, dtype=torch.float32)   # kept per chunk
             self.dq = torch.empty_like(self.q)
-            self.gk = torch.empty(B, Hkv, N, D, device=dev, dtype=torch.float32)
+            self.gk = torch.empty(Bx, Hkvx, self.N, Dx, device=dev, dtype=torch.float32)
             self.gv = torch.empty_like(self.gk)
             # workspaces sized by the library for this shape (delta; partial results of the short-chunk path)
             d = seco.binding.make_desc(self.rows(self.q, 0), self.kc, 0, scale, o=self.rows(self.o, 0), g=self.gk)
@@ -119,7 +170,10 @@ def main():
                 seco.spaco_chunk_attn_bwd(*args, weights, self.C, d_q=self.rows(self.dq, j), ws=self.ws,
                                           dq_weight=dq_weights)
 
-    L = Layer(N, C)
+    t_in = time.perf_counter()
+    L = Layer(cfg, None if args.device_inputs else uploaded_inputs(cfg, set(oracle_units)))
+    torch.cuda.synchronize()
+    input_seconds = time.perf_counter() - t_in
 
     def step():
         seco.kvgrad_zero(L.gk, L.gv)
@@ -169,6 +223,33 @@ def main():
         with torch.cuda.graph(graph):
             step()
         run_step = graph.replay
+
+    bf16 = cfg.dtype == "bf16"
+    peak = PEAK_BF16_TFLOPS if bf16 else 157.3
+
+    def roofline_of(name, kind, alg_flops, ms, n, n_steps, where):
+        """Roofline object of one kernel kind: algorithmic FLOPs of its launches / their summed event durations.
+        bf16 kernels are dense MFMA contractions (2500 TFLOP/s); the fp32 parity kernels use the vector ALU only
+        (256 CUs x 128 lanes x 2 FLOP x 2.4 GHz = 157.3 TFLOP/s)."""
+        achieved = alg_flops * n_steps / (ms * 1e-3) / 1e12
+        twice = 2.0 if (bf16 and kind == "dkdv") else 1.0       # dK/dV computes S and dP a second time
+        return {"bound": "mfma" if bf16 else "alu", "kernel": kind + ("_bf16_kernel" if bf16 else "_f32_kernel"),
+                "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                "traffic": hbm_traffic_per_launch(name, kind),
+                "avg_launch_ms": round(ms / n, 5), "launches": int(n),
+                "executed_over_algorithmic": twice, "executed_frac": round(achieved * twice / peak, 4),
+                "measured_in": where}
+
+    def kernel_table(kprof, alg, n_steps):
+        kern = {}
+        for kind, (ms, n) in kprof.items():
+            if n:
+                kern[kind] = {"launches": int(n), "avg_ms": round(ms / n, 5), "total_ms_per_step": round(ms / n_steps, 4)}
+                if kind in alg:
+                    kern[kind]["tflops"] = round(alg[kind] * n_steps / (ms * 1e-3) / 1e12, 2)
+                    if bf16:      # fraction of the dense bf16 matrix-core peak (algorithmic work)
+                        kern[kind]["frac_of_mfma_peak"] = round(kern[kind]["tflops"] / PEAK_BF16_TFLOPS, 4)
+        return kern
 
     # Per-kernel event times come from the warm-up steps (every launch bracketed).  In the timed steps only the
     # launches of the dominant kernel are bracketed, and only in every PROF_EVERY-th step: an event costs a gap of
@@ -220,9 +301,12 @@ def main():
         "metric": "chunk_attn_fwd_bwd_tflops", "value": round(tflops, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: SeCO fwd+bwd, one call pair per chunk, full gK/gV accumulation",
+        "config": {"workload": f"{cfg.name}: SeCO fwd+bwd (Alg. 1 second loop), one call pair per chunk, full gK/gV "
+                               f"accumulation, {N}-token layer",
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "seq_len": N, "chunk_len": C,
-                   "n_chunks": k_chunks, "flops_per_step": flops_step},
+                   "n_chunks": k_chunks, "flops_per_step": flops_step,
+                   "inputs": "device-generated (torch generator)" if args.device_inputs else
+                             f"seeded host arrays of workloads.head_slice, uploaded ({input_seconds:.1f} s, untimed)"},
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "launch_mode": "hip_graph_replay" if args.graph else "eager",
         "step_ms_min": round(per_step[0], 4), "step_ms_median": round(per_step[len(per_step) // 2], 4),
@@ -237,41 +321,85 @@ def main():
 
     if prof is not None:
         alg = {"fwd": flops_fwd, "dq": flops_dq, "dkdv": flops_dkdv}
-        kern = {}
         kprof, ksteps = (warm_prof, 1) if warm_prof is not None else (prof, n_prof_steps)
-        for kind, (ms, n) in kprof.items():
-            if n:
-                kern[kind] = {"launches": int(n), "avg_ms": round(ms / n, 5), "total_ms_per_step": round(ms / ksteps, 4)}
-                if kind in alg:
-                    kern[kind]["tflops"] = round(alg[kind] * ksteps / (ms * 1e-3) / 1e12, 2)
-                    if cfg.dtype == "bf16":      # fraction of the dense bf16 matrix-core peak (algorithmic work)
-                        kern[kind]["frac_of_mfma_peak"] = round(kern[kind]["tflops"] / PEAK_BF16_TFLOPS, 4)
+        kern = kernel_table(kprof, alg, ksteps)
         kern["measured_in"] = "last warm-up step (every launch bracketed by events)" if warm_prof is not None else "timed steps"
         if dom is None:
             dom = max(alg, key=lambda kd: prof[kd][0])
         ms, n = prof[dom]
-        achieved = alg[dom] * n_prof_steps / (ms * 1e-3) / 1e12
-        # bf16 kernels are dense MFMA contractions (2500 TFLOP/s); the fp32 parity kernels use the vector ALU only
-        # (256 CUs x 128 lanes x 2 FLOP x 2.4 GHz = 157.3 TFLOP/s)
-        bf16 = cfg.dtype == "bf16"
-        peak = PEAK_BF16_TFLOPS if bf16 else 157.3
-        out["roofline"] = {"bound": "mfma" if bf16 else "alu", "kernel": dom + ("_bf16_kernel" if bf16 else "_f32_kernel"),
-                           "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                           "frac": round(achieved / peak, 4),
-                           "traffic": HBM_TRAFFIC_PER_LAUNCH.get((cfg.name, dom)),
-                           "avg_launch_ms": round(ms / n, 5), "launches": int(n),
-                           # matrix work the kernel executes per algorithmic FLOP (dK/dV computes S and dP again)
-                           "executed_over_algorithmic": 2.0 if (bf16 and dom == "dkdv") else 1.0,
-                           "executed_frac": round(achieved * (2.0 if (bf16 and dom == "dkdv") else 1.0) / peak, 4),
-                           "measured_in": f"timed steps (HIP events around every launch of this kernel in {n_prof_steps} "
-                                          f"of the {args.steps} timed steps)"}
+        out["roofline"] = roofline_of(cfg.name, dom, alg[dom], ms, n, n_prof_steps,
+                                      f"timed steps (HIP events around every launch of this kernel in {n_prof_steps} "
+                                      f"of the {args.steps} timed steps)")
         out["kernels"] = kern
+
+    # The outputs of the last timed step, brought to the host for the units the oracle is going to evaluate (the
+    # comparison itself follows the oracle's timed run below).
+    gpu_units = {}
+    for (b, kvh) in oracle_units:
+        hs = slice(kvh * G, (kvh + 1) * G)
+        lse_full = torch.cat([L.lse[j][b:b + 1, hs] for j in range(k_chunks)], dim=2)
+        gpu_units[(b, kvh)] = {"o": L.o[b:b + 1, hs].double().cpu().numpy(), "lse": lse_full.double().cpu().numpy(),
+                               "dq": L.dq[b:b + 1, hs].double().cpu().numpy(),
+                               "gk": L.gk[b:b + 1, kvh:kvh + 1].double().cpu().numpy(),
+                               "gv": L.gv[b:b + 1, kvh:kvh + 1].double().cpu().numpy()}
+
+    def other_workload(cx, selected=None, steps=5, warmup=2):
+        """value + per-kernel table + roofline of the dominant kernel for another workload (device-generated inputs of
+        the same distribution): the SeCO step, or with `selected` the Alg. 2 step (forward + backward calls of the
+        selected chunks only, dK/dV restricted to selected chunks and weighted with the factor k/t)."""
+        Lx = Layer(cx)
+        kx, Cx = cx.n_chunks, cx.chunk_len
+        pp = cx.head_dim * cx.n_q_heads * cx.batch
+        calls = list(range(kx - 1, -1, -1)) if selected is None else list(selected)
+        lam = 1.0 if selected is None else kx / len(selected)
+
+        def sel_pairs(j):      # (row, col) pairs of call j whose columns lie in selected chunks
+            if selected is None:
+                return pairs(j, Cx)
+            return sum(Cx * Cx for i in selected if i < j) + Cx * (Cx + 1) // 2
+
+        alg = {"fwd": sum(4 * pairs(j, Cx) for j in calls) * pp, "dq": sum(6 * pairs(j, Cx) for j in calls) * pp,
+               "dkdv": sum(4 * sel_pairs(j) for j in calls) * pp}
+        total = sum(alg.values())
+
+        def stepx():
+            seco.kvgrad_zero(Lx.gk, Lx.gv)
+            for j in calls:
+                Lx.fwd(j)
+                Lx.bwd(j, None if selected is None else seco.spaco_chunk_weights(selected, j, lam))
+
+        for _ in range(warmup):
+            stepx()
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(steps):
+            stepx()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - a) * 1e3 / steps
+        seco.seco_profile_enable(True)
+        stepx()
+        torch.cuda.synchronize()
+        kp = seco.seco_profile_read()
+        seco.seco_profile_enable(False)
+        domx = max(alg, key=lambda kd: kp[kd][0])
+        tag = cx.name if selected is None else f"{cx.name}_spaco_t{len(selected)}"
+        res = {"workload": f"{cx.name}: " + ("SeCO fwd+bwd, all chunks" if selected is None else
+                                             f"Alg. 2 step, {len(selected)} of {kx} chunks selected {list(selected)}, factor {lam:g}"),
+               "seq_len": cx.seq_len, "chunk_len": Cx, "value": round(total / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+               "ms_per_step": round(ms, 4), "steps": steps, "warmup": warmup, "flops_per_step": total,
+               "pct_of_bf16_mfma_peak": round(100 * total / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+               "kernels": kernel_table(kp, alg, 1),
+               "roofline": roofline_of(tag, domx, alg[domx], kp[domx][0], kp[domx][1], 1,
+                                       "one extra step with HIP events around every launch")}
+        del Lx
+        torch.cuda.empty_cache()
+        return res
 
     def layer_seconds(cx):
         """Seconds per layer of configuration cx under the two schedules (Alg. 1: k forwards, then forward +
         backward per chunk in reverse order; Alg. 2: k forwards, then forward + backward for the t selected
         chunks with factor k/t), best of 3."""
-        Lx = Layer(cx.seq_len, cx.chunk_len)
+        Lx = Layer(cx)
         kx, tx = cx.n_chunks, cx.spaco_t
         sel = seco.spaco_select_chunks(cx.seed, 0, kx, tx)
         lam = kx / tx
@@ -292,7 +420,7 @@ def main():
                 Lx.fwd(j)
                 Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam))
 
-        lse_full = torch.empty(B, Hq, cx.seq_len, device=dev, dtype=torch.float32)
+        lse_full = torch.empty(cx.batch, cx.n_q_heads, cx.seq_len, device=dev, dtype=torch.float32)
         d_full = seco.binding.make_desc(Lx.q, Lx.kc, 0, scale, o=Lx.o)
         n_full = seco.seco_workspace_bytes(d_full, seco.binding.SECO_OP_FWD)
         ws_full = torch.empty(n_full, device=dev, dtype=torch.uint8) if n_full else False
@@ -338,7 +466,7 @@ def main():
             for j in sel:
                 Lx.bwd(j, seco.spaco_chunk_weights(sel, j, lam), seco.spaco_chunk_weights(sel, j, lam_q))
 
-        stats_t = torch.empty(2, B, Hq, (cx.seq_len + 3) // 4 * 4, device=dev, dtype=torch.float32)
+        stats_t = torch.empty(2, cx.batch, cx.n_q_heads, (cx.seq_len + 3) // 4 * 4, device=dev, dtype=torch.float32)
 
         def gather_bwd(j, row_weight=None):
             seco.seco_chunk_attn_bwd_gather(Lx.q[:, :, j * Lx.C:], Lx.kc, Lx.vc, Lx.rows(Lx.o, j), Lx.lse[j],
@@ -434,7 +562,7 @@ def main():
         visiting the selected chunks only (spaco_chunk_attn_bwd_sparse_dq, weight (k-1)/(t-1))."""
         Cx, tx, res = 2048, 8, {}
         for Nx in (16384, 32768, 65536):
-            Lx = Layer(Nx, Cx)
+            Lx = Layer(CONFIGS["cfg3"], seq_len=Nx)          # cfg3's shape: chunks of 2048
             kx = Nx // Cx
             sel = [kx - 1 - i * (kx // tx) for i in range(tx)]
             lam, lam_q = kx / tx, (kx - 1) / (tx - 1)
@@ -475,56 +603,75 @@ def main():
         # the two schedules on the benchmarked configuration itself
         out["sec_per_layer"] = dict(layer_seconds(cfg), seq_len=N, chunk_len=C)
 
+    if not args.no_other_workloads and cfg.dtype == "bf16" and not args.graph:
+        # the other workloads the target spans (16K and 64K tokens) and the Alg. 2 steps (t = 4 at 32K, t = 8 at 64K,
+        # seeded selections), each with its own whole-step TFLOP/s and the roofline of its dominant kernel
+        L = None
+        torch.cuda.empty_cache()
+        others = {}
+        for name in ("cfg2", "cfg3", "cfg4"):
+            if name != cfg.name:
+                others[name] = other_workload(CONFIGS[name])
+        for name in ("cfg3", "cfg4"):
+            cx = CONFIGS[name]
+            sel = seco.spaco_select_chunks(cx.seed, 0, cx.n_chunks, cx.spaco_t)
+            others[f"{name}_spaco_t{cx.spaco_t}"] = other_workload(cx, selected=sel)
+        out["other_workloads"] = others
+
     if not args.no_layer32k and cfg.dtype == "bf16":
         # seconds per 32K-token layer: 16 chunks of 2048, t = 4
-        del L
+        L = None
         torch.cuda.empty_cache()
         out["sec_per_32k_layer"] = layer_seconds(CONFIGS["cfg3"])
 
-    if not args.no_cpu_baseline:
-        # the oracle, as it stands, on one independent (batch, KV head) unit of the same workload
+    if oracle_units:
+        # The oracle, as it stands, on whole (batch, KV head) units of the same workload and the same arrays the GPU
+        # was given: the complete Alg. 1 loop of the unit (every forward and backward call), timed on the host cores;
+        # its results are then compared element by element with what the last timed GPU step left for that unit.
         from oracle import attention as A
-        from workloads import kv_group
         try:
             from threadpoolctl import threadpool_info
             cores = max((p.get("num_threads", 1) for p in threadpool_info()), default=1)
         except Exception:
             cores = len(os.sched_getaffinity(0))
-        n_time = min(k_chunks, 16)
-        chunks = list(range(k_chunks - 1, k_chunks - 1 - n_time, -1))
-        done = units = 0
-        fl = 0
-        el = 0.0
-        # whole (batch, KV head) units, one after the other, until about 10 s of oracle time have been spent
-        for kvh in range(Hkv):
-            grp = kv_group(cfg, 0, kvh)
-            q = grp["q"][None].astype(np.float64)
-            do = grp["do"][None].astype(np.float64)
-            kk = grp["k"][None, None].astype(np.float64)
-            vv = grp["v"][None, None].astype(np.float64)
+        unit_flops = 14 * sum(pairs(j, C) for j in range(k_chunks)) * D * G
+        el, done = 0.0, []
+        errs = {n: 0.0 for n in TOL[cfg.dtype]}
+        errs_floor = dict(errs)
+        for u in oracle_units:
+            if u in done:
+                continue
+            h = host_units[u]
+            xq, xdo = np.stack(h["q"])[None], np.stack(h["do"])[None]
+            xk, xv = h["k"][0][None, None], h["v"][0][None, None]
             t_unit = time.perf_counter()
-            for j in chunks:
-                qs = q[:, :, j * C:(j + 1) * C]
-                o_j, lse_j = A.chunk_attn_fwd(qs, kk, vv, j * C, scale)
-                A.chunk_attn_bwd(qs, kk, vv, o_j, lse_j, do[:, :, j * C:(j + 1) * C], j * C, scale)
-                done += 1
-                fl += 14 * pairs(j, C) * D * (Hq // Hkv)
-                if el + time.perf_counter() - t_unit > 25:
-                    break
-            unit_s = time.perf_counter() - t_unit
-            el += unit_s
-            units += 1
-            if el >= 10 or el + unit_s > 25:
+            ref = A.seco_layer(xq, xk, xv, xdo, C, scale)
+            el += time.perf_counter() - t_unit
+            done.append(u)
+            for n, r in zip(("o", "lse", "dq", "gk", "gv"), ref):
+                x = gpu_units[u][n]
+                top = max(np.abs(r).max(), 1e-30)
+                errs[n] = max(errs[n], float(np.abs(x - r).max() / top))
+                errs_floor[n] = max(errs_floor[n], float((np.abs(x - r) / np.maximum(np.abs(r), 1e-3 * top)).max()))
+            if el >= 10:          # bounded: about 10 - 30 s of oracle time
                 break
-        out["cpu_baseline"] = {"value": round(fl / el / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-                               "sample": f"fp64 NumPy oracle, fwd+bwd of {done} chunk calls (the last {n_time} chunks of "
-                                         f"{units} (batch, KV head) unit(s) of {cfg.name}, {Hq // Hkv} query heads each), "
-                                         f"{el:.1f} s",
+        out["cpu_baseline"] = {"value": round(unit_flops * len(done) / el / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": int(cores), "kind": "oracle",
+                               "sample": f"fp64 NumPy oracle, the whole Alg. 1 loop (forward + backward of all {k_chunks} "
+                                         f"chunks) of {len(done)} of the {B * Hkv} (batch, KV head) units of {cfg.name} "
+                                         f"{done}, {G} query heads each, {el:.1f} s",
                                "host_cores_available": len(os.sched_getaffinity(0))}
+        tol = TOL[cfg.dtype]
+        out["parity"] = {"against": "the oracle's results for the units above, same host arrays on both sides, GPU "
+                                    "outputs of the last timed step, every element of the units",
+                         "units": [list(u) for u in done],
+                         "max_rel_err": {n: float(f"{e:.3e}") for n, e in errs.items()},
+                         "max_elementwise_rel_err_floor_1e-3": {n: float(f"{e:.3e}") for n, e in errs_floor.items()},
+                         "tolerance": tol, "pass": all(errs[n] <= tol[n] for n in tol)}
 
     if args.hbm_kernels:
         # the HBM-bound helpers on this configuration's buffers: bytes moved / time against the 8 TB/s of HBM3E
-        Lh = Layer(N, C)
+        Lh = Layer(cfg)
         j = k_chunks - 1
         knew = torch.randn(B, C, Hkv, D, device=dev).to(tdt).transpose(1, 2)
         dk = torch.empty(B, C, Hkv, D, device=dev, dtype=tdt).transpose(1, 2)

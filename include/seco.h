@@ -78,8 +78,8 @@ typedef struct seco_desc {
   float softmax_scale;    /* s > 0, normally 1/sqrt(head_dim) */
   int64_t q_stride[3];    /* Q and dQ  : (batch, head, row) strides in elements */
   int64_t o_stride[3];    /* O and dO  */
-  int64_t kv_stride[3];   /* K and V cache (row index = global position) */
-  int64_t g_stride[3];    /* gK and gV, fp32 (row index = global position) */
+  int64_t kv_stride[3];   /* K and V cache (row index = global position); ONE triple: V must be laid out like K */
+  int64_t g_stride[3];    /* gK and gV, fp32 (row index = global position); ONE triple: gV laid out like gK */
 } seco_desc;
 
 /*
@@ -89,7 +89,7 @@ typedef struct seco_desc {
  * q        in   [B, Hq, C, D]   (q_stride)
  * k_cache  in   [B, Hkv, >= q_start + C, D]   (kv_stride); v_cache alike
  * o        out  [B, Hq, C, D]   (o_stride), overwritten
- * lse      out  fp32 [B, Hq, C] contiguous, overwritten
+ * lse      out  fp32 [B, Hq, C] contiguous (no strides are taken for it: a sliced view is not accepted), overwritten
  * ws       optional workspace, 256-byte aligned.  seco_workspace_bytes(desc, SECO_OP_FWD) is non-zero only for
  *          bf16 calls with so few query rows that the row tiles cannot fill the GPU (short chunks, as in the
  *          chunk-size study of Sec. 6.3); given at least that many bytes, the visible cache rows are divided
@@ -267,7 +267,7 @@ int rope_rotate(const seco_desc* desc, int32_t n_heads, const void* x_in, void* 
                 float rope_base, int32_t inverse, void* hip_stream);
 
 /*
- * SpaCO chunk selection (Alg. 2: "randomly select t distinct indices"), host only.
+ * SpaCO chunk selection (Alg. 2, selection step: t different chunks out of k, uniformly), host only.
  * Deterministic in (seed, step): SplitMix64 stream keyed by (seed, step), unbiased bounded
  * draws by rejection, first t steps of a Fisher-Yates shuffle of 0..k-1, result sorted in
  * DESCENDING order (the order in which the chunks have to be back-propagated).
@@ -310,6 +310,16 @@ float spaco_compensation_factor(int32_t k, int32_t t, float cap);
  * selected_host: n_selected chunk indices (any order); w_host: j + 1 floats, overwritten.
  */
 int spaco_chunk_weights(const int32_t* selected_host, int32_t n_selected, int32_t j, float factor, float* w_host);
+
+/*
+ * Row weights of spaco_chunk_attn_bwd_gather for selected chunk i of k under the paper's policy (Alg. 2 with the
+ * factor of Sec. 5), host only: one weight per chunk of query rows from chunk i on,
+ *   w[0] = 1 (the chunk's own rows), w[m - i] = factor for a selected chunk m > i, 0 for every other chunk,
+ * i.e. the transpose of spaco_chunk_weights: call m of the accumulating order puts `factor` on chunk i exactly
+ * when m is selected.  selected_host: n_selected chunk indices (any order); w_host: k - i floats, overwritten.
+ */
+int spaco_gather_row_weights(const int32_t* selected_host, int32_t n_selected, int32_t i, int32_t k, float factor,
+                             float* w_host);
 
 /*
  * Optional per-kernel timing, for benchmarks (not part of the method).  While enabled, every

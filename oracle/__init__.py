@@ -10,7 +10,7 @@ Contents
   attention.py  chunked causal attention forward / backward and the SeCO and
                 SpaCO per-layer schedules (Eq. 1, Alg. 1, Alg. 2), in two
                 tiers: scalar loops ("loops") and NumPy fp64 matmuls ("matmul")
-  selection.py  SpaCO chunk selection (Alg. 2, "select t distinct indices"),
+  selection.py  SpaCO chunk selection (Alg. 2, selection step: t different chunks of k),
                 compensation factor (Sec. 5 "Compensation Factor", Sec. 6.4 cap)
                 and the per-call chunk weight vector
   model.py      Alg. 1 and Alg. 2 over a small multi-layer decoder (torch fp64 autograd per chunk, the

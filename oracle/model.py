@@ -4,7 +4,7 @@ TEST INFRASTRUCTURE ONLY (see the package docstring).  fp64 PyTorch on the CPU; 
 supplies the per-layer derivatives, this file supplies the schedules of the paper:
 
   * `monolithic_grads`  - ordinary training step on the whole sequence: the reference the
-    paper compares SeCO with (Sec. 4, "match those from naive parallel training");
+    paper compares SeCO with (Sec. 4: the exactness claim, gradients equal to whole-sequence training);
   * `seco_grads`        - Alg. 1: stage 1 runs the chunks in inference mode and keeps the KV
     caches m'_1..m'_k of every layer as checkpoints; stage 2 rebuilds each chunk's graph in
     reverse order against those checkpoints, hands the gradient collected on m'_i over to

@@ -2,7 +2,7 @@
 
 TEST INFRASTRUCTURE ONLY (see the package docstring).
 
-Alg. 2 draws "t distinct indices" out of the k chunks but names no generator.
+Alg. 2 draws t different chunks out of the k (selection step) but names no generator.
 This build fixes one so that the host library and this oracle can be compared
 bit for bit:
 
@@ -96,6 +96,20 @@ def chunk_weights(selected, j, factor):
         if i < j:
             w[int(i)] = factor
     w[j] = 1.0
+    return w
+
+
+def gather_row_weights(selected, i, k, factor):
+    """Row weights of the backward call for selected chunk i when the calls run in the transposed order (each call
+    forms the finished gradient rows of its own chunk from its own and every later chunk's queries): one weight per
+    chunk i .. k-1, 1 for chunk i itself, `factor` for a later selected chunk, 0 otherwise.  This is Alg. 2's
+    weighting read column by column: call m deposits `factor` on an earlier selected chunk i (chunk_weights(sel, m)[i])
+    exactly when m itself is back-propagated.  fp32."""
+    w = np.zeros(k - i, dtype=np.float32)
+    for m in selected:
+        if i < m < k:
+            w[int(m) - i] = factor
+    w[0] = 1.0
     return w
 
 

@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     spaco_chunk_attn_bwd,
     spaco_chunk_weights,
     spaco_compensation_factor,
+    spaco_gather_row_weights,
     spaco_percall_weights,
     spaco_select_bernoulli,
     spaco_select_chunks,

@@ -71,6 +71,8 @@ def load_library():
     lib.kv_append_rope.restype = lib.kvgrad_readout_rope.restype = lib.rope_rotate.restype = C.c_int
     lib.spaco_select_chunks.argtypes = [C.c_uint64, C.c_uint64, i32, i32, C.POINTER(i32)]
     lib.spaco_chunk_weights.argtypes = [C.POINTER(i32), i32, i32, C.c_float, C.POINTER(C.c_float)]
+    lib.spaco_gather_row_weights.argtypes = [C.POINTER(i32), i32, i32, i32, C.c_float, C.POINTER(C.c_float)]
+    lib.spaco_gather_row_weights.restype = C.c_int
     lib.spaco_percall_weights.argtypes = [C.c_uint64, C.c_uint64, i32, i32, C.POINTER(C.c_float)]
     lib.spaco_percall_weights.restype = C.c_int
     lib.spaco_select_bernoulli.argtypes = [C.c_uint64, C.c_uint64, i32, C.c_double, C.POINTER(i32), C.POINTER(i32)]
@@ -146,6 +148,21 @@ def _ptr(t):
     return C.c_void_p(t.data_ptr()) if t is not None else None
 
 
+def _check_shared(k_cache, v_cache, gk=None, gv=None, lse=None):
+    """The descriptor carries ONE stride triple for K and V and one for gK and gV, and the kernels index LSE as a
+    contiguous fp32 [B, Hq, C] array: refuse tensors that do not fit that instead of computing on wrong addresses."""
+    import torch
+    if v_cache.stride() != k_cache.stride() or v_cache.shape != k_cache.shape:
+        raise ValueError("k_cache and v_cache must share shape and strides")
+    if gk is not None and gv is not None and (gv.stride() != gk.stride() or gv.shape != gk.shape):
+        raise ValueError("gk and gv must share shape and strides")
+    for g in (gk, gv):
+        if g is not None and g.dtype != torch.float32:
+            raise TypeError("gk / gv must be float32")
+    if lse is not None and (lse.dtype != torch.float32 or not lse.is_contiguous()):
+        raise ValueError("lse must be a contiguous float32 [B, Hq, C] tensor")
+
+
 def seco_workspace_bytes(desc, op):
     n = load_library().seco_workspace_bytes(C.byref(desc), int(op))
     if n == C.c_size_t(-1).value:
@@ -170,6 +187,9 @@ def seco_chunk_attn_fwd(q, k_cache, v_cache, q_start, scale, o=None, lse=None, s
         o = torch.empty_like(q)
     if lse is None:
         lse = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
+    if tuple(lse.shape) != tuple(q.shape[:3]):
+        raise ValueError("lse must have shape [B, Hq, C]")
+    _check_shared(k_cache, v_cache, lse=lse)
     d = make_desc(q, k_cache, q_start, scale, o=o)
     if ws is False:            # explicitly none: the library then takes the direct path
         ws = None
@@ -189,6 +209,7 @@ def seco_chunk_attn_bwd(q, k_cache, v_cache, o, lse, d_o, gk, gv, q_start, scale
         d_q = torch.empty_strided(q.size(), q.stride(), dtype=q.dtype, device=q.device)
     if o.stride() != d_o.stride() or q.stride() != d_q.stride():
         raise ValueError("o/d_o and q/d_q must share strides")
+    _check_shared(k_cache, v_cache, gk, gv, lse)
     d = make_desc(q, k_cache, q_start, scale, o=o, g=gk)
     if ws is None:
         ws, _ = _workspace(d, SECO_OP_BWD, q)
@@ -209,6 +230,7 @@ def spaco_chunk_attn_bwd(q, k_cache, v_cache, o, lse, d_o, gk, gv, q_start, scal
         d_q = torch.empty_strided(q.size(), q.stride(), dtype=q.dtype, device=q.device)
     if o.stride() != d_o.stride() or q.stride() != d_q.stride():
         raise ValueError("o/d_o and q/d_q must share strides")
+    _check_shared(k_cache, v_cache, gk, gv, lse)
     d = make_desc(q, k_cache, q_start, scale, o=o, g=gk)
     if ws is None:
         ws, _ = _workspace(d, SECO_OP_BWD, q)
@@ -243,6 +265,7 @@ def seco_chunk_attn_bwd_gather(q_rows, k_cache, v_cache, o, lse, d_o_rows, gk, g
         d_q = torch.empty_strided(qc.size(), qc.stride(), dtype=qc.dtype, device=qc.device)
     if o.stride() != doc.stride() or qc.stride() != d_q.stride():
         raise ValueError("o/d_o and q/d_q must share strides")
+    _check_shared(k_cache, v_cache, gk, gv, lse)
     if row_stats.dtype != torch.float32 or not row_stats.is_contiguous() or row_stats.dim() != 4:
         raise ValueError("row_stats must be a contiguous fp32 [2, B, Hq, stat_rows] tensor")
     d = make_desc(qc, k_cache, q_start, scale, o=o, g=gk)
@@ -395,6 +418,15 @@ def spaco_chunk_weights(selected, j, factor):
     sel = (C.c_int32 * max(len(selected), 1))(*[int(i) for i in selected])
     w = (C.c_float * (int(j) + 1))()
     _check(load_library().spaco_chunk_weights(sel, len(selected), int(j), float(factor), w), "spaco_chunk_weights")
+    return list(w)
+
+
+def spaco_gather_row_weights(selected, i, k, factor):
+    """Row weights w[0 .. k-i) of the transposed-order backward call for selected chunk i of k (list of float)."""
+    sel = (C.c_int32 * max(len(selected), 1))(*[int(x) for x in selected])
+    w = (C.c_float * (int(k) - int(i)))() if k > i else (C.c_float * 1)()
+    _check(load_library().spaco_gather_row_weights(sel, len(selected), int(i), int(k), float(factor), w),
+           "spaco_gather_row_weights")
     return list(w)
 
 

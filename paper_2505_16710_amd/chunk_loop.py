@@ -89,7 +89,7 @@ class ChunkAttention(torch.autograd.Function):
             if st.gather_rows is not None:      # Alg. 2: 1 on the chunk's own rows, the factor on later selected chunks
                 sel, factor, wlen, k = st.gather_rows
                 j = s0 // wlen
-                row_w = [1.0 if i == j else (factor if i in sel else 0.0) for i in range(j, k)]
+                row_w = _b.spaco_gather_row_weights(sel, j, k, factor)
             d_q = _b.seco_chunk_attn_bwd_gather(q_all[:, :, s0:], st.k, st.v, o_all[:, :, s0:s0 + C], lse,
                                                 do_all[:, :, s0:], st.gk, st.gv, s0, ctx.scale, C, stats,
                                                 d_q=dq_all[:, :, s0:s0 + C], row_weight=row_w,

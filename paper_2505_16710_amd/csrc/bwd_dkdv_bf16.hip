@@ -7,7 +7,7 @@
 //
 // The workgroup has 8 wavefronts: 4 column blocks of 32 cache rows x 2 roles.
 //   role A ("probabilities"): keeps K^T fragments and the dV accumulator; computes
-//          S = Q K^T, P = exp(S - LSE) (causal mask applied), hands P (bf16) to its partner
+//          S = Q K^T, P = exp(s S - LSE) (causal mask applied), hands P (bf16) to its partner
 //          through LDS and accumulates dV += P^T dO;
 //   role B ("score gradient"): keeps V^T fragments and the dK accumulator; computes
 //          dP = dO V^T, dS = P * (dP - delta) and accumulates dK += dS^T Q.
@@ -119,15 +119,12 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   bf16x8 frag[8];
 #pragma unroll
   for (int t = 0; t < 8; ++t) frag[t] = *reinterpret_cast<const bf16x8*>(fptr + 16 * t + 8 * g);
-  // Role A folds the softmax scale and the change to base 2 into its K^T fragments (one rounding to bf16, once
-  // per workgroup), so that its MFMA chains, started from -LSE instead of zero, deliver log2 P directly; role B
-  // starts its chains from -delta.  Neither needs a subtraction or a multiply-add per score afterwards.
-  if (role == 0) {
-#pragma unroll
-    for (int t = 0; t < 8; ++t)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) frag[t][i] = (__bf16)((float)frag[t][i] * (p.scale * kLog2e));
-  }
+  // Role A starts its MFMA chains from -LSE / s instead of zero, so that a chain delivers q.k - LSE / s and
+  // P = exp2(c * that) with c = s * log2(e): one multiply per score, in fp32.  (Folding c into the K^T fragments
+  // would save that multiply but round K a second time, to bf16: with scores far from zero, as with the outlier
+  // components of trained models, P = exp(S - LSE) hangs on the low-order bits of S, and the extra rounding showed
+  // as errors of several per cent in gV and gK.)  Role B starts its chains from -delta.
+  const float c2 = p.scale * kLog2e;
 
   // query-row stages that see at least one cache row of this workgroup; iteration = (head of the group, stage)
   const int rt0 = max(0, c0 - p.q_start) / BQ;
@@ -193,7 +190,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       }
     }
   };
-  // -LSE (in log2 units) and -delta of the stage's rows, as the dQ kernel left them in the workspace: one
+  // -LSE / s and -delta of the stage's rows, as the dQ kernel left them in the workspace: one
   // asynchronous 64-lane copy each (wavefronts 0 and 1), straight into the stage's slot.  The last, ragged stage
   // of a head goes through registers instead: rows past the chunk get -LSE = -inf so that their probabilities vanish.
   static_assert(BQ == 64, "one 64-lane copy per row statistic");
@@ -247,9 +244,9 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
     }
   };
 
-  // role A: S = Q K^T for row block rb of the stage in `slot`, P = exp2(S*c - LSE) with the causal mask;
+  // role A: S = Q K^T for row block rb of the stage in `slot`, P = exp2(c2 * (S - LSE / s)) with the causal mask;
   // P goes to pbuf as two operand halves (lane-contiguous 16-byte words)
-  auto scores = [&](int slot, int parity, int r0, int rb, float lw) {   // lw: log2 of the rows' weight
+  auto scores = [&](int slot, int parity, int r0, int rb, float lw) {   // lw: log2 of the rows' weight, divided by c2
     lds_char* qt = smem + slot * kStageBytes;
     SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + 32 * rb;
     bf16x8 a[8];
@@ -265,7 +262,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
     for (int t = 0; t < 8; ++t) s = mfma(a[t], frag[t], s);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r]);
+    for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r] * c2);
     mask_above_diagonal(s, p.q_start + r0 + 32 * rb);
     lds_char* pb = pslot(parity, rb);
     *reinterpret_cast<SECO_LDS bf16x8*>(pb + lane * 16) = pack8(s, 0);
@@ -286,7 +283,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   __syncthreads();
   if (role == 0) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) scores(0, 0, cur.r0, rb, ROWS ? rr.log2w[cur.ri] : 0.f);
+    for (int rb = 0; rb < RB; ++rb) scores(0, 0, cur.r0, rb, ROWS ? rr.log2w[cur.ri] / c2 : 0.f);
   }
   __syncthreads();
   Pos nxt2 = advance(nxt);
@@ -343,7 +340,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
       for (int r = 0; r < 16; ++r) s1[r] = lse_s[32 + 8 * (r >> 2) + 4 * g + (r & 3)];
       if constexpr (ROWS) {                   // probabilities of the next stage's rows carry their run's weight
-        const float lw = rr.log2w[nxt.ri];
+        const float lw = rr.log2w[nxt.ri] / c2;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           s0[r] += lw;
@@ -361,8 +358,8 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       for (int t = 0; t < 8; ++t) {
         s1 = mfma(x[t], frag[t], s1);
         x[t] = lds_tr8_at(dot, t_off[t & 3], 32 + 16 * (t >> 2));
-        s0[2 * t] = fast_exp2(s0[2 * t]);
-        s0[2 * t + 1] = fast_exp2(s0[2 * t + 1]);
+        s0[2 * t] = fast_exp2(s0[2 * t] * c2);
+        s0[2 * t + 1] = fast_exp2(s0[2 * t + 1] * c2);
       }
       mask_above_diagonal(s0, p.q_start + nxt.r0);
       const bf16x8 pn0[2] = {pack8(s0, 0), pack8(s0, 1)};
@@ -375,8 +372,8 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       for (int i = 0; i < 8; ++i) {
         acc[i & 3] = mfma(pa1[i >> 2], x[i], acc[i & 3]);
         x[i] = lds_tr8_at(dot1, t_off[i & 3], 16 * (i >> 2));
-        s1[2 * i] = fast_exp2(s1[2 * i]);
-        s1[2 * i + 1] = fast_exp2(s1[2 * i + 1]);
+        s1[2 * i] = fast_exp2(s1[2 * i] * c2);
+        s1[2 * i + 1] = fast_exp2(s1[2 * i + 1] * c2);
       }
       mask_above_diagonal(s1, p.q_start + nxt.r0 + 32);
       pa0[0] = pn0[0];

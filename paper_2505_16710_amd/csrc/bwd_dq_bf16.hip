@@ -87,8 +87,8 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, SegT
   const float lse_c = p.lse[stat] * kLog2e;
   // delta = rowsum(dO * O) is computed here, from the dO fragments already in registers and the matching O
   // fragments: a lane holds half of its row's head_dim (the other half is in lane ^ 32).  It is also written to
-  // the workspace for the dK/dV kernel that follows on the same stream, negated, together with -LSE in log2 units:
-  // the two values that kernel starts its MFMA chains from.
+  // the workspace for the dK/dV kernel that follows on the same stream, negated, together with -LSE / s (the
+  // log-sum-exp in units of the unscaled dot product): the two values that kernel starts its MFMA chains from.
   float delta = 0.f;
   {
     const __bf16* optr = static_cast<const __bf16*>(p.o) + b * p.os[0] + h * p.os[1] + (int64_t)crow * p.os[2];
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, SegT
     if (kh == 0 && sp == 0 && g == 0 && row < p.C) {
       const int64_t kept = ((int64_t)b * p.Hq + h) * p.stat_stride + p.stat_off + crow;
       p.delta[kept] = -delta;
-      p.nlse2[kept] = -lse_c;
+      p.nlse2[kept] = -p.lse[stat] / p.scale;
     }
   }
   const float c = p.scale * kLog2e;

@@ -272,14 +272,22 @@ int launch_readout(void* oa, void* ob, const float* ga, const float* gb, float s
 // (i, i + D/2), theta_i = pos * base^(-2 i / D).  Work item = 4 consecutive i of one row (both halves); angles and
 // sines in fp64, one rounding of the result.  In / out element types are template parameters so that the same
 // kernel serves the cache append (storage type -> storage type, rows at r0 of the destination), the gradient
-// read-out (fp32 -> storage type, rows at r0 of the source) and the plain rotation.
+// read-out (fp32 -> storage type, rows at r0 of the source) and the plain rotation.  A second tensor pair with the
+// same strides (the values of an append, the value gradient of a read-out) rides along as blockIdx.y == 1: the same
+// rows, scaled and converted but not rotated, so that keys and values take one pass and one launch.
 template <typename TIn, typename TOut>
-__global__ __launch_bounds__(256) void rope_rows_kernel(TOut* out, const TIn* in, int H, int C,   // (out may be in)
+__global__ __launch_bounds__(256) void rope_rows_kernel(TOut* out, const TIn* in, TOut* plain_out, const TIn* plain_in,
+                                                        int H, int C,   // (out may be in)
                                                         int D, int64_t os0, int64_t os1, int64_t os2, int64_t is0,
                                                         int64_t is1, int64_t is2, int64_t out_r0, int64_t in_r0,
                                                         int64_t pos0, double log2_base, float sign, float scale,
-                                                        int64_t total) {
+                                                        int plain_from, int64_t total) {
   const int q4 = D / 8;                                   // groups of 4 pairs per row
+  const bool plain = (int)blockIdx.y >= plain_from;       // plain_from: 1 with a rotated pair present, else 0
+  if (plain) {
+    out = plain_out;
+    in = plain_in;
+  }
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
     const int grp = (int)(i % q4);
     int64_t t = i / q4;
@@ -293,6 +301,14 @@ __global__ __launch_bounds__(256) void rope_rows_kernel(TOut* out, const TIn* in
     for (int j = 0; j < 4; ++j) {
       lo[j] = (float)src[j] * scale;
       hi[j] = (float)src[D / 2 + j] * scale;
+    }
+    if (plain) {                                          // (uniform over the workgroup)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        dst[j] = (TOut)lo[j];
+        dst[D / 2 + j] = (TOut)hi[j];
+      }
+      continue;
     }
     const double pos = (double)(pos0 + row);
 #pragma unroll
@@ -308,20 +324,23 @@ __global__ __launch_bounds__(256) void rope_rows_kernel(TOut* out, const TIn* in
   }
 }
 
-int launch_rope_rows(void* out, const void* in, int in_kind, int out_kind, int B, int H, int C, int D,
-                     const int64_t out_s[3], const int64_t in_s[3], int64_t out_r0, int64_t in_r0, int64_t pos0,
-                     float base, bool inverse, float scale, hipStream_t s) {
+int launch_rope_rows(void* out, const void* in, void* plain_out, const void* plain_in, int in_kind, int out_kind, int B,
+                     int H, int C, int D, const int64_t out_s[3], const int64_t in_s[3], int64_t out_r0, int64_t in_r0,
+                     int64_t pos0, float base, bool inverse, float scale, hipStream_t s) {
   const int64_t total = (int64_t)B * H * C * (D / 8);
-  if (total == 0 || !out) return SECO_OK;
+  if (total == 0 || (!out && !plain_out)) return SECO_OK;
   const double l2b = log2((double)base);
   const float sign = inverse ? -1.f : 1.f;
   {
     ProfScope prof(kKernelKvgrad, s);
-    const dim3 grid(grid_for(total));
+    // grid.y: one slice of workgroups per tensor pair present (the rotated pair first)
+    const int plain_from = out ? 1 : 0;
+    const dim3 grid(grid_for(total), (out ? 1u : 0u) + (plain_out ? 1u : 0u));
 #define SECO_ROPE_LAUNCH(TI, TO)                                                                                       \
   hipLaunchKernelGGL((rope_rows_kernel<TI, TO>), grid, dim3(256), 0, s, static_cast<TO*>(out),                         \
-                     static_cast<const TI*>(in), H, C, D, out_s[0], out_s[1], out_s[2], in_s[0], in_s[1], in_s[2],      \
-                     out_r0, in_r0, pos0, l2b, sign, scale, total)
+                     static_cast<const TI*>(in), static_cast<TO*>(plain_out), static_cast<const TI*>(plain_in), H, C,   \
+                     D, out_s[0], out_s[1], out_s[2], in_s[0], in_s[1], in_s[2], out_r0, in_r0, pos0, l2b, sign,        \
+                     scale, plain_from, total)
     if (in_kind == SECO_BF16 && out_kind == SECO_BF16) SECO_ROPE_LAUNCH(__bf16, __bf16);
     else if (in_kind == SECO_F32 && out_kind == SECO_BF16) SECO_ROPE_LAUNCH(float, __bf16);
     else SECO_ROPE_LAUNCH(float, float);

@@ -542,13 +542,11 @@ extern "C" int kv_append_rope(const seco_desc* desc, const void* k_new, const vo
     if (ptr && !aligned16(ptr)) return SECO_ERR_ALIGN;
   const int eb = desc->dtype == SECO_BF16 ? 2 : 4;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (k_new &&
-      (rc = launch_rope_rows(k_cache, k_new, desc->dtype, desc->dtype, desc->batch, desc->n_kv_heads, desc->chunk_len,
-                             desc->head_dim, desc->kv_stride, desc->q_stride, desc->q_start, 0, desc->q_start, rope_base,
-                             false, 1.f, s)))
-    return rc;
-  return launch_rows_copy(v_cache, nullptr, v_new, nullptr, eb, desc->batch, desc->n_kv_heads, desc->chunk_len,
-                          desc->head_dim, desc->kv_stride, desc->q_stride, desc->q_start, s);
+  (void)eb;
+  // one launch: the keys rotated, the values copied (scale 1 and equal types: the conversion is the identity)
+  return launch_rope_rows(k_cache, k_new, v_cache, v_new, desc->dtype, desc->dtype, desc->batch, desc->n_kv_heads,
+                          desc->chunk_len, desc->head_dim, desc->kv_stride, desc->q_stride, desc->q_start, 0,
+                          desc->q_start, rope_base, false, 1.f, s);
 }
 
 extern "C" int kvgrad_readout_rope(const seco_desc* desc, const float* gk, const float* gv, void* d_k_new,
@@ -562,12 +560,11 @@ extern "C" int kvgrad_readout_rope(const seco_desc* desc, const float* gk, const
     if (ptr && !aligned16(ptr)) return SECO_ERR_ALIGN;
   const bool bf16 = desc->dtype == SECO_BF16;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (gk && (rc = launch_rope_rows(d_k_new, gk, SECO_F32, desc->dtype, desc->batch, desc->n_kv_heads, desc->chunk_len,
-                                   desc->head_dim, desc->q_stride, desc->g_stride, 0, desc->q_start, desc->q_start,
-                                   rope_base, true, scaler, s)))
-    return rc;
-  return launch_readout(d_v_new, nullptr, gv, nullptr, scaler, bf16, desc->batch, desc->n_kv_heads, desc->chunk_len,
-                        desc->head_dim, desc->q_stride, desc->g_stride, desc->q_start, s);
+  (void)bf16;
+  // one launch: the key gradient scaled and turned back, the value gradient scaled
+  return launch_rope_rows(d_k_new, gk, d_v_new, gv, SECO_F32, desc->dtype, desc->batch, desc->n_kv_heads,
+                          desc->chunk_len, desc->head_dim, desc->q_stride, desc->g_stride, 0, desc->q_start,
+                          desc->q_start, rope_base, true, scaler, s);
 }
 
 extern "C" int rope_rotate(const seco_desc* desc, int32_t n_heads, const void* x_in, void* x_out, int64_t pos_start,
@@ -581,7 +578,7 @@ extern "C" int rope_rotate(const seco_desc* desc, int32_t n_heads, const void* x
   if (!x_in || !x_out) return SECO_ERR_NULL;
   if (!aligned16(x_in) || !aligned16(x_out)) return SECO_ERR_ALIGN;
   if (n_heads < 1 || n_heads > 65535 || pos_start < 0 || pos_start > ((int64_t)1 << 40)) return SECO_ERR_RANGE;
-  return launch_rope_rows(x_out, x_in, desc->dtype, desc->dtype, desc->batch, n_heads, desc->chunk_len, desc->head_dim,
+  return launch_rope_rows(x_out, x_in, nullptr, nullptr, desc->dtype, desc->dtype, desc->batch, n_heads, desc->chunk_len, desc->head_dim,
                           desc->o_stride, desc->q_stride, 0, 0, pos_start, rope_base, inverse != 0, 1.f,
                           static_cast<hipStream_t>(hip_stream));
 }

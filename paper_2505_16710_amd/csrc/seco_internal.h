@@ -17,7 +17,7 @@ struct AttnParams {
   void* d_q;
   float* lse;        // [B, Hq, C] contiguous
   float* delta;      // [B, Hq, stat_stride], backward only: rowsum(dO * O); NEGATED on the bf16 path
-  float* nlse2;      // bf16 backward: -LSE * log2(e), [B, Hq, stat_stride], written by the dQ kernel for the dK/dV kernel
+  float* nlse2;      // bf16 backward: -LSE / scale, [B, Hq, stat_stride], written by the dQ kernel for the dK/dV kernel
   int stat_stride;   // rows per (batch, head) of delta / nlse2: C (workspace of one call), or the length of
   int stat_off;      // arrays kept for the whole sequence, in which this call's first query row sits at stat_off
   float* gk;
@@ -146,10 +146,12 @@ int launch_readout(void* oa, void* ob, const float* ga, const float* gb, float s
                    int D, const int64_t out_s[3], const int64_t gs[3], int64_t r0, hipStream_t s);
 
 // out rows [out_r0, out_r0 + C) <- rotary embedding (or its inverse) of scale * in rows [in_r0, in_r0 + C), row r at
-// position pos0 + r; in_kind / out_kind: SECO_F32 or SECO_BF16 (bf16 -> f32 is not needed and not provided)
-int launch_rope_rows(void* out, const void* in, int in_kind, int out_kind, int B, int H, int C, int D,
-                     const int64_t out_s[3], const int64_t in_s[3], int64_t out_r0, int64_t in_r0, int64_t pos0,
-                     float base, bool inverse, float scale, hipStream_t s);
+// position pos0 + r; in_kind / out_kind: SECO_F32 or SECO_BF16 (bf16 -> f32 is not needed and not provided).
+// plain_out / plain_in: a second pair with the same strides and row ranges that is scaled and converted but not
+// rotated, in the same launch; either pair may be NULL (skipped).
+int launch_rope_rows(void* out, const void* in, void* plain_out, const void* plain_in, int in_kind, int out_kind, int B,
+                     int H, int C, int D, const int64_t out_s[3], const int64_t in_s[3], int64_t out_r0, int64_t in_r0,
+                     int64_t pos0, float base, bool inverse, float scale, hipStream_t s);
 
 // Optional per-kernel timing (seco_profile_enable): a scope brackets one launch with HIP events
 // on the launch stream.  Disabled by default; then a scope costs one branch.

@@ -1,5 +1,5 @@
-// Host-only parts of the C ABI: SpaCO chunk selection (Alg. 2, "randomly select t
-// distinct indices"), the per-call chunk weight vector (Alg. 2 with the compensation
+// Host-only parts of the C ABI: SpaCO chunk selection (Alg. 2, selection step: t different
+// chunks of k, uniformly), the per-call chunk weight vector (Alg. 2 with the compensation
 // factor of Sec. 5), and status strings.
 #include <algorithm>
 #include <cmath>
@@ -102,6 +102,20 @@ extern "C" int spaco_chunk_weights(const int32_t* selected_host, int32_t n_selec
   for (int32_t i = 0; i < n_selected; ++i)
     if (selected_host[i] < j) w_host[selected_host[i]] = factor;
   w_host[j] = 1.f;
+  return SECO_OK;
+}
+
+extern "C" int spaco_gather_row_weights(const int32_t* selected_host, int32_t n_selected, int32_t i, int32_t k,
+                                        float factor, float* w_host) {
+  if (!w_host || (n_selected > 0 && !selected_host)) return SECO_ERR_NULL;
+  if (i < 0 || k <= i || n_selected < 0) return SECO_ERR_RANGE;
+  for (int32_t n = 0; n < n_selected; ++n)
+    if (selected_host[n] < 0) return SECO_ERR_RANGE;
+  // the transpose of spaco_chunk_weights: what call m > i deposits on chunk i carries the factor iff m is selected
+  std::fill(w_host, w_host + (k - i), 0.f);
+  for (int32_t n = 0; n < n_selected; ++n)
+    if (selected_host[n] > i && selected_host[n] < k) w_host[selected_host[n] - i] = factor;
+  w_host[0] = 1.f;
   return SECO_OK;
 }
 

@@ -65,3 +65,25 @@ def run_layer(x, chunk_len, scale, dtype, selected=None, factor=1.0, weights_fn=
 def max_rel(x, ref):
     """max |x - ref| / max |ref| per tensor."""
     return float(np.abs(x - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def max_rel_per_head(x, ref):
+    """The same error normalised per (batch, head) slice, worst slice: a head (or a KV head's gradient rows) of small
+    magnitude cannot hide behind a large one.  Slices whose reference is identically zero must be zero."""
+    x, ref = np.asarray(x, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    if x.ndim < 3:
+        return max_rel(x, ref)
+    ax = tuple(range(2, x.ndim))
+    err = np.abs(x - ref).max(axis=ax)
+    top = np.abs(ref).max(axis=ax)
+    if (top == 0).any():
+        assert not err[top == 0].any()
+        top = np.where(top == 0, 1.0, top)
+    return float((err / top).max())
+
+
+def max_rel_floor(x, ref, floor=1e-3):
+    """Element-wise relative error with an absolute floor: max |x - ref| / max(|ref|, floor * max |ref|)."""
+    x, ref = np.asarray(x, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    den = np.maximum(np.abs(ref), floor * max(np.abs(ref).max(), 1e-30))
+    return float((np.abs(x - ref) / den).max())

@@ -157,6 +157,24 @@ def test_chunk_weights_match_oracle():
     assert lib.spaco_chunk_weights(None, 2, 1, 1.0, w) == -1
 
 
+def test_gather_row_weights_match_oracle_and_are_the_transpose_of_the_chunk_weights():
+    """Row weights of the transposed-order call for chunk i: library == oracle, and entry m - i equals what
+    chunk_weights of call m puts on chunk i whenever call m takes place (m selected), 0 when it does not."""
+    for sel, k, lam in (([3, 2, 0], 4, 4 / 3), ([5], 6, 8.0), ([7, 4, 1], 8, 3.0), ([9, 8, 7, 2], 10, 2.5), ([0], 3, 3.0)):
+        for i in sel:
+            want = S.gather_row_weights(sel, i, k, np.float32(lam))
+            got = np.array(seco.spaco_gather_row_weights(sel, i, k, lam), dtype=np.float32)
+            assert np.array_equal(got, want)
+            for m in range(i, k):
+                col = S.chunk_weights(sel, m, np.float32(lam))[i] if m in sel else np.float32(0)
+                assert want[m - i] == col, (sel, i, m)
+    lib = seco.load_library()
+    w = (C.c_float * 4)()
+    assert lib.spaco_gather_row_weights(None, 0, 2, 2, 1.0, w) == -8       # k must exceed i
+    assert lib.spaco_gather_row_weights(None, 2, 0, 3, 1.0, w) == -1
+    assert lib.spaco_gather_row_weights(None, 0, 1, 3, 1.0, None) == -1
+
+
 def test_bernoulli_selection_matches_oracle_bit_exactly_and_has_the_right_rate():
     for k in (1, 5, 16, 128, 512):
         for q in (1.0, 0.5, 0.25, 1 / 3, 0.9, 1e-3, 8 / 128):
@@ -351,3 +369,28 @@ def test_weighted_gather_backward_validates_its_weights():
     assert call([1.0, 2.0, 0.0, 1.0]) == -7                # covers more chunks than there are rows
     assert call([1.0, -2.0, 0.0]) == -7 and call([1.0, float("nan"), 0.0]) == -7
     assert call([1.0 + i % 2 for i in range(50)], wlen=64, later=50 * 64 - 256) == -10   # more than 24 runs
+
+
+def test_binding_refuses_layouts_the_descriptor_cannot_express():
+    """One stride triple serves K and V, one gK and gV, and LSE is indexed as a contiguous fp32 [B, Hq, C] array:
+    the binding raises before anything reaches the library (CPU tensors suffice: no call is made)."""
+    import torch
+    q = torch.zeros(1, 4, 8, 128, dtype=torch.bfloat16)
+    k = torch.zeros(1, 2, 16, 128, dtype=torch.bfloat16)
+    v_other = torch.zeros(1, 16, 2, 128, dtype=torch.bfloat16).transpose(1, 2)      # same shape, other strides
+    with pytest.raises(ValueError):
+        seco.seco_chunk_attn_fwd(q, k, v_other, 8, 0.088)
+    lse_view = torch.zeros(1, 4, 16)[:, :, ::2]
+    with pytest.raises(ValueError):
+        seco.seco_chunk_attn_fwd(q, k, k, 8, 0.088, lse=lse_view)
+    with pytest.raises(ValueError):
+        seco.seco_chunk_attn_fwd(q, k, k, 8, 0.088, lse=torch.zeros(1, 4, 8, dtype=torch.float64))
+    o, lse = torch.zeros_like(q), torch.zeros(1, 4, 8)
+    gk = torch.zeros(1, 2, 16, 128)
+    gv_other = torch.zeros(1, 16, 2, 128).transpose(1, 2)
+    with pytest.raises(ValueError):
+        seco.seco_chunk_attn_bwd(q, k, k, o, lse, o, gk, gv_other, 8, 0.088, d_q=torch.zeros_like(q))
+    with pytest.raises(ValueError):
+        seco.seco_chunk_attn_bwd(q, k, v_other, o, lse, o, gk, gk, 8, 0.088, d_q=torch.zeros_like(q))
+    with pytest.raises(ValueError):
+        seco.seco_chunk_attn_bwd(q, k, k, o, lse_view, o, gk, gk, 8, 0.088, d_q=torch.zeros_like(q))

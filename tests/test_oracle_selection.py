@@ -1,4 +1,4 @@
-"""Pins for oracle/selection.py (Alg. 2: "randomly select t distinct indices")."""
+"""Pins for oracle/selection.py (Alg. 2, selection step: t different chunks of k, uniformly)."""
 import itertools
 from collections import Counter
 
