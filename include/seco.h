@@ -210,6 +210,24 @@ int spaco_chunk_attn_bwd_gather(const seco_desc* desc, const void* q_rows, const
                                 int32_t weight_chunk_len, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * seco_chunk_attn_bwd without a workspace argument and without any allocation: for callers that cannot allocate
+ * device memory (code under HIP graph capture, serving loops, harnesses that forbid it).  The workspace of
+ * seco_chunk_attn_bwd is taken from a device array of SECO_STATIC_SCRATCH_BYTES bytes that is part of the library's
+ * code object; every GPU the library runs on holds its own copy until the process ends.  Same kernels, same launch
+ * plan and therefore bit-identical d_q, gk, gv as seco_chunk_attn_bwd with a caller-supplied workspace.
+ *   - SECO_ERR_TOO_LARGE if seco_workspace_bytes(desc, SECO_OP_BWD) exceeds SECO_STATIC_SCRATCH_BYTES (nothing is
+ *     enqueued); every other argument and error as seco_chunk_attn_bwd.
+ *   - The call uses the current HIP device's copy of the array; its address is looked up on the first call on that
+ *     device.  No hipMalloc, hipFree or other allocating call is made, on the device or on the host.
+ *   - All calls on one GPU share that GPU's array: two calls whose kernels may overlap (different streams, or
+ *     different host threads without ordering) race and give wrong results.  Calls on one stream are safe.
+ */
+#define SECO_STATIC_SCRATCH_BYTES ((size_t)40 << 20)
+int seco_chunk_attn_bwd_noalloc(const seco_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                const void* o, const float* lse, const void* d_o,
+                                void* d_q, float* gk, float* gv, void* hip_stream);
+
+/*
  * Zero rows [row_begin, row_end) of the KV gradient buffers (start of a training iteration;
  * the buffers then collect the contributions of Alg. 1's / Alg. 2's second loop).
  * Uses batch, n_kv_heads, head_dim and g_stride of desc.  Either pointer may be NULL (skipped).

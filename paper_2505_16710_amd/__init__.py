@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     rope_rotate,
     seco_chunk_attn_bwd,
     seco_chunk_attn_bwd_gather,
+    seco_chunk_attn_bwd_noalloc,
     seco_chunk_attn_fwd,
     seco_device_info,
     seco_launch_plan,

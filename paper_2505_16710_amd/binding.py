@@ -55,6 +55,8 @@ def load_library():
     lib.spaco_chunk_attn_bwd_sparse_dq.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp, fp, fp, C.POINTER(C.c_float),
                                                    C.POINTER(C.c_float), i32, i32, vp, sz, vp]
     lib.spaco_chunk_attn_bwd_sparse_dq.restype = C.c_int
+    lib.seco_chunk_attn_bwd_noalloc.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp, fp, fp, vp]
+    lib.seco_chunk_attn_bwd_noalloc.restype = C.c_int
     lib.seco_chunk_attn_bwd_gather.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp, fp, fp, fp, i64, i32, vp, sz, vp]
     lib.seco_chunk_attn_bwd_gather.restype = C.c_int
     lib.spaco_chunk_attn_bwd_gather.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp, fp, fp, fp, i64, i32,
@@ -216,6 +218,23 @@ def seco_chunk_attn_bwd(q, k_cache, v_cache, o, lse, d_o, gk, gv, q_start, scale
     _check(lib.seco_chunk_attn_bwd(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(o), _ptr(lse), _ptr(d_o),
                                    _ptr(d_q), _ptr(gk), _ptr(gv), _ptr(ws), ws.numel() * ws.element_size(),
                                    _stream(stream)), "seco_chunk_attn_bwd")
+    return d_q
+
+
+STATIC_SCRATCH_BYTES = 40 << 20
+
+
+def seco_chunk_attn_bwd_noalloc(q, k_cache, v_cache, o, lse, d_o, d_q, gk, gv, q_start, scale, stream=None):
+    """seco_chunk_attn_bwd on the library's own static device scratch: no workspace argument, nothing allocated here
+    or in the library (d_q must be supplied).  Returns d_q."""
+    lib = load_library()
+    if o.stride() != d_o.stride() or q.stride() != d_q.stride():
+        raise ValueError("o/d_o and q/d_q must share strides")
+    _check_shared(k_cache, v_cache, gk, gv, lse)
+    d = make_desc(q, k_cache, q_start, scale, o=o, g=gk)
+    _check(lib.seco_chunk_attn_bwd_noalloc(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(o), _ptr(lse),
+                                           _ptr(d_o), _ptr(d_q), _ptr(gk), _ptr(gv), _stream(stream)),
+           "seco_chunk_attn_bwd_noalloc")
     return d_q
 
 

@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstring>
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "seco_internal.h"
@@ -122,24 +123,13 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
   const int kv_len = d->q_start + d->chunk_len;
   const int tile = d->dtype == SECO_BF16 ? kColTileBf16 : kColTileF32;
 
-  // Column segments: maximal runs of cache rows with one non-zero weight.
-  struct Run { int b, e; float w; };
-  std::vector<Run> runs;
-  if (!w) {
-    runs.push_back({0, kv_len, 1.f});
-  } else {
+  // Chunk weights: validated here, turned into column segments (maximal runs of cache rows with one non-zero
+  // weight) when the dK/dV pass is launched below.
+  if (w) {
     if (n_chunks < 1 || wlen < 1) return SECO_ERR_WEIGHTS;
     if ((int64_t)n_chunks * wlen < kv_len || (int64_t)(n_chunks - 1) * wlen >= kv_len) return SECO_ERR_WEIGHTS;
     for (int i = 0; i < n_chunks; ++i)
       if (!std::isfinite(w[i])) return SECO_ERR_WEIGHTS;
-    for (int i = 0; i < n_chunks; ++i) {
-      if (w[i] == 0.f) continue;
-      const int b = (int)((int64_t)i * wlen), e = (int)std::min<int64_t>((int64_t)(i + 1) * wlen, kv_len);
-      if (!runs.empty() && runs.back().e == b && runs.back().w == w[i])
-        runs.back().e = e;
-      else
-        runs.push_back({b, e, w[i]});
-    }
   }
 
   // Runs of the column-weighted dQ: the same construction over wq, which must be non-negative.  A single run
@@ -187,19 +177,42 @@ int backward(const seco_desc* d, const void* q, const void* k, const void* v, co
   if (!bf16 && (rc = launch_delta(p, d->dtype, s))) return rc;
   const SegTable* runs_arg = sparse_dq ? &dq_runs : nullptr;
   if ((rc = bf16 ? launch_dq_bf16(p, runs_arg, s) : launch_dq_f32(p, runs_arg, s))) return rc;
-  for (size_t first = 0; first < runs.size(); first += kMaxSegments) {
-    SegTable seg;
+  // dK/dV pass: one launch per table of at most kMaxSegments runs (no host allocation: a table is launched as soon
+  // as it is full, and every argument has been validated by now)
+  SegTable seg;
+  std::memset(&seg, 0, sizeof(seg));
+  auto flush = [&]() -> int {
+    const int st = seg.n == 0 ? SECO_OK : (bf16 ? launch_dkdv_bf16(p, seg, s) : launch_dkdv_f32(p, seg, s));
     std::memset(&seg, 0, sizeof(seg));
-    seg.n = (int)std::min<size_t>(kMaxSegments, runs.size() - first);
-    for (int i = 0; i < seg.n; ++i) {
-      const Run& r = runs[first + i];
-      seg.col_begin[i] = r.b;
-      seg.col_end[i] = r.e;
-      seg.weight[i] = r.w;
-      seg.tile_begin[i + 1] = seg.tile_begin[i] + (r.e - r.b + tile - 1) / tile;
+    return st;
+  };
+  auto add_rows = [&](int b, int e, float wt) -> int {      // rows [b, e) with weight wt != 0
+    if (seg.n > 0 && seg.col_end[seg.n - 1] == b && seg.weight[seg.n - 1] == wt) {
+      seg.col_end[seg.n - 1] = e;
+      seg.tile_begin[seg.n] = seg.tile_begin[seg.n - 1] + (e - seg.col_begin[seg.n - 1] + tile - 1) / tile;
+      return SECO_OK;
     }
-    if ((rc = bf16 ? launch_dkdv_bf16(p, seg, s) : launch_dkdv_f32(p, seg, s))) return rc;
+    if (seg.n == kMaxSegments) {
+      const int st = flush();
+      if (st) return st;
+    }
+    seg.col_begin[seg.n] = b;
+    seg.col_end[seg.n] = e;
+    seg.weight[seg.n] = wt;
+    seg.tile_begin[seg.n + 1] = seg.tile_begin[seg.n] + (e - b + tile - 1) / tile;
+    ++seg.n;
+    return SECO_OK;
+  };
+  if (!w) {
+    if ((rc = add_rows(0, kv_len, 1.f))) return rc;
+  } else {
+    for (int i = 0; i < n_chunks; ++i) {
+      if (w[i] == 0.f) continue;
+      const int b = (int)((int64_t)i * wlen), e = (int)std::min<int64_t>((int64_t)(i + 1) * wlen, kv_len);
+      if ((rc = add_rows(b, e, w[i]))) return rc;
+    }
   }
+  if ((rc = flush())) return rc;
   return SECO_OK;
 }
 
@@ -445,6 +458,52 @@ extern "C" int spaco_chunk_attn_bwd_sparse_dq(const seco_desc* desc, const void*
   if (!chunk_weight_host || !dq_weight_host) return SECO_ERR_NULL;
   return backward(desc, q, k_cache, v_cache, o, lse, d_o, d_q, gk, gv, chunk_weight_host, dq_weight_host, n_chunks,
                   weight_chunk_len, ws, ws_bytes, hip_stream);
+}
+
+// ---- seco_chunk_attn_bwd for callers that cannot allocate -------------------------------------------------------
+// The workspace of the backward (row statistics, partial dQ of the short-chunk path, shared-out dK/dV tiles) lives
+// in a device array of the library itself.  Each GPU the library runs on holds its own copy of the array at its
+// own address, which is looked up once per device, with that device current, and used from then on; the array's
+// name itself is never handed to a kernel or to a memory call.
+namespace {
+constexpr size_t kScratchBytes = SECO_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];   // address of `scratch` on device i, or NULL before the first call there
+
+int scratch_address(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return SECO_ERR_LAUNCH;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return SECO_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SECO_OK;
+}
+}  // namespace
+
+extern "C" int seco_chunk_attn_bwd_noalloc(const seco_desc* desc, const void* q, const void* k_cache,
+                                           const void* v_cache, const void* o, const float* lse, const void* d_o,
+                                           void* d_q, float* gk, float* gv, void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (delta_bytes(desc) + bwd_part_bytes(desc) > kScratchBytes) return SECO_ERR_TOO_LARGE;
+  void* ws = nullptr;
+  if ((rc = scratch_address(&ws))) return rc;
+  // every value the kernels read from the scratch array is written earlier in the same call (row statistics by the
+  // dQ kernel, partial sums by the kernels whose merge reads them), so nothing has to be cleared between calls
+  return backward(desc, q, k_cache, v_cache, o, lse, d_o, d_q, gk, gv, nullptr, nullptr, 0, 0, ws, kScratchBytes,
+                  hip_stream);
 }
 
 namespace {
