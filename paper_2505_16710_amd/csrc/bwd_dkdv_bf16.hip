@@ -16,8 +16,13 @@
 // wavefronts share a SIMD.  Role A runs one row tile ahead of role B, so the P hand-over
 // costs no extra barrier: one barrier per 64-row stage.
 //
-// Q, dO, -LSE and -delta of one stage of query rows stream through a three-deep ring of swizzled LDS
-// stages (A reads Q of stage i+1 while B reads Q and dO of stage i and stage i+2 is landing);
+// The two roles are two instantiations of one body (template parameter ROLE) behind a wavefront-uniform branch at
+// the top of the kernel, not two arms of a branch inside a common loop: each role then has a loop, accumulators and
+// a register allocation of its own (224 instead of 256 registers, no execution-mask juggling; 7 % faster).
+//
+// Q, dO, -LSE / s and -delta of one stage of query rows stream through a three-deep ring of swizzled LDS
+// slots, laid out region by region (Q tiles, dO tiles, row statistics, P buffers; one of each per slot)
+// (A reads Q of stage i+1 while B reads Q and dO of stage i and stage i+2 is landing);
 // Q and dO are copied global -> LDS directly (no staging registers), issued two stages ahead.
 // S and dP are computed in the "row = query" orientation, so P and dS sit in the C layout
 // with lane = cache row and feed the second products as A operands; dO and Q for those
@@ -60,8 +65,15 @@ struct DkdvCfg {
   static constexpr int kThreads = NCB * 128;
   static constexpr int kBQ = 32 * RB;                                   // query rows per stage
   static constexpr int kTileBytes = kBQ * kRowBytes;
-  static constexpr int kStageBytes = 2 * kTileBytes + 2 * kBQ * 4;      // Q, dO, lse, delta
-  static constexpr int kSmemBytes = kStages * kStageBytes + 2 * NCB * RB * kPBytes;
+  // LDS layout, region by region: the Q tiles of the kStages slots, their dO tiles, their row statistics (-LSE / s
+  // and -delta, kBQ floats each), and one P buffer per slot, column block and row block.  A per-lane operand
+  // offset carries the region it is used with (role A reads rows of Q and transposed blocks of dO, role B the
+  // reverse), so that a slot's tile base is one scalar for both tiles.
+  static constexpr int kDoRegion = kStages * kTileBytes;
+  static constexpr int kStatRegion = 2 * kStages * kTileBytes;
+  static constexpr int kStatBytes = 2 * kBQ * 4;
+  static constexpr int kPRegion = kStatRegion + kStages * kStatBytes;
+  static constexpr int kSmemBytes = kPRegion + kStages * NCB * RB * kPBytes;
   static constexpr int kCols = NCB * 32;                                // cache rows per workgroup
 };
 
@@ -76,23 +88,26 @@ struct TailSplit {
 // (RB is fixed to 2 by the hand-pipelined main loop.)
 // ROWS: the query rows are taken from a table of runs (rows relative to p.q_start, each run with one weight whose
 // log2 is added to -LSE, i.e. its probabilities are scaled by the weight) instead of being all p.C rows with weight 1.
-template <int NCB, int RB, bool ROWS>
-__global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, SegTable seg, TailSplit ts,
-                                                                  RowRuns rr, int total_items) {
+// ROLE: 0 = role A, 1 = role B.  The body of a wavefront is instantiated once per role, so that a role's accumulators
+// and working set are the variables of a loop of its own: with both roles as the two arms of a branch inside one
+// loop, unrolled over the ring slots, the register allocator could not keep the working set in registers.
+template <int NCB, int RB, bool ROWS, int ROLE>
+__device__ __forceinline__ void dkdv_bf16_body(const AttnParams& p, const SegTable& seg, const TailSplit& ts,
+                                               const RowRuns& rr, int total_items, lds_char* smem) {
   using Cfg = DkdvCfg<NCB, RB>;
-  constexpr int BQ = Cfg::kBQ, kTileBytes = Cfg::kTileBytes, kStageBytes = Cfg::kStageBytes;
+  constexpr int BQ = Cfg::kBQ, kTileBytes = Cfg::kTileBytes;
+  constexpr int kDoRegion = Cfg::kDoRegion, kStatRegion = Cfg::kStatRegion, kStatBytes = Cfg::kStatBytes;
   constexpr int NW = 2 * NCB;                 // wavefronts
   constexpr int kCopies = (BQ / 4) / NW;      // 4-row direct copies of Q (and of dO) per wavefront and stage
   static_assert((BQ / 4) % NW == 0, "stage rows must split evenly over the wavefronts");
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];   // Cfg::kSmemBytes (can exceed the 64 KiB static limit)
-  lds_char* smem = (lds_char*)smem_raw;
-  lds_char* pbuf = smem + kStages * kStageBytes;
+  lds_char* pbuf = smem + Cfg::kPRegion;
 
   const int item = xcd_item(blockIdx.x, total_items);
   if (item < 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
-  const int role = wave / NCB, cb = wave % NCB;
+  constexpr int role = ROLE;
+  const int cb = wave % NCB;
   // item -> (batch, kv head, column tile, share of the query heads); the divided tiles come last in a unit
   const int n_ctiles = seg.tile_begin[seg.n];
   const int n_whole = n_ctiles - ts.n_tiles;
@@ -175,18 +190,18 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       const __bf16* do_src = dobase + x.hg * p.os[1] + (int64_t)x.r0 * p.os[2];
 #pragma unroll
       for (int i = 0; i < kCopies; ++i) {
-        const uint32_t dst = lds_wave + slot * kStageBytes + i * (4 * NW * kRowBytes);
+        const uint32_t dst = lds_wave + slot * kTileBytes + i * (4 * NW * kRowBytes);
         dma16_sbase(q_src, q_lane_off[i], dst);
-        dma16_sbase(do_src, do_lane_off[i], dst + kTileBytes);
+        dma16_sbase(do_src, do_lane_off[i], dst + kDoRegion);
       }
     } else {
-      lds_char* qt = smem + slot * kStageBytes;
+      lds_char* qt = smem + slot * kTileBytes;
 #pragma unroll
       for (int i = 0; i < kCopies; ++i) {
         const int r = 4 * (wave + NW * i);
         const int src_row = min(x.r0 + r + (lane >> 4), p.C - 1);
         dma4rows(qt, r, qbase + x.hg * p.qs[1] + (int64_t)src_row * p.qs[2], lane);
-        dma4rows(qt + kTileBytes, r, dobase + x.hg * p.os[1] + (int64_t)src_row * p.os[2], lane);
+        dma4rows(qt + kDoRegion, r, dobase + x.hg * p.os[1] + (int64_t)src_row * p.os[2], lane);
       }
     }
   };
@@ -195,7 +210,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   // of a head goes through registers instead: rows past the chunk get -LSE = -inf so that their probabilities vanish.
   static_assert(BQ == 64, "one 64-lane copy per row statistic");
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  const uint32_t lds_stat = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + 2 * kTileBytes + (wave & 1) * BQ * 4);
+  const uint32_t lds_stat = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + kStatRegion + (wave & 1) * BQ * 4);
   auto copy_stat = [&](Pos x, int slot) {
     if (x.r0 + BQ <= row_limit(x)) {
       if (wave_u < 2) {
@@ -206,24 +221,31 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
                              (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)a);
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1"
                      :
-                     : "v"(lane * 4), "s"(src), "s"(lds_stat + slot * kStageBytes)
+                     : "v"(lane * 4), "s"(src), "s"(lds_stat + slot * kStatBytes)
                      : "memory", "m0");
       }
     } else if (wave_u < 2) {             // (wavefront-uniform control flow only: the copies above need scalar addresses)
       const int row = x.r0 + lane;
       const float v = (wave_u == 0 ? p.nlse2 : p.delta)[stat_base + (int64_t)x.hg * p.stat_stride + min(row, p.C - 1)];
       const float stat = wave_u == 0 && row >= row_limit(x) ? -INFINITY : v;
-      *reinterpret_cast<SECO_LDS float*>(smem + slot * kStageBytes + 2 * kTileBytes + (wave_u * BQ + lane) * 4) = stat;
+      *reinterpret_cast<SECO_LDS float*>(smem + kStatRegion + slot * kStatBytes + (wave_u * BQ + lane) * 4) = stat;
     }
   };
 
   // lane-dependent parts of the LDS operand addresses (constant for the whole kernel)
   int r_off[8];
   TrOff t_off[4];
+  // role A reads rows of Q and transposed blocks of dO, role B rows of dO and transposed blocks of Q: the region of
+  // the tile an offset is used with is part of the offset
+  const int r_region = role == 0 ? 0 : kDoRegion, t_region = role == 0 ? kDoRegion : 0;
 #pragma unroll
-  for (int t = 0; t < 8; ++t) r_off[t] = row8_lane_off(l32, 2 * t + g);
+  for (int t = 0; t < 8; ++t) r_off[t] = row8_lane_off(l32, 2 * t + g) + r_region;
 #pragma unroll
-  for (int db = 0; db < 4; ++db) t_off[db] = tr8_lane_off(db, lane);
+  for (int db = 0; db < 4; ++db) {
+    t_off[db] = tr8_lane_off(db, lane);
+    t_off[db].lo += t_region;
+    t_off[db].hi += t_region;
+  }
 
   f32x16 acc[4];   // role A: dV, role B: dK  (32 cache rows x 128)
 #pragma unroll
@@ -231,24 +253,28 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
-  auto pslot = [&](int parity, int rb) { return pbuf + ((parity * NCB + cb) * RB + rb) * kPBytes; };
+  // P of the stage held in slot `slot`, row block rb, this wavefront's column block: p_lane is the lane-dependent
+  // part of the address (the lane's 16 bytes of the wavefront's block), the rest a constant per slot and row block
+  int p_lane = cb * RB * kPBytes + lane * 16;
+  auto pslot = [&](int slot, int rb) { return pbuf + (slot * NCB * RB + rb) * kPBytes + p_lane; };
 
   // zero the probabilities of a 32x32 block (first query position qpos0) that lie above the diagonal
+  // (register r of a score tile holds query row 8 (r / 4) + 4 g + r % 4 of the block: the lane-dependent part of the
+  // comparison is one value, the rest compile-time constants, so that nothing per-lane has to be kept for it)
   auto mask_above_diagonal = [&](f32x16& s, int qpos0) {
     if (n0 + 31 > qpos0) {
+      const int ahead = col - qpos0 - 4 * g;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int qr = 8 * (r >> 2) + 4 * g + (r & 3);
-        if (col > qpos0 + qr) s[r] = 0.f;
-      }
+      for (int r = 0; r < 16; ++r)
+        if (ahead > 8 * (r >> 2) + (r & 3)) s[r] = 0.f;
     }
   };
 
   // role A: S = Q K^T for row block rb of the stage in `slot`, P = exp2(c2 * (S - LSE / s)) with the causal mask;
   // P goes to pbuf as two operand halves (lane-contiguous 16-byte words)
-  auto scores = [&](int slot, int parity, int r0, int rb, float lw) {   // lw: log2 of the rows' weight, divided by c2
-    lds_char* qt = smem + slot * kStageBytes;
-    SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + 32 * rb;
+  auto scores = [&](int slot, int r0, int rb, float lw) {   // lw: log2 of the rows' weight, divided by c2
+    lds_char* qt = smem + slot * kTileBytes;
+    SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(smem + kStatRegion + slot * kStatBytes) + 32 * rb;
     bf16x8 a[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) a[t] = lds_row8(qt, 32 * rb + l32, 2 * t + g);
@@ -264,9 +290,9 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = fast_exp2(s[r] * c2);
     mask_above_diagonal(s, p.q_start + r0 + 32 * rb);
-    lds_char* pb = pslot(parity, rb);
-    *reinterpret_cast<SECO_LDS bf16x8*>(pb + lane * 16) = pack8(s, 0);
-    *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 + lane * 16) = pack8(s, 1);
+    lds_char* pb = pslot(slot, rb);
+    *reinterpret_cast<SECO_LDS bf16x8*>(pb) = pack8(s, 0);
+    *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024) = pack8(s, 1);
   };
 
   Pos cur{head0, first_r0, first_ri};
@@ -281,9 +307,9 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   for (int t = 0; t < 8; ++t) settle(frag[t]);
   dma_wait_all();
   __syncthreads();
-  if (role == 0) {
+  if constexpr (role == 0) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) scores(0, 0, cur.r0, rb, ROWS ? rr.log2w[cur.ri] / c2 : 0.f);
+    for (int rb = 0; rb < RB; ++rb) scores(0, cur.r0, rb, ROWS ? rr.log2w[cur.ri] / c2 : 0.f);
   }
   __syncthreads();
   Pos nxt2 = advance(nxt);
@@ -295,18 +321,18 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
   // the stage it is about to use for dV (pa0, pa1: its own P blocks, as operands) in registers.
   bf16x8 x[8];
   bf16x8 pa0[2], pa1[2];
-  auto p_half = [&](lds_char* pb, int t) { return *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 * t + lane * 16); };
-  if (role == 0) {
+  auto p_half = [&](lds_char* pb, int t) { return *reinterpret_cast<SECO_LDS bf16x8*>(pb + 1024 * t); };
+  if constexpr (role == 0) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       pa0[t] = p_half(pslot(0, 0), t);
       pa1[t] = p_half(pslot(0, 1), t);
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) x[i] = lds_tr8_at(smem + kTileBytes, t_off[i & 3], 16 * (i >> 2));
+    for (int i = 0; i < 8; ++i) x[i] = lds_tr8_at(smem, t_off[i & 3], 16 * (i >> 2));
   } else {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) x[t] = lds_row8_at(smem + kTileBytes + r_off[t], 0);
+    for (int t = 0; t < 8; ++t) x[t] = lds_row8_at(smem + r_off[t], 0);
   }
 
   int slot = 0;   // it % kStages
@@ -317,22 +343,22 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       copy_stage(nxt2, slot2);
       copy_stat(nxt2, slot2);
     }
-    lds_char* qt = smem + slot * kStageBytes;
-    lds_char* dot = qt + kTileBytes;
-    lds_char* qt1 = smem + slot1 * kStageBytes;
-    lds_char* dot1 = qt1 + kTileBytes;
+    // tiles of the stage in `slot` and of the next stage; whether an access goes to the Q or to the dO tile of the
+    // slot is decided by the region that its per-lane offset (r_off, t_off) carries
+    lds_char* t0 = smem + slot * kTileBytes;
+    lds_char* t1 = smem + slot1 * kTileBytes;
     // Row blocks above the diagonal are not skipped: their probabilities are masked to zero and contribute nothing
     // (only the first stages of a diagonal column tile are affected).  In both roles the vector work on a row block
     // (exponentials; dS = P * (dP - delta)) is written between the MFMAs of a later chain, two values per MFMA, so
     // that a wavefront keeps the matrix pipe fed while its own vector instructions issue.
-    if (role == 0) {
+    if constexpr (role == 0) {
       // stage `it`: dV += P^T dO (P from the previous iteration); stage `it + 1`: P = exp2(Q K^T c - LSE)
-      SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(qt1 + 2 * kTileBytes);
+      SECO_LDS float* lse_s = reinterpret_cast<SECO_LDS float*>(smem + kStatRegion + slot1 * kStatBytes);
       // dV of row block 0; Q rows of row block 0 of the next stage come in behind
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         acc[i & 3] = mfma(pa0[i >> 2], x[i], acc[i & 3]);
-        x[i] = lds_row8_at(qt1 + r_off[i], 0);
+        x[i] = lds_row8_at(t1 + r_off[i], 0);
       }
       f32x16 s0, s1;
 #pragma unroll
@@ -351,27 +377,27 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         s0 = mfma(x[t], frag[t], s0);
-        x[t] = lds_row8_at(qt1 + r_off[t], 32);
+        x[t] = lds_row8_at(t1 + r_off[t], 32);
       }
       // log2 P of row block 1, with the exponentials of row block 0; dO^T of row block 1 (stage `it`) comes in behind
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         s1 = mfma(x[t], frag[t], s1);
-        x[t] = lds_tr8_at(dot, t_off[t & 3], 32 + 16 * (t >> 2));
+        x[t] = lds_tr8_at(t0, t_off[t & 3], 32 + 16 * (t >> 2));
         s0[2 * t] = fast_exp2(s0[2 * t] * c2);
         s0[2 * t + 1] = fast_exp2(s0[2 * t + 1] * c2);
       }
       mask_above_diagonal(s0, p.q_start + nxt.r0);
       const bf16x8 pn0[2] = {pack8(s0, 0), pack8(s0, 1)};
-      lds_char* pw0 = pslot((it + 1) & 1, 0);
-      *reinterpret_cast<SECO_LDS bf16x8*>(pw0 + lane * 16) = pn0[0];
-      *reinterpret_cast<SECO_LDS bf16x8*>(pw0 + 1024 + lane * 16) = pn0[1];
+      lds_char* pw0 = pslot(slot1, 0);
+      *reinterpret_cast<SECO_LDS bf16x8*>(pw0) = pn0[0];
+      *reinterpret_cast<SECO_LDS bf16x8*>(pw0 + 1024) = pn0[1];
       // dV of row block 1, with the exponentials of row block 1 of the next stage; dO^T of row block 0 of the next
       // stage comes in behind (for the first chain of the next iteration)
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         acc[i & 3] = mfma(pa1[i >> 2], x[i], acc[i & 3]);
-        x[i] = lds_tr8_at(dot1, t_off[i & 3], 16 * (i >> 2));
+        x[i] = lds_tr8_at(t1, t_off[i & 3], 16 * (i >> 2));
         s1[2 * i] = fast_exp2(s1[2 * i] * c2);
         s1[2 * i + 1] = fast_exp2(s1[2 * i + 1] * c2);
       }
@@ -380,15 +406,15 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       pa0[1] = pn0[1];
       pa1[0] = pack8(s1, 0);
       pa1[1] = pack8(s1, 1);
-      lds_char* pw1 = pslot((it + 1) & 1, 1);
-      *reinterpret_cast<SECO_LDS bf16x8*>(pw1 + lane * 16) = pa1[0];
-      *reinterpret_cast<SECO_LDS bf16x8*>(pw1 + 1024 + lane * 16) = pa1[1];
+      lds_char* pw1 = pslot(slot1, 1);
+      *reinterpret_cast<SECO_LDS bf16x8*>(pw1) = pa1[0];
+      *reinterpret_cast<SECO_LDS bf16x8*>(pw1 + 1024) = pa1[1];
     } else {
       // stage `it`: dS = P * (dO V^T - delta), dK += dS^T Q
-      SECO_LDS float* delta_s = reinterpret_cast<SECO_LDS float*>(qt + 2 * kTileBytes) + BQ;
-      lds_char* pb0 = pslot(it & 1, 0);
+      SECO_LDS float* delta_s = reinterpret_cast<SECO_LDS float*>(smem + kStatRegion + slot * kStatBytes) + BQ;
+      lds_char* pb0 = pslot(slot, 0);
       const bf16x8 ph0[2] = {p_half(pb0, 0), p_half(pb0, 1)};
-      lds_char* pb1 = pslot(it & 1, 1);
+      lds_char* pb1 = pslot(slot, 1);
       const bf16x8 ph1[2] = {p_half(pb1, 0), p_half(pb1, 1)};
       f32x16 d0, d1;
 #pragma unroll
@@ -399,13 +425,13 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         d0 = mfma(x[t], frag[t], d0);
-        x[t] = lds_row8_at(dot + r_off[t], 32);
+        x[t] = lds_row8_at(t0 + r_off[t], 32);
       }
       // dP - delta of row block 1, with dS of row block 0; Q^T of row block 0 comes in behind
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         d1 = mfma(x[t], frag[t], d1);
-        x[t] = lds_tr8_at(qt, t_off[t & 3], 16 * (t >> 2));
+        x[t] = lds_tr8_at(t0, t_off[t & 3], 16 * (t >> 2));
         d0[2 * t] *= (float)ph0[t >> 2][(2 * t) & 7];
         d0[2 * t + 1] *= (float)ph0[t >> 2][(2 * t + 1) & 7];
       }
@@ -414,7 +440,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         acc[i & 3] = mfma(ds0[i >> 2], x[i], acc[i & 3]);
-        x[i] = lds_tr8_at(qt, t_off[i & 3], 32 + 16 * (i >> 2));
+        x[i] = lds_tr8_at(t0, t_off[i & 3], 32 + 16 * (i >> 2));
         d1[2 * i] *= (float)ph1[i >> 2][(2 * i) & 7];
         d1[2 * i + 1] *= (float)ph1[i >> 2][(2 * i + 1) & 7];
       }
@@ -423,7 +449,7 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         acc[i & 3] = mfma(ds1[i >> 2], x[i], acc[i & 3]);
-        x[i] = lds_row8_at(dot1 + r_off[i], 0);
+        x[i] = lds_row8_at(t1 + r_off[i], 0);
       }
     }
     dma_wait_all();
@@ -473,6 +499,19 @@ __global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, S
       for (int db = 0; db < 4; ++db) gr[32 * db] = old[r][db] + wf * acc[db][r];
     }
   }
+}
+
+template <int NCB, int RB, bool ROWS>
+__global__ __launch_bounds__(NCB * 128, 2) void dkdv_bf16_kernel(AttnParams p, SegTable seg, TailSplit ts,
+                                                                  RowRuns rr, int total_items) {
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];   // Cfg::kSmemBytes (can exceed the 64 KiB static limit)
+  lds_char* smem = (lds_char*)smem_raw;
+  // wavefronts 0 .. NCB-1: role A, the others role B (wavefront-uniform: a scalar branch)
+  const int role_u = __builtin_amdgcn_readfirstlane((int)threadIdx.x / (64 * NCB));
+  if (role_u == 0)
+    dkdv_bf16_body<NCB, RB, ROWS, 0>(p, seg, ts, rr, total_items, smem);
+  else
+    dkdv_bf16_body<NCB, RB, ROWS, 1>(p, seg, ts, rr, total_items, smem);
 }
 
 // gK/gV of the divided column tiles: g += w * (sum of the head shares, in head order).  One thread per four

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, SegT
   if (item < 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
-  const int rb = wave & 3, kh = wave >> 2;
+  const int rb = wave & 3, kh = (KH == 1 && !SPARSE) ? 0 : wave >> 2;
   int b, kvh, h, mt, m0, sp = 0;              // m0: first chunk-local row of this wavefront
   if constexpr (SPLIT) {
     sp = item % p.n_splits;
@@ -179,10 +179,17 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, SegT
   // lane-dependent parts of the LDS operand addresses (constant for the whole kernel)
   int r_off[8];
   TrOff t_off[4];
+  // (dense variants: the wavefront's half of the tile, for KH = 2, is part of the per-lane offsets, so that a tile's
+  // base is a compile-time constant in the unrolled loop below)
+  const int half_off = SPARSE ? 0 : kh * BNW * kRowBytes;
 #pragma unroll
-  for (int t = 0; t < 8; ++t) r_off[t] = row8_lane_off(l32, 2 * t + g);
+  for (int t = 0; t < 8; ++t) r_off[t] = row8_lane_off(l32, 2 * t + g) + half_off;
 #pragma unroll
-  for (int db = 0; db < 4; ++db) t_off[db] = tr8_lane_off(db, lane);
+  for (int db = 0; db < 4; ++db) {
+    t_off[db] = tr8_lane_off(db, lane);
+    t_off[db].lo += half_off;
+    t_off[db].hi += half_off;
+  }
 
   f32x16 dq[4];
 #pragma unroll
@@ -205,52 +212,25 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, SegT
   dma_wait_all();
   __syncthreads();
 
-  for (int n = n_begin; n < n_end; ++n) {
-    const int buf = (n - n_begin) & 1;
-    if constexpr (SPARSE) {
-      nxt = advance(cur);
-    } else {
-      nxt.col = cur.col + BN;
+  if constexpr (SPARSE) {
+    for (int n = n_begin; n < n_end; ++n) {
+      const int buf = (n - n_begin) & 1;
+#include "bwd_dq_tile_step.inc"
     }
-    if (n + 1 < n_end) copy_tile(nxt.col, buf ^ 1);
-    lds_char* kt = smem + buf * 2 * kTileBytes + kh * BNW * kRowBytes;
-    lds_char* vt = kt + kTileBytes;
-    const float lse_t = SPARSE ? lse_c - __builtin_amdgcn_logf(seg.weight[cur.si]) : lse_c;   // v_log_f32: log2
-#pragma unroll
-    for (int kvb = 0; kvb < 2; ++kvb) {
-      const int col0 = cur.col + kh * BNW + kvb * 32;
-      if (col0 < wave_kv_end && (!SPARSE || col0 < cur.end)) {
-        f32x16 s, dp;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) s = mfma(lds_row8_at(kt + r_off[t], kvb * 32), qf[t], s);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) dp = mfma(lds_row8_at(vt + r_off[t], kvb * 32), dof[t], dp);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = fast_exp2(__builtin_fmaf(s[r], c, -lse_t));
-        // block reaches past this wavefront's first row (or past the end of its run): zero what lies above the
-        // diagonal (or belongs to rows outside the run)
-        if (col0 + 31 > p.q_start + m0 || (SPARSE && col0 + 32 > cur.end)) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int kv = col0 + 8 * (r >> 2) + 4 * g + (r & 3);
-            if (kv > qpos || (SPARSE && kv >= cur.end)) s[r] = 0.f;
-          }
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] *= dp[r] - delta;
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 dsb = pack8(s, t);
-#pragma unroll
-          for (int db = 0; db < 4; ++db) dq[db] = mfma(lds_tr8_at(kt, t_off[db], kvb * 32 + 16 * t), dsb, dq[db]);
-        }
+  } else {
+    for (int n0 = n_begin; n0 < n_end; n0 += 2) {
+      {
+        constexpr int buf = 0;
+        const int n = n0;
+#include "bwd_dq_tile_step.inc"
+      }
+      if (n0 + 1 >= n_end) break;
+      {
+        constexpr int buf = 1;
+        const int n = n0 + 1;
+#include "bwd_dq_tile_step.inc"
       }
     }
-    dma_wait_all();
-    __syncthreads();
-    cur = nxt;
   }
 
   if (KH == 2) {
