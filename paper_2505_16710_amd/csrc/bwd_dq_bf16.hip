@@ -41,7 +41,9 @@ __global__ __launch_bounds__(256 * KH, 2) void dq_bf16_kernel(AttnParams p, SegT
 
   const int item = xcd_item(blockIdx.x, total_items);
   if (item < 0) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // (the wavefront index through readfirstlane: the compiler then knows that it, and every tile coordinate and branch
+  // condition derived from it, is uniform over the wavefront and keeps them in scalar registers)
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, g = lane >> 5;
   const int rb = wave & 3, kh = (KH == 1 && !SPARSE) ? 0 : wave >> 2;
   int b, kvh, h, mt, m0, sp = 0;              // m0: first chunk-local row of this wavefront
