@@ -129,6 +129,11 @@ def test_cfg3_full_shape_calls_element_wise(j):
         _check_unit_call(L, u, C, j, got, f"cfg3 {plan}")
 
 
+def test_cfg3_full_shape_spaco_sampled():
+    """cfg3 as specified: Alg. 2 with 4 of 16 chunks (seeded), factor k/t = 4, on the full 32-head launch; two units."""
+    _spaco_full_launch_check(_layer("cfg3", CFG3_UNITS), CONFIGS["cfg3"], CFG3_UNITS)
+
+
 # ---- cfg2 shape: 8-wavefront forward and dQ with long tile loops, all 16 calls --------------------------------------
 
 CFG2_UNITS = ((0, 2), (0, 5))
@@ -198,12 +203,35 @@ def test_cfg5_full_size_seco_calls(C, calls):
 
 @pytest.mark.parametrize("name", ["cfg5_c512", "cfg5_c4096"])
 def test_cfg5_full_size_spaco_sampled(name):
-    """Alg. 2 on the full cfg5 launch with the seeded selection (a quarter of the chunks, factor k/t = 4): the oracle
-    checks, on two units, sampled query rows of every selected chunk (O, LSE, dQ), the own rows of the top selected
-    chunk (gK/gV there come from that call alone), the rows of the lowest selected chunk in full (own block plus
-    factor x the blocks of every higher selected call), and that unselected chunks stay exactly zero."""
-    L = _layer("cfg5_c512", CFG5_UNITS)
-    cfg = CONFIGS[name]
+    """Alg. 2 on the full cfg5 launch with the seeded selection (a quarter of the chunks, factor k/t = 4)."""
+    _spaco_full_launch_check(_layer("cfg5_c512", CFG5_UNITS), CONFIGS[name], CFG5_UNITS)
+
+
+CFG4_UNITS = ((0, 0), (0, 5))
+
+
+def test_cfg4_full_shape_last_call_element_wise():
+    """cfg4 (64K tokens, 32 chunks of 2048): the SeCO call pair of the LAST chunk on the full launch (65536 visible
+    cache rows, 4096 column tiles, 16 rounds of the dK/dV pass), two whole units element by element."""
+    L = _layer("cfg4", CFG4_UNITS)
+    C, j = L.cfg.chunk_len, L.cfg.n_chunks - 1
+    plan = _assert_direct(L, C, j * C, expect_row_tiles_at_least=512)
+    got = _one_call(L, C, j)
+    for u in CFG4_UNITS:
+        _check_unit_call(L, u, C, j, got, f"cfg4 {plan}")
+
+
+def test_cfg4_full_shape_spaco_sampled():
+    """cfg4 as specified: Alg. 2 with 8 of 32 chunks (seeded), factor 4, on the full launch; two units."""
+    _spaco_full_launch_check(_layer("cfg4", CFG4_UNITS), CONFIGS["cfg4"], CFG4_UNITS)
+
+
+def _spaco_full_launch_check(L, cfg, units):
+    """Alg. 2 on a full launch with the configuration's seeded selection: the oracle checks, on the given units,
+    sampled query rows of every selected chunk (O, LSE, dQ), the own rows of the top selected chunk (gK/gV there come
+    from that call alone), the rows of the lowest selected chunk in full (own block plus factor x the blocks of
+    every higher selected call), and that unselected chunks stay exactly zero."""
+    name = cfg.name
     k_chunks, t, C, scale = cfg.n_chunks, cfg.spaco_t, cfg.chunk_len, cfg.scale
     sel = S.select_chunks(cfg.seed, 0, k_chunks, t).tolist()
     assert sel == seco.spaco_select_chunks(cfg.seed, 0, k_chunks, t)
@@ -224,7 +252,7 @@ def test_cfg5_full_size_spaco_sampled(name):
     torch.cuda.synchronize()
     rng = np.random.default_rng(11)
     G = L.G
-    for (b, kvh) in CFG5_UNITS:
+    for (b, kvh) in units:
         x = L.unit((b, kvh))
         q64, k64, v64, do64 = x["q"], x["k"], x["v"], x["do"]
         hs = slice(kvh * G, (kvh + 1) * G)
