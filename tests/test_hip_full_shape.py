@@ -134,6 +134,40 @@ def test_cfg3_full_shape_spaco_sampled():
     _spaco_full_launch_check(_layer("cfg3", CFG3_UNITS), CONFIGS["cfg3"], CFG3_UNITS)
 
 
+def test_cfg3_full_shape_last_call_with_its_own_draw():
+    """The other reading of cfg3's wording: the single call of the last chunk with 4 sampled earlier chunks plus
+    itself (weights j / 4 on the drawn chunks, 1 on its own rows, from the library's host policy call, which the CPU
+    tests compare with the oracle's bit for bit), on the full launch; dQ exact, gK / gV = weight x the call's dK / dV,
+    unselected chunks untouched.  Two units, every element."""
+    L = _layer("cfg3", CFG3_UNITS)
+    cfg, G = L.cfg, L.G
+    C, j = cfg.chunk_len, cfg.n_chunks - 1
+    w = seco.spaco_percall_weights(cfg.seed, 0, j, cfg.spaco_t)
+    assert np.array_equal(np.array(w, dtype=np.float32), S.percall_weights(cfg.seed, 0, j, cfg.spaco_t))
+    assert sum(1 for x in w[:j] if x != 0) == cfg.spaco_t and w[j] == 1.0
+    q, k, v, do = (L.dev[n] for n in ("q", "k", "v", "do"))
+    sl = slice(j * C, (j + 1) * C)
+    gk = torch.zeros(k.shape, dtype=torch.float32, device=DEV)
+    gv = torch.zeros_like(gk)
+    o, lse = seco.seco_chunk_attn_fwd(q[:, :, sl], k, v, j * C, cfg.scale)
+    dq = seco.spaco_chunk_attn_bwd(q[:, :, sl], k, v, o, lse, do[:, :, sl].contiguous(), gk, gv, j * C, cfg.scale, w, C)
+    torch.cuda.synchronize()
+    wrow = np.repeat(np.array(w, dtype=np.float64), C)[None, None, :, None]
+    for (b, kvh) in CFG3_UNITS:
+        x = L.unit((b, kvh))
+        o_ref, lse_ref = A.chunk_attn_fwd(x["q"][:, :, sl], x["k"], x["v"], j * C, cfg.scale)
+        dq_ref, dk_ref, dv_ref = A.chunk_attn_bwd(x["q"][:, :, sl], x["k"], x["v"], o_ref, lse_ref, x["do"][:, :, sl],
+                                                  j * C, cfg.scale)
+        hs = slice(kvh * G, (kvh + 1) * G)
+        gk_u, gv_u = to_host(gk[b:b + 1, kvh:kvh + 1]), to_host(gv[b:b + 1, kvh:kvh + 1])
+        errs = {"dq": max_rel(to_host(dq[b:b + 1, hs]), dq_ref), "gk": max_rel(gk_u, wrow * dk_ref),
+                "gv": max_rel(gv_u, wrow * dv_ref)}
+        print(f"cfg3 last call, weights {[round(x, 2) for x in w]}, unit {(b, kvh)}: {errs}", flush=True)
+        assert all(e <= TOL[n] for n, e in errs.items()), errs
+        zero_rows = np.repeat(np.array(w) == 0.0, C)
+        assert not gk_u[:, :, zero_rows].any() and not gv_u[:, :, zero_rows].any()
+
+
 # ---- cfg2 shape: 8-wavefront forward and dQ with long tile loops, all 16 calls --------------------------------------
 
 CFG2_UNITS = ((0, 2), (0, 5))
