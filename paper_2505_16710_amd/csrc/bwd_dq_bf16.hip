@@ -318,7 +318,7 @@ int launch_dq_bf16(const AttnParams& p, const SegTable* runs, hipStream_t s) {
   }
   const int n_mtiles = (p.C + BM - 1) / BM;
   const int total = p.B * p.Hq * n_mtiles;
-  if (total < 2 * kNumCUs)
+  if (total < 2 * device_cus())
     return runs ? launch_kh<2, false, true>(p, seg, n_mtiles, total, s) : launch_kh<2, false, false>(p, seg, n_mtiles, total, s);
   return runs ? launch_kh<1, false, true>(p, seg, n_mtiles, total, s) : launch_kh<1, false, false>(p, seg, n_mtiles, total, s);
 }

@@ -275,7 +275,7 @@ int launch_fwd_bf16(const AttnParams& p, hipStream_t s) {
   const int n_mtiles = (p.C + BM - 1) / BM;
   const int total = p.B * p.Hq * n_mtiles;
   // fewer row tiles than two per CU: use the 8-wavefront shape so that every SIMD still has two wavefronts
-  return total < 2 * kNumCUs ? launch_fwd8(p, n_mtiles, total, s) : launch_fwd4_bf16(p, false, n_mtiles, total, s);
+  return total < 2 * device_cus() ? launch_fwd8(p, n_mtiles, total, s) : launch_fwd4_bf16(p, false, n_mtiles, total, s);
 }
 
 }  // namespace seco

@@ -31,7 +31,6 @@ typedef SECO_LDS char lds_char;
 
 constexpr int kHeadDim = 128;
 constexpr int kRowBytes = kHeadDim * 2;
-constexpr int kNumCUs = 256;   // MI355X
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 

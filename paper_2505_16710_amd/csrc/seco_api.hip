@@ -9,6 +9,19 @@
 #include "seco_internal.h"
 
 namespace seco {
+
+int device_cus() {
+  static const int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      return n;
+    (void)hipGetLastError();
+    return kDefaultCUs;
+  }();
+  return cus;
+}
+
 namespace {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -95,7 +108,7 @@ int splits_for(const seco_desc* d) {
 // workspace of the dK/dV pass for the column tiles it divides by query head (bf16, grouped heads only)
 size_t tail_part_bytes(const seco_desc* d) {
   if (d->dtype != SECO_BF16 || d->n_q_heads / d->n_kv_heads < 2) return 0;
-  return (size_t)kTailMaxShares * 2 * kColTileBf16 * 128 * sizeof(float);
+  return (size_t)device_cus() * 2 * kColTileBf16 * 128 * sizeof(float);   // at most one share per CU (tail_plan)
 }
 // the partial dQ of the split path and the divided dK/dV tiles are never live together: they share one region
 size_t bwd_part_bytes(const seco_desc* d) { return std::max(split_part_bytes(d), tail_part_bytes(d)); }

@@ -62,12 +62,19 @@ struct SplitPlan {
   int items;        // B * Hkv * n_mtiles
   int max_splits;   // 1: the split path is never used for this shape
 };
+// Compute units of the current device, asked of the device once per process (kDefaultCUs, an MI355X's 256, when
+// there is no device to ask, as in host-only use of the planning calls).  Every launch-shape decision below and in the launchers counts
+// workgroups against this one number; seco_device_info reports the same attribute.
+constexpr int kDefaultCUs = 256;
+int device_cus();
+
 inline SplitPlan split_plan(int B, int Hkv, int G, int C) {
   SplitPlan pl;
+  const int cus = device_cus();
   const int cpad = (C + 31) / 32 * 32;
   pl.n_mtiles = (G * cpad + 127) / 128;
   pl.items = B * Hkv * pl.n_mtiles;
-  pl.max_splits = pl.items >= 256 ? 1 : (512 + pl.items - 1) / pl.items;
+  pl.max_splits = pl.items >= cus ? 1 : (2 * cus + pl.items - 1) / pl.items;
   if (pl.max_splits > 64) pl.max_splits = 64;
   return pl;
 }
@@ -81,23 +88,23 @@ int launch_fwd_merge(const AttnParams& p, hipStream_t s);   // O, LSE from the p
 int launch_dq_merge(const AttnParams& p, hipStream_t s);    // dQ = scale * sum of the partials, in split order
 
 // Last round of the bf16 dK/dV pass.  One workgroup fills a CU, so n_units * n_ctiles column tiles run in rounds of
-// 256 (the CUs); when the last round would hold at most half of that, the last n_tiles column tiles of every
+// one workgroup per CU; when the last round would hold at most half of that, the last n_tiles column tiles of every
 // (batch, KV head) are divided among hs workgroups by query head (hs = 1: nothing is divided).  A share keeps
-// at least 512 query rows, and all shares together fit one round.
-constexpr int kTailRound = 256;          // workgroups of one round: the CUs of an MI355X
-constexpr int kTailMaxShares = kTailRound;   // upper bound of n_units * n_tiles * hs
+// at least 512 query rows, and all shares together fit one round (device_cus() shares at most, which is also what
+// the workspace for their partial sums is sized for).
 struct TailPlan {
   int n_tiles;
   int hs;
 };
 inline TailPlan tail_plan(int n_units, int n_ctiles, int G, int C) {
   TailPlan tp{0, 1};
+  const int round = device_cus();
   const int64_t items = (int64_t)n_units * n_ctiles;
-  const int tail = (int)(items % kTailRound);
-  if (tail == 0 || tail > kTailRound / 2) return tp;
+  const int tail = (int)(items % round);
+  if (tail == 0 || tail > round / 2) return tp;
   const int n_tiles = (tail + n_units - 1) / n_units;
   for (int hs = 4; hs >= 2; hs >>= 1) {
-    if (G % hs != 0 || (int64_t)n_units * n_tiles * hs > kTailMaxShares) continue;
+    if (G % hs != 0 || (int64_t)n_units * n_tiles * hs > round) continue;
     if ((int64_t)C * (G / hs) < 512) continue;
     tp.n_tiles = n_tiles;
     tp.hs = hs;
