@@ -363,7 +363,9 @@ int seco_profile_set_kinds(uint32_t kind_mask);     /* the same mask, but the ev
                                                        benchmark bracket only some of its steps */
 int seco_profile_read(double* total_ms_host, int64_t* launches_host);
 
-/* Workspace bytes an entry point needs for this desc (0 if none; (size_t)-1 on an invalid desc). */
+/* Workspace bytes an entry point needs for this desc (0 if none; (size_t)-1 on an invalid desc).  The launch plan,
+ * and with it this size, counts workgroups against the number of compute units of the device that is current when
+ * the library is first used (256, an MI355X's, when no device can be asked): ask on the device the call will run on. */
 size_t seco_workspace_bytes(const seco_desc* desc, int op);
 
 /*
@@ -373,7 +375,7 @@ size_t seco_workspace_bytes(const seco_desc* desc, int op);
  *   [0] workgroups that share the cache rows of one row tile in the forward / dQ pass (1: no division)
  *   [1] row tiles of the forward / dQ pass (work items before that division)
  *   [2] cache tiles per (batch, KV head), counted from the last, that the dK/dV pass shares out by query head
- *   [3] workgroups per such tile (1: none); [2] * [3] * batch * n_kv_heads never exceeds 256
+ *   [3] workgroups per such tile (1: none); [2] * [3] * batch * n_kv_heads never exceeds the device's compute units
  * Returns SECO_OK, or the status of an invalid desc; SECO_ERR_DTYPE for fp32 (its kernels have one shape).
  */
 int seco_launch_plan(const seco_desc* desc, int32_t n_col_tiles, int32_t* plan_host);
