@@ -23,7 +23,8 @@
 // Q, dO, -LSE / s and -delta of one stage of query rows stream through a three-deep ring of swizzled LDS
 // slots, laid out region by region (Q tiles, dO tiles, row statistics, P buffers; one of each per slot)
 // (A reads Q of stage i+1 while B reads Q and dO of stage i and stage i+2 is landing);
-// Q and dO are copied global -> LDS directly (no staging registers), issued two stages ahead.
+// Q and dO are copied global -> LDS directly (no staging registers), issued two stages ahead (after the first
+// MFMA chain of an iteration, so that the matrix pipe starts right behind the barrier).
 // S and dP are computed in the "row = query" orientation, so P and dS sit in the C layout
 // with lane = cache row and feed the second products as A operands; dO and Q for those
 // products come through the LDS transpose read.  P is written to LDS once (bf16, in operand
@@ -339,10 +340,17 @@ __device__ __forceinline__ void dkdv_bf16_body(const AttnParams& p, const SegTab
   for (int it = 0; it < n_iter; ++it) {
     const int slot1 = slot + 1 == kStages ? 0 : slot + 1;
     const int slot2 = slot1 + 1 == kStages ? 0 : slot1 + 1;
-    if (it + 2 < n_iter) {
-      copy_stage(nxt2, slot2);
-      copy_stat(nxt2, slot2);
-    }
+    // The copies of stage it + 2 are issued after the first MFMA chain of the iteration, not at its top: right
+    // after the barrier every wavefront has the operands of its first chain in registers, and the matrix pipe
+    // should start on them at once instead of waiting behind sixteen copy instructions and their address
+    // arithmetic (3 % on the kernel; issued later still, the copy has too little time to land before the
+    // wait at the end of the iteration).
+    auto issue_copies = [&]() {
+      if (it + 2 < n_iter) {
+        copy_stage(nxt2, slot2);
+        copy_stat(nxt2, slot2);
+      }
+    };
     // tiles of the stage in `slot` and of the next stage; whether an access goes to the Q or to the dO tile of the
     // slot is decided by the region that its per-lane offset (r_off, t_off) carries
     lds_char* t0 = smem + slot * kTileBytes;
@@ -360,6 +368,7 @@ __device__ __forceinline__ void dkdv_bf16_body(const AttnParams& p, const SegTab
         acc[i & 3] = mfma(pa0[i >> 2], x[i], acc[i & 3]);
         x[i] = lds_row8_at(t1 + r_off[i], 0);
       }
+      issue_copies();
       f32x16 s0, s1;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s0[r] = lse_s[8 * (r >> 2) + 4 * g + (r & 3)];
@@ -427,6 +436,7 @@ __device__ __forceinline__ void dkdv_bf16_body(const AttnParams& p, const SegTab
         d0 = mfma(x[t], frag[t], d0);
         x[t] = lds_row8_at(t0 + r_off[t], 32);
       }
+      issue_copies();
       // dP - delta of row block 1, with dS of row block 0; Q^T of row block 0 comes in behind
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
