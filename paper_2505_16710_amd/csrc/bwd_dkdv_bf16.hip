@@ -185,10 +185,22 @@ __device__ __forceinline__ void dkdv_bf16_body(const AttnParams& p, const SegTab
     do_lane_off[i] = dma_lane_offset(4 * (wave + NW * i), p.os[2] * 2, lane);
   }
   const uint32_t lds_wave = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + wave * 4 * kRowBytes);
-  auto copy_stage = [&](Pos x, int slot) {
+  // Global addresses of a stage's first row (Q, dO, and the row statistic this wavefront copies).  They are carried
+  // along with the stage two ahead and advanced by one stage's worth per iteration: computing them from (head, row)
+  // costs a dozen 64-bit scalar multiplies per iteration and wavefront.
+  struct Src { const __bf16* q; const __bf16* d_o; const float* stat; };
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  auto src_of = [&](Pos x) {
+    Src r;
+    r.q = qbase + x.hg * p.qs[1] + (int64_t)x.r0 * p.qs[2];
+    r.d_o = dobase + x.hg * p.os[1] + (int64_t)x.r0 * p.os[2];
+    r.stat = (wave_u == 0 ? p.nlse2 : p.delta) + stat_base + (int64_t)x.hg * p.stat_stride + x.r0;
+    return r;
+  };
+  auto copy_stage = [&](Pos x, int slot, const Src& src) {
     if (x.r0 + BQ <= row_limit(x)) {
-      const __bf16* q_src = qbase + x.hg * p.qs[1] + (int64_t)x.r0 * p.qs[2];
-      const __bf16* do_src = dobase + x.hg * p.os[1] + (int64_t)x.r0 * p.os[2];
+      const __bf16* q_src = src.q;
+      const __bf16* do_src = src.d_o;
 #pragma unroll
       for (int i = 0; i < kCopies; ++i) {
         const uint32_t dst = lds_wave + slot * kTileBytes + i * (4 * NW * kRowBytes);
@@ -210,12 +222,11 @@ __device__ __forceinline__ void dkdv_bf16_body(const AttnParams& p, const SegTab
   // asynchronous 64-lane copy each (wavefronts 0 and 1), straight into the stage's slot.  The last, ragged stage
   // of a head goes through registers instead: rows past the chunk get -LSE = -inf so that their probabilities vanish.
   static_assert(BQ == 64, "one 64-lane copy per row statistic");
-  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const uint32_t lds_stat = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + kStatRegion + (wave & 1) * BQ * 4);
-  auto copy_stat = [&](Pos x, int slot) {
+  auto copy_stat = [&](Pos x, int slot, const Src& src) {
     if (x.r0 + BQ <= row_limit(x)) {
       if (wave_u < 2) {
-        const uint64_t a = (uint64_t)(uintptr_t)((wave_u == 0 ? p.nlse2 : p.delta) + stat_base + (int64_t)x.hg * p.stat_stride + x.r0);
+        const uint64_t a = (uint64_t)(uintptr_t)src.stat;
         // (wavefront-uniform by construction; the halves go through readfirstlane so that the compiler keeps them
         // in scalar registers; each half is widened from an unsigned 32-bit value)
         const uint64_t src = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(a >> 32)) << 32) |
@@ -298,11 +309,14 @@ __device__ __forceinline__ void dkdv_bf16_body(const AttnParams& p, const SegTab
 
   Pos cur{head0, first_r0, first_ri};
   Pos nxt = advance(cur);
-  copy_stage(cur, 0);
-  copy_stat(cur, 0);
-  if (n_iter > 1) {
-    copy_stage(nxt, 1);
-    copy_stat(nxt, 1);
+  {
+    const Src s0 = src_of(cur), s1 = src_of(nxt);
+    copy_stage(cur, 0, s0);
+    copy_stat(cur, 0, s0);
+    if (n_iter > 1) {
+      copy_stage(nxt, 1, s1);
+      copy_stat(nxt, 1, s1);
+    }
   }
 #pragma unroll
   for (int t = 0; t < 8; ++t) settle(frag[t]);
@@ -314,6 +328,13 @@ __device__ __forceinline__ void dkdv_bf16_body(const AttnParams& p, const SegTab
   }
   __syncthreads();
   Pos nxt2 = advance(nxt);
+  Src src2 = src_of(nxt2);
+  // (all rows, no runs) one stage on: BQ rows further, or, behind a head's last stage, back to the first stage's row
+  // of the next head
+  const int64_t q_step = (int64_t)BQ * p.qs[2], do_step = (int64_t)BQ * p.os[2];
+  const int64_t back_rows = (int64_t)(n_rt - 1) * BQ;
+  const int64_t q_wrap = p.qs[1] - back_rows * p.qs[2], do_wrap = p.os[1] - back_rows * p.os[2];
+  const int64_t stat_wrap = p.stat_stride - back_rows;
 
   // One operand buffer x[8] rotates through the four MFMA chains of an iteration: while a chain consumes x[t], the
   // operand of the next chain is requested into the same register ("comes in behind").  The last chain of an
@@ -347,8 +368,8 @@ __device__ __forceinline__ void dkdv_bf16_body(const AttnParams& p, const SegTab
     // wait at the end of the iteration).
     auto issue_copies = [&]() {
       if (it + 2 < n_iter) {
-        copy_stage(nxt2, slot2);
-        copy_stat(nxt2, slot2);
+        copy_stage(nxt2, slot2, src2);
+        copy_stat(nxt2, slot2, src2);
       }
     };
     // tiles of the stage in `slot` and of the next stage; whether an access goes to the Q or to the dO tile of the
@@ -466,7 +487,18 @@ __device__ __forceinline__ void dkdv_bf16_body(const AttnParams& p, const SegTab
     __syncthreads();
     cur = nxt;
     nxt = nxt2;
-    nxt2 = advance(nxt2);
+    {
+      const Pos adv = advance(nxt2);
+      if constexpr (ROWS) {
+        src2 = src_of(adv);
+      } else {
+        const bool wrap = adv.hg != nxt2.hg;
+        src2.q += wrap ? q_wrap : q_step;
+        src2.d_o += wrap ? do_wrap : do_step;
+        src2.stat += wrap ? stat_wrap : (int64_t)BQ;
+      }
+      nxt2 = adv;
+    }
     slot = slot1;
   }
 
